@@ -1,0 +1,223 @@
+/*
+ * hawq.h -- C interface of the MI355X (gfx950) integer-only inference kernels for
+ * HAWQ-V3 ("Dyadic Neural Network Quantization").
+ *
+ * The library implements the inference-time arithmetic of the paper and nothing else:
+ * low-bit integer convolution / matrix multiply with INT32 accumulation, INT32 bias add,
+ * requantisation by a dyadic number b / 2^c (one integer multiply, one rounding right
+ * shift; no floating point, no integer division), ReLU / clamp, the dyadic residual
+ * addition and integer pooling.
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ * -------------------------------------------------------------------
+ *  - Every tensor / array pointer is DEVICE memory owned by the caller.  The library
+ *    allocates nothing on these calls and keeps no reference after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work; they never synchronise.
+ *  - Layouts: activations NHWC, weights KRSC (K output channels, R x S window,
+ *    C input channels); dense, innermost axis contiguous.
+ *  - HAWQ_U4 / HAWQ_S4 tensors hold two elements per byte along the innermost
+ *    (channel) axis: element 2i in bits 0..3, element 2i+1 in bits 4..7 (the same
+ *    bytes as eight nibbles in a little-endian 32-bit word); S4 is two's complement.
+ *    A 4-bit tensor's channel count must be even.
+ *  - Dyadic rescaling of an integer t by (b, c):
+ *        rq(t, b, c) = floor(t * b / 2^c + 1/2)         (ties toward +infinity)
+ *    evaluated exactly in 64-bit integers.  Preconditions the library cannot check
+ *    (the arrays live in device memory): 0 <= b < 2^31 and 1 <= c <= 62.
+ *  - Accumulators must stay inside int32.  A static bound is checked from the shape and
+ *    the operand ranges (HAWQ_ERR_OVERFLOW); within that bound the caller's bias must
+ *    keep |acc + bias| < 2^31.
+ *  - Errors are return codes; argument validation happens on the host before any launch
+ *    (so it can be exercised without a GPU).  On error nothing has been enqueued.
+ */
+#ifndef HAWQ_H
+#define HAWQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HAWQ_OK = 0,
+    HAWQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    HAWQ_ERR_SHAPE = 2,       /* non-positive size, window larger than padded image, odd 4-bit channel count */
+    HAWQ_ERR_DTYPE = 3,       /* dtype not allowed in this position / operand widths differ */
+    HAWQ_ERR_RANGE = 4,       /* clamp interval empty or outside the output type */
+    HAWQ_ERR_OVERFLOW = 5,    /* static bound says the INT32 accumulator could overflow */
+    HAWQ_ERR_UNSUPPORTED = 6, /* valid request this build cannot serve (e.g. tensor >= 2 GiB) */
+    HAWQ_ERR_DEVICE = 7,      /* a HIP call failed */
+    HAWQ_ERR_WORKSPACE = 8    /* caller's workspace is too small */
+} hawq_status;
+
+typedef enum { HAWQ_U8 = 0, HAWQ_S8 = 1, HAWQ_U4 = 2, HAWQ_S4 = 3, HAWQ_S32 = 4 } hawq_dtype;
+
+/* One quantised convolution layer (all fields int32 so the struct has no padding). */
+typedef struct {
+    int32_t N, H, W, C;            /* input  [N,H,W,C]                                        */
+    int32_t K, R, S;               /* weights [K,R,S,C]                                       */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;          /* zero padding; output P = (H + 2 pad_h - R)/stride_h + 1 */
+    int32_t x_dtype;               /* HAWQ_U8 | HAWQ_S8 | HAWQ_U4                             */
+    int32_t w_dtype;               /* HAWQ_S8 with 8-bit x, HAWQ_S4 with HAWQ_U4 x            */
+    int32_t y_dtype;               /* HAWQ_U8 | HAWQ_S8 | HAWQ_U4 | HAWQ_S4 | HAWQ_S32        */
+    int32_t res_dtype;             /* HAWQ_U8 | HAWQ_S8 | HAWQ_U4 | HAWQ_S4 (ignored if residual == NULL) */
+    int32_t relu;                  /* 1: y = max(y, 0) before the clamp                       */
+    int32_t y_lo, y_hi;            /* clamp, e.g. [0,127], [0,15], [-128,127]                 */
+    int32_t x_hi;                  /* largest |activation| the caller guarantees; 0 = the type's maximum.
+                                      Used by the overflow bound; HAWQ_U8 data with x_hi <= 127 (the
+                                      post-ReLU 8-bit range of the workloads) runs on the signed INT8
+                                      matrix cores, larger values take a slower exact kernel.   */
+} hawq_conv_desc;
+
+/*
+ * Quantised convolution layer -- Section 3.1 (integer convolution accumulated in INT32, then
+ * dyadic requantisation), Appendix D (INT32 bias of the folded batch norm added to the
+ * accumulator), Section 3.3 (optional residual: each branch rescaled by its own dyadic
+ * number, rounded separately, then added), Figure 1 (ReLU / clamp to the next layer's range).
+ *
+ *   acc[n,p,q,k] = sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c] * w[k,r,s,c]
+ *   t = acc + bias[k]
+ *   y = rq(t, b[k], c[k])  (+ rq(residual[n,p,q,k], res_b[k], res_c[k]) if residual != NULL)
+ *   y = clamp(relu ? max(y,0) : y, y_lo, y_hi)          stored as y_dtype, [N,P,Q,K]
+ *
+ * bias, b, res_b: int32 [K]; c, res_c: uint8 [K].  b == c == NULL is allowed only with
+ * y_dtype == HAWQ_S32 and no residual: y = t (raw accumulator + bias).
+ * The INT32 accumulator never goes to memory; x and y must not overlap.
+ */
+hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias,
+                            const int32_t *b, const uint8_t *c, const void *residual, const int32_t *res_b,
+                            const uint8_t *res_c, void *y, void *stream);
+
+/*
+ * Quantised fully connected layer / GEMM -- the matrix-multiply form of Section 3.1:
+ *   y[m,n] = epilogue( sum_k x[m,k] * w[n,k] + bias[n] ),   x [M,Kdim], w [N,Kdim], y [M,N]
+ * with the epilogue of hawq_conv2d_int (no residual).  b == c == NULL with y_dt == HAWQ_S32
+ * returns the raw INT32 logits of the last layer.
+ */
+hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int32_t w_dt, int32_t y_dt, const void *x,
+                          const void *w, const int32_t *bias, const int32_t *b, const uint8_t *c, int32_t relu,
+                          int32_t y_lo, int32_t y_hi, void *y, void *stream);
+
+/*
+ * Stand-alone residual addition -- Section 3.3:
+ *   y[p,k] = clamp( relu?( rq(m[p,k], m_b[k], m_c[k]) + rq(r[p,k], r_b[k], r_c[k]) ), y_lo, y_hi )
+ * m: main branch, [n_pixels,K] of HAWQ_S32 (the INT32 accumulator) | S8 | U8 | U4 | S4;
+ * r: shortcut, S8 | U8 | U4 | S4 | S32;  y: U8 | S8 | U4 | S4 | S32.  y may alias m or r when the types match.
+ */
+hawq_status hawq_residual_add_dyadic(int64_t n_pixels, int32_t K, int32_t m_dt, int32_t r_dt, int32_t y_dt,
+                                     const void *m, const int32_t *m_b, const uint8_t *m_c, const void *r,
+                                     const int32_t *r_b, const uint8_t *r_c, int32_t relu, int32_t y_lo,
+                                     int32_t y_hi, void *y, void *stream);
+
+/*
+ * Integer global average pool -- Appendix E (pooling carried in INT32) with the paper's rule
+ * that no integer division is used: 1/(H*W) is folded into the dyadic multiplier.
+ *   s[n,k] = sum_{h,w} x[n,h,w,k]  (INT32);   y[n,k] = clamp(rq(s, b[k], c[k]), y_lo, y_hi)
+ * x [N,H,W,C] U8 | S8 | U4 | S4;  y [N,C] U8 | S8 | U4 | S4 | S32.
+ */
+hawq_status hawq_avgpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t x_dt, int32_t y_dt, const void *x,
+                             const int32_t *b, const uint8_t *c, int32_t y_lo, int32_t y_hi, void *y, void *stream);
+
+/*
+ * Max pool 3x3, stride 2, padding 1 on a quantised tensor (the pool that follows the first
+ * convolution of a ResNet; an integer maximum over the in-image taps, then clamp).
+ * x [N,H,W,C] U8 | S8 | U4 | S4;  y [N,P,Q,C] with P = (H-1)/2 + 1, of type U8 | S8 | U4 | S4.
+ */
+hawq_status hawq_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t x_dt, int32_t y_dt, const void *x,
+                             int32_t y_lo, int32_t y_hi, void *y, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Whole-network forward (integer-only ResNet18 / ResNet50, Figure 2 and Section 3.3).
+ *
+ * Canonical layer order: conv1, then for every stage and block c1, c2, [c3], [ds], finally fc.
+ * ResNet50 puts the stride-2 on c1 of a stage's first block.  Storage rule for mixed precision
+ * (Section 3.4: one bit width per layer for weights and activations): a tensor is stored at the
+ * width of the convolution that reads it (8-bit: 0..127, 4-bit: 0..15, packed); ds shares c1's
+ * width and reads the same stored block input; a ds output is signed 8-bit; conv1, the pooled
+ * vector and fc are 8-bit (Appendix H).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct hawq_net hawq_net;
+
+/* Parameters of one layer, HOST pointers (copied to the device by hawq_net_create). */
+typedef struct {
+    const void *w;          /* [K,R,S,C] int8, or packed nibbles when bits == 4             */
+    const int32_t *bias;    /* [K]                                                          */
+    const int32_t *b;       /* [K]  (ignored for fc: raw INT32 logits)                      */
+    const uint8_t *c;       /* [K]                                                          */
+    const int32_t *res_b;   /* [K] for the last conv of a block (it adds the shortcut), else NULL */
+    const uint8_t *res_c;   /* [K] likewise                                                 */
+    int32_t bits;           /* 4 or 8; conv1 and fc must be 8; ds must equal its block's c1 */
+    int32_t reserved;
+} hawq_layer_params;
+
+/* Shape of layer `index` of the canonical order, for a square image of side image_hw. */
+typedef struct {
+    char name[24];          /* "conv1", "layer2.0.c1", "layer2.0.ds", "fc", ...             */
+    int32_t C, K, R, S, stride, pad;
+    int32_t H, W;           /* input size                                                   */
+    int32_t P, Q;           /* output size                                                  */
+    int32_t has_residual;   /* 1: res_b / res_c are required                                */
+    int32_t is_ds;          /* 1: transition (shortcut) convolution                         */
+} hawq_layer_info;
+
+/* Host-only topology queries (no GPU needed).  arch = 18 or 50. */
+int32_t hawq_net_num_layers(int32_t arch);
+hawq_status hawq_net_layer_info(int32_t arch, int32_t image_hw, int32_t num_classes, int32_t index,
+                                hawq_layer_info *out);
+
+/*
+ * Build a network: validates the parameters (here b and c are host data, so 0 <= b < 2^31 and
+ * 1 <= c <= 62 ARE checked -> HAWQ_ERR_RANGE), allocates one device arena, uploads weights
+ * (conv1 re-tiled for its kernel) and parameters.  pool_b / pool_c: [C_last] host arrays of
+ * the average pool's dyadic multiplier.  keep_activations != 0 gives every layer's output its own
+ * workspace slot (for layer-by-layer comparison) instead of reusing buffers.
+ * Synchronous; call outside any timed region.  Free with hawq_net_destroy.
+ */
+hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes, const hawq_layer_params *layers,
+                            int32_t n_layers, const int32_t *pool_b, const uint8_t *pool_c,
+                            int32_t keep_activations, hawq_net **out);
+void hawq_net_destroy(hawq_net *net);
+
+/* Bytes of caller-provided device workspace hawq_forward_resnet needs for a batch of N. */
+size_t hawq_net_workspace_bytes(const hawq_net *net, int32_t N);
+
+/* Number of launches of one forward: conv1, max pool, the convolutions, average pool, fc. */
+int32_t hawq_net_num_steps(const hawq_net *net);
+
+/*
+ * Where step `step` leaves its output inside the workspace for batch N, and what it is
+ * (valid until a later step reuses the slot; permanent with keep_activations).
+ * name: at least 24 bytes.  dtype: hawq_dtype of the stored tensor.
+ */
+hawq_status hawq_net_step_output(const hawq_net *net, int32_t N, int32_t step, char *name, size_t *offset,
+                                 size_t *bytes, int32_t *dtype, int32_t *dims4 /* N,P,Q,K */);
+
+/*
+ * Integer-only forward: x uint8 [N,image_hw,image_hw,3] (values 0..255) -> logits int32
+ * [N,num_classes].  x, logits and workspace are device memory; workspace must hold
+ * hawq_net_workspace_bytes(net, N) bytes, 256-byte aligned.  Enqueues every layer on `stream`.
+ */
+hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+/*
+ * Same forward with a pair of HIP events around every step, recorded on `stream`; on return the
+ * stream has been synchronised and step_ms[i] (host array, hawq_net_num_steps entries) holds the
+ * device time of step i in milliseconds.  For measurement only.
+ */
+hawq_status hawq_forward_resnet_timed(const hawq_net *net, const void *x, int32_t N, int32_t *logits,
+                                      void *workspace, size_t workspace_bytes, void *stream, float *step_ms);
+
+/* Static description of a step for reporting: multiply-accumulates and minimum HBM bytes
+ * (input once + weights + parameters + output once + shortcut once) at batch N. */
+hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, double *macs, double *bytes);
+
+const char *hawq_status_string(hawq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAWQ_H */

@@ -1,0 +1,195 @@
+// C interface: host-side argument validation and dispatch.  Nothing here touches device memory.
+#include "common.h"
+
+using namespace hawq;
+
+namespace {
+
+bool dtype_range(int dt, int64_t &lo, int64_t &hi) {
+    switch (dt) {
+    case HAWQ_U8: lo = 0; hi = 255; return true;
+    case HAWQ_S8: lo = -128; hi = 127; return true;
+    case HAWQ_U4: lo = 0; hi = 15; return true;
+    case HAWQ_S4: lo = -8; hi = 7; return true;
+    case HAWQ_S32: lo = INT32_MIN; hi = INT32_MAX; return true;
+    default: return false;
+    }
+}
+
+bool low_bit(int dt) { return dt == HAWQ_U8 || dt == HAWQ_S8 || dt == HAWQ_U4 || dt == HAWQ_S4; }
+
+hawq_status check_clamp(int y_dt, int32_t y_lo, int32_t y_hi) {
+    int64_t lo, hi;
+    if (!dtype_range(y_dt, lo, hi)) return HAWQ_ERR_DTYPE;
+    if (y_lo > y_hi || y_lo < lo || y_hi > hi) return HAWQ_ERR_RANGE;
+    return HAWQ_OK;
+}
+
+const int64_t kMaxBytes = (int64_t)1 << 31;
+
+}  // namespace
+
+namespace hawq {
+
+// Validate a convolution request and fill the kernel argument block.  x_hi_out receives the
+// effective activation bound.  Shared by hawq_conv2d_int, hawq_gemm_int and the network plan.
+hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                           const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,
+                           bool check_pointers, ConvArgs &a, int &x_hi_out) {
+    if (!d) return HAWQ_ERR_NULL;
+    if (check_pointers) {
+        if (!x || !w || !bias || !y) return HAWQ_ERR_NULL;
+        if ((b == nullptr) != (c == nullptr)) return HAWQ_ERR_NULL;
+        if (residual && (!res_b || !res_c)) return HAWQ_ERR_NULL;
+    }
+    if (d->N < 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->stride_h <= 0 ||
+        d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return HAWQ_ERR_SHAPE;
+    if ((int64_t)d->H + 2 * (int64_t)d->pad_h < d->R || (int64_t)d->W + 2 * (int64_t)d->pad_w < d->S) return HAWQ_ERR_SHAPE;
+    // operand types: weights and activations of a layer share one bit width (Section 3.4)
+    if (d->x_dtype == HAWQ_U8 || d->x_dtype == HAWQ_S8) {
+        if (d->w_dtype != HAWQ_S8) return HAWQ_ERR_DTYPE;
+    } else if (d->x_dtype == HAWQ_U4) {
+        if (d->w_dtype != HAWQ_S4) return HAWQ_ERR_DTYPE;
+    } else {
+        return HAWQ_ERR_DTYPE;
+    }
+    int64_t tlo, thi;
+    if (!dtype_range(d->y_dtype, tlo, thi)) return HAWQ_ERR_DTYPE;
+    if (residual && !low_bit(d->res_dtype)) return HAWQ_ERR_DTYPE;
+    const bool raw = (b == nullptr) && check_pointers;
+    if (raw && (d->y_dtype != HAWQ_S32 || residual)) return HAWQ_ERR_DTYPE;
+    if (is4(d->x_dtype) && (d->C & 1)) return HAWQ_ERR_SHAPE;
+    if (is4(d->y_dtype) && (d->K & 1)) return HAWQ_ERR_SHAPE;
+    if (residual && is4(d->res_dtype) && (d->K & 1)) return HAWQ_ERR_SHAPE;
+    if (!raw) {
+        hawq_status st = check_clamp(d->y_dtype, d->y_lo, d->y_hi);
+        if (st != HAWQ_OK) return st;
+    }
+    // activation bound and the static INT32 overflow check
+    const int x_type_hi = d->x_dtype == HAWQ_U8 ? 255 : (d->x_dtype == HAWQ_S8 ? 128 : 15);
+    if (d->x_hi < 0 || d->x_hi > x_type_hi) return HAWQ_ERR_RANGE;
+    const int x_hi = d->x_hi == 0 ? x_type_hi : d->x_hi;
+    const int64_t w_hi = d->w_dtype == HAWQ_S8 ? 128 : 8;
+    const int64_t kdim = (int64_t)d->R * d->S * d->C;
+    if (kdim * x_hi * w_hi >= ((int64_t)1 << 31) - ((int64_t)1 << 24)) return HAWQ_ERR_OVERFLOW;
+
+    const int64_t P = ((int64_t)d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    const int64_t Q = ((int64_t)d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    const int64_t M = (int64_t)d->N * P * Q;
+    if (M >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    if (tensor_bytes((int64_t)d->N * d->H * d->W * d->C, d->x_dtype) >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    if (tensor_bytes(M * d->K, d->y_dtype) >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    if (tensor_bytes(kdim * d->K, d->w_dtype) >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+
+    a.x = (const uint8_t *)x; a.w = (const uint8_t *)w; a.bias = bias; a.b = b; a.c = c;
+    a.res = (const uint8_t *)residual; a.res_b = residual ? res_b : nullptr; a.res_c = residual ? res_c : nullptr;
+    a.y = (uint8_t *)y;
+    a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
+    a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
+    a.P = (int32_t)P; a.Q = (int32_t)Q; a.M = (int32_t)M;
+    a.x_dt = d->x_dtype; a.w_dt = d->w_dtype; a.y_dt = d->y_dtype; a.res_dt = d->res_dtype;
+    a.lo = (d->relu && d->y_lo < 0) ? 0 : d->y_lo;
+    a.hi = d->y_hi;
+    if (raw) { a.lo = INT32_MIN; a.hi = INT32_MAX; }
+    // ReLU with a clamp interval entirely below zero: max(y,0) then min(.,hi) gives hi
+    if (d->relu && d->y_hi < 0) { a.lo = d->y_hi; a.hi = d->y_hi; }
+    x_hi_out = x_hi;
+    return HAWQ_OK;
+}
+
+hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    if (conv_mfma_eligible(a, x_hi)) return launch_conv_mfma(a, s);
+    return launch_conv_direct(a, s);
+}
+
+}  // namespace hawq
+
+extern "C" {
+
+hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                            const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,
+                            void *stream) {
+    ConvArgs a;
+    int x_hi;
+    hawq_status st = make_conv_args(desc, x, w, bias, b, c, residual, res_b, res_c, y, true, a, x_hi);
+    if (st != HAWQ_OK) return st;
+    return dispatch_conv(a, x_hi, (hipStream_t)stream);
+}
+
+hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int32_t w_dt, int32_t y_dt, const void *x,
+                          const void *w, const int32_t *bias, const int32_t *b, const uint8_t *c, int32_t relu, int32_t y_lo,
+                          int32_t y_hi, void *y, void *stream) {
+    if (M < 0 || N <= 0 || Kdim <= 0) return HAWQ_ERR_SHAPE;
+    hawq_conv_desc d = {};
+    d.N = 1; d.H = 1; d.W = M > 0 ? M : 1; d.C = Kdim; d.K = N; d.R = 1; d.S = 1;
+    d.stride_h = d.stride_w = 1; d.pad_h = d.pad_w = 0;
+    d.x_dtype = x_dt; d.w_dtype = w_dt; d.y_dtype = y_dt; d.res_dtype = HAWQ_U8;
+    d.relu = relu; d.y_lo = y_lo; d.y_hi = y_hi;
+    d.x_hi = (x_dt == HAWQ_U8) ? 127 : 0;   // unsigned 8-bit activations are the post-ReLU range 0..127
+    ConvArgs a;
+    int x_hi;
+    hawq_status st = make_conv_args(&d, x, w, bias, b, c, nullptr, nullptr, nullptr, y, true, a, x_hi);
+    if (st != HAWQ_OK) return st;
+    if (M == 0) return HAWQ_OK;
+    return dispatch_conv(a, x_hi, (hipStream_t)stream);
+}
+
+hawq_status hawq_residual_add_dyadic(int64_t n_pixels, int32_t K, int32_t m_dt, int32_t r_dt, int32_t y_dt, const void *m,
+                                     const int32_t *m_b, const uint8_t *m_c, const void *r, const int32_t *r_b,
+                                     const uint8_t *r_c, int32_t relu, int32_t y_lo, int32_t y_hi, void *y, void *stream) {
+    if (!m || !m_b || !m_c || !r || !r_b || !r_c || !y) return HAWQ_ERR_NULL;
+    if (n_pixels < 0 || K <= 0) return HAWQ_ERR_SHAPE;
+    int64_t lo, hi;
+    if (!dtype_range(m_dt, lo, hi) || !dtype_range(r_dt, lo, hi)) return HAWQ_ERR_DTYPE;
+    hawq_status st = check_clamp(y_dt, y_lo, y_hi);
+    if (st != HAWQ_OK) return st;
+    if ((is4(m_dt) || is4(r_dt) || is4(y_dt)) && (K & 1)) return HAWQ_ERR_SHAPE;
+    if (n_pixels * (int64_t)K >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    int32_t lo2 = (relu && y_lo < 0) ? 0 : y_lo, hi2 = y_hi;
+    if (relu && y_hi < 0) lo2 = hi2 = y_hi;
+    return launch_residual_add(n_pixels, K, m_dt, r_dt, y_dt, m, m_b, m_c, r, r_b, r_c, lo2, hi2, y, (hipStream_t)stream);
+}
+
+hawq_status hawq_avgpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t x_dt, int32_t y_dt, const void *x,
+                             const int32_t *b, const uint8_t *c, int32_t y_lo, int32_t y_hi, void *y, void *stream) {
+    if (!x || !b || !c || !y) return HAWQ_ERR_NULL;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0) return HAWQ_ERR_SHAPE;
+    if (!low_bit(x_dt)) return HAWQ_ERR_DTYPE;
+    hawq_status st = check_clamp(y_dt, y_lo, y_hi);
+    if (st != HAWQ_OK) return st;
+    if ((is4(x_dt) || is4(y_dt)) && (C & 1)) return HAWQ_ERR_SHAPE;
+    if ((int64_t)H * W * 255 >= kMaxBytes) return HAWQ_ERR_OVERFLOW;
+    if ((int64_t)N * H * W * C >= kMaxBytes || N > 65535) return HAWQ_ERR_UNSUPPORTED;
+    return launch_avgpool(N, H * W, C, x_dt, y_dt, x, b, c, y_lo, y_hi, y, (hipStream_t)stream);
+}
+
+hawq_status hawq_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t x_dt, int32_t y_dt, const void *x,
+                             int32_t y_lo, int32_t y_hi, void *y, void *stream) {
+    if (!x || !y) return HAWQ_ERR_NULL;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0) return HAWQ_ERR_SHAPE;
+    if (!low_bit(x_dt) || !low_bit(y_dt)) return HAWQ_ERR_DTYPE;
+    hawq_status st = check_clamp(y_dt, y_lo, y_hi);
+    if (st != HAWQ_OK) return st;
+    if ((is4(x_dt) || is4(y_dt)) && (C & 1)) return HAWQ_ERR_SHAPE;
+    if ((int64_t)N * H * W * C >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    return launch_maxpool(N, H, W, C, x_dt, y_dt, x, y_lo, y_hi, y, (hipStream_t)stream);
+}
+
+const char *hawq_status_string(hawq_status s) {
+    switch (s) {
+    case HAWQ_OK: return "ok";
+    case HAWQ_ERR_NULL: return "required pointer is NULL";
+    case HAWQ_ERR_SHAPE: return "invalid shape";
+    case HAWQ_ERR_DTYPE: return "invalid dtype combination";
+    case HAWQ_ERR_RANGE: return "value outside the allowed range";
+    case HAWQ_ERR_OVERFLOW: return "INT32 accumulator could overflow";
+    case HAWQ_ERR_UNSUPPORTED: return "unsupported request";
+    case HAWQ_ERR_DEVICE: return "HIP call failed";
+    case HAWQ_ERR_WORKSPACE: return "workspace too small";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

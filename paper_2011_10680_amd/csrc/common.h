@@ -1,0 +1,102 @@
+// Internal declarations shared by the kernels and the C interface (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "../../include/hawq.h"
+
+namespace hawq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Everything a convolution kernel needs; passed by value as the kernel argument.
+struct ConvArgs {
+    const uint8_t *x;        // activations (bytes; 4-bit: packed)
+    const uint8_t *w;        // weights [K][R*S*C] (bytes; 4-bit: packed)
+    const int32_t *bias;     // [K]
+    const int32_t *b;        // [K] or nullptr (raw output)
+    const uint8_t *c;        // [K]
+    const uint8_t *res;      // shortcut tensor [M][K] or nullptr
+    const int32_t *res_b;
+    const uint8_t *res_c;
+    uint8_t *y;              // output [M][K]
+    int32_t N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, P, Q;
+    int32_t M;               // N*P*Q output pixels
+    int32_t x_dt, w_dt, y_dt, res_dt;
+    int32_t lo, hi;          // clamp with ReLU already folded in (lo = max(lo,0))
+};
+
+__host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }
+// bytes of `n` elements of a dense tensor of type dt (n even for 4-bit types)
+__host__ __device__ inline int64_t tensor_bytes(int64_t n, int dt) {
+    return dt == HAWQ_S32 ? n * 4 : (is4(dt) ? n / 2 : n);
+}
+
+// ---- dyadic requantisation: rq(t,b,c) = floor(t*b/2^c + 1/2), exact in 64-bit ----
+__device__ __forceinline__ int64_t rq64(int32_t t, int32_t b, int32_t c) {
+    return ((int64_t)t * (int64_t)b + ((int64_t)1 << (c - 1))) >> c;
+}
+
+__device__ __forceinline__ int32_t clamp64(int64_t v, int32_t lo, int32_t hi) {
+    v = v < (int64_t)lo ? (int64_t)lo : v;
+    v = v > (int64_t)hi ? (int64_t)hi : v;
+    return (int32_t)v;
+}
+
+// Read logical element i of a dense tensor (slow path / element-wise kernels).
+__device__ __forceinline__ int32_t load_elem(const void *p, int dt, int64_t i) {
+    switch (dt) {
+    case HAWQ_U8: return ((const uint8_t *)p)[i];
+    case HAWQ_S8: return ((const int8_t *)p)[i];
+    case HAWQ_S32: return ((const int32_t *)p)[i];
+    case HAWQ_U4: {
+        uint32_t v = ((const uint8_t *)p)[i >> 1];
+        return (int32_t)((i & 1) ? (v >> 4) : (v & 0xF));
+    }
+    default: {
+        uint32_t v = ((const uint8_t *)p)[i >> 1];
+        int32_t n = (int32_t)((i & 1) ? (v >> 4) : (v & 0xF));
+        return n >= 8 ? n - 16 : n;
+    }
+    }
+}
+
+// Compile-time loop: indices into register arrays stay constants even when the body is large.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// XCD-aware remap of a linear workgroup id.  Workgroups are dealt round-robin to the 8 XCDs
+// (each with its own L2); this gives every XCD one contiguous range of logical tile ids so
+// neighbouring tiles (shared input halo, shared activation rows) meet in the same L2.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks) {
+    const uint32_t per = nblocks >> 3, rem = nblocks & 7u;
+    const uint32_t xcd = bid & 7u, idx = bid >> 3;
+    return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+// ---- launchers (host) ----
+hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s);     // requires conv_mfma_eligible
+bool conv_mfma_eligible(const ConvArgs &a, int x_hi);
+hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
+// conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
+// bias corrected for the -128 input offset by the host (see net.cpp)
+hawq_status launch_conv_stem(const ConvArgs &a, hipStream_t s);
+hawq_status launch_residual_add(int64_t n_pixels, int K, int m_dt, int r_dt, int y_dt, const void *m,
+                                const int32_t *m_b, const uint8_t *m_c, const void *r, const int32_t *r_b,
+                                const uint8_t *r_c, int lo, int hi, void *y, hipStream_t s);
+hawq_status launch_avgpool(int N, int HW, int C, int x_dt, int y_dt, const void *x, const int32_t *b,
+                           const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
+hawq_status launch_maxpool(int N, int H, int W, int C, int x_dt, int y_dt, const void *x, int lo, int hi, void *y,
+                           hipStream_t s);
+
+inline hawq_status check_launch() { return hipGetLastError() == hipSuccess ? HAWQ_OK : HAWQ_ERR_DEVICE; }
+
+}  // namespace hawq

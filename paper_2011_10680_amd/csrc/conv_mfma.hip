@@ -1,0 +1,254 @@
+// Implicit-GEMM quantised convolution on the gfx950 INT8 matrix cores.
+//
+// GEMM view (Section 3.1's integer convolution): D[k][m] = sum_kg Wt[k][kg] * X[m][kg] with
+// m = (n,p,q) an output pixel, k an output channel and kg = (r,s,c).  With NHWC activations and
+// KRSC weights both operands are contiguous along kg inside one filter tap, so a K-step is
+// "one tap, 64 input channels": 64 bytes per row for INT8, 32 bytes for packed INT4.
+//
+// Weights are the MFMA "row" operand and pixels the "column" operand, and the rows of a wave's
+// tile are assigned to channels through a fixed permutation such that every lane ends up
+// holding 16 (or 32) *consecutive* output channels of one pixel: the epilogue then requantises
+// in registers and writes 16-byte runs straight into the NHWC output.  INT32 never leaves the
+// register file.
+//
+// INT4 operands stay packed in HBM; the loader splits each 16-byte chunk into low and high
+// nibbles (weights sign-extended) and writes two INT8 chunks to LDS.  Both operands use the
+// same nibble de-interleave, i.e. the same permutation of kg, which leaves the dot product
+// unchanged.
+#include "common.h"
+#include "epilogue.h"
+
+namespace hawq {
+
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
+
+template <int BC, int BP, int WC, int WP, bool INT4>
+__global__ void __launch_bounds__(WC *WP * 64)
+conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
+    constexpr int T = WC * WP * 64;
+    constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
+    constexpr int BKB = INT4 ? 32 : 64;         // bytes of one K-step in memory
+    constexpr int NA = (BC * CPR + T - 1) / T;  // chunks per thread, weight tile
+    constexpr int NB = (BP * CPR + T - 1) / T;  // chunks per thread, pixel tile
+    constexpr int TC = BC / WC / 32;            // 32x32 MFMA tiles per wave along channels
+    constexpr int TP = BP / WP / 32;            //                        ... along pixels
+    static_assert(BC % (WC * 32) == 0 && BP % (WP * 32) == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][(BC + BP) * 64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wp = wave / WC;
+
+    const uint32_t L = xcd_remap(blockIdx.x, nblocks);
+    const int m0 = (int)(L / n_ctiles) * BP;
+    const int k0 = (int)(L % n_ctiles) * BC;
+
+    const int Cb = INT4 ? a.C / 2 : a.C;          // bytes per pixel
+    const int cchunks = a.C / 64;                 // K-steps per tap
+    const int steps = a.R * a.S * cchunks;
+    const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
+
+    // ---- per-thread load bookkeeping ----
+    int a_row[NA], a_ch[NA];
+    const uint8_t *a_ptr[NA];
+    bool a_ok[NA];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int i = tid + j * T;
+        a_row[j] = i / CPR;
+        a_ch[j] = i % CPR;
+        const int k = k0 + a_row[j];
+        a_ok[j] = (i < BC * CPR) && (k < a.K);
+        a_ptr[j] = a.w + (int64_t)(a_ok[j] ? k : 0) * wrow_bytes + a_ch[j] * 16;
+    }
+    int b_row[NB], b_ch[NB], b_ih0[NB], b_iw0[NB];
+    const uint8_t *b_ptr[NB];
+    bool b_ok[NB];
+    const int PQ = a.P * a.Q;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int i = tid + j * T;
+        b_row[j] = i / CPR;
+        b_ch[j] = i % CPR;
+        const int m = m0 + b_row[j];
+        b_ok[j] = (i < BP * CPR) && (m < a.M);
+        const int mm = b_ok[j] ? m : 0;
+        const int n = mm / PQ, pq = mm - n * PQ;
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        b_ih0[j] = p * a.stride_h - a.pad_h;
+        b_iw0[j] = q * a.stride_w - a.pad_w;
+        b_ptr[j] = a.x + (int64_t)n * a.H * a.W * Cb + b_ch[j] * 16;
+    }
+
+    v4i ra[NA], rb[NB];
+    int r = 0, s = 0, cc = 0;  // tap and channel chunk of the K-step being *loaded*
+
+    auto gload = [&](int step) {
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            v4i v = {0, 0, 0, 0};
+            if (a_ok[j]) v = *(const v4i *)(a_ptr[j] + (int64_t)step * BKB);
+            ra[j] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int ih = b_ih0[j] + r, iw = b_iw0[j] + s;
+            v4i v = {0, 0, 0, 0};
+            if (b_ok[j] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+                v = *(const v4i *)(b_ptr[j] + ((int64_t)ih * a.W + iw) * Cb + cc * BKB);
+            rb[j] = v;
+        }
+        if (++cc == cchunks) {
+            cc = 0;
+            if (++s == a.S) { s = 0; ++r; }
+        }
+    };
+
+    auto lstore = [&](int buf) {
+        uint8_t *la = lds[buf];
+        uint8_t *lb = lds[buf] + BC * 64;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            if (NA * T != BC * CPR && tid + j * T >= BC * CPR) continue;
+            const int row = a_row[j], sw = swz(row);
+            if (INT4) {
+                v4i lo, hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t u = (uint32_t)ra[j][e];
+                    uint32_t l = u & 0x0F0F0F0Fu, h = (u >> 4) & 0x0F0F0F0Fu;
+                    l |= (l & 0x08080808u) * 0x1Eu;   // sign-extend each nibble to a byte
+                    h |= (h & 0x08080808u) * 0x1Eu;
+                    lo[e] = (int)l; hi[e] = (int)h;
+                }
+                *(v4i *)(la + row * 64 + (((2 * a_ch[j]) ^ sw) << 4)) = lo;
+                *(v4i *)(la + row * 64 + (((2 * a_ch[j] + 1) ^ sw) << 4)) = hi;
+            } else {
+                *(v4i *)(la + row * 64 + ((a_ch[j] ^ sw) << 4)) = ra[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (NB * T != BP * CPR && tid + j * T >= BP * CPR) continue;
+            const int row = b_row[j], sw = swz(row);
+            if (INT4) {
+                v4i lo, hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t u = (uint32_t)rb[j][e];
+                    lo[e] = (int)(u & 0x0F0F0F0Fu);
+                    hi[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
+                }
+                *(v4i *)(lb + row * 64 + (((2 * b_ch[j]) ^ sw) << 4)) = lo;
+                *(v4i *)(lb + row * 64 + (((2 * b_ch[j] + 1) ^ sw) << 4)) = hi;
+            } else {
+                *(v4i *)(lb + row * 64 + ((b_ch[j] ^ sw) << 4)) = rb[j];
+            }
+        }
+    };
+
+    // ---- MFMA fragment addresses (loop invariant) ----
+    // Row operand: MFMA row rho = lane%32 of channel tile tc is output register i = (rho>>3)*4 + (rho&3)
+    // of lane half h = (rho>>2)&1; we want that register to be channel  h*16*TC + tc*16 + i  of the wave.
+    const int rho = lane & 31, khalf = lane >> 5;
+    const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
+    int a_off[TC][2], b_off[TP][2];
+#pragma unroll
+    for (int tc = 0; tc < TC; ++tc) {
+        const int row = wc * (BC / WC) + hsel * 16 * TC + tc * 16 + isel;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) a_off[tc][kk] = row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
+    }
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp) {
+        const int row = wp * (BP / WP) + tp * 32 + rho;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) b_off[tp][kk] = BC * 64 + row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
+    }
+
+    v16i acc[TP][TC];
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
+
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int step = 0; step < steps; ++step) {
+        const int cur = step & 1;
+        if (step + 1 < steps) gload(step + 1);
+        const uint8_t *base = lds[cur];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            v4i af[TC], bf[TP];
+#pragma unroll
+            for (int tc = 0; tc < TC; ++tc) af[tc] = *(const v4i *)(base + a_off[tc][kk]);
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) bf[tp] = *(const v4i *)(base + b_off[tp][kk]);
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+                for (int tc = 0; tc < TC; ++tc)
+                    acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[tc], bf[tp], acc[tp][tc], 0, 0, 0);
+        }
+        if (step + 1 < steps) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
+    const int ch0 = k0 + wc * (BC / WC) + khalf * 16 * TC;
+    if (ch0 >= a.K) return;
+    static_for<0, TP>([&](auto tpc) {
+        constexpr int tp = decltype(tpc)::value;
+        const int m = m0 + wp * (BP / WP) + tp * 32 + rho;
+        if (m >= a.M) return;
+        if (vec_epilogue) epilogue_pixel<TC, true>(a, m, ch0, acc[tp]);
+        else epilogue_pixel<TC, false>(a, m, ch0, acc[tp]);
+    });
+}
+
+bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
+    if (a.C % 64 != 0) return false;
+    const bool four = is4(a.x_dt);
+    if (four != is4(a.w_dt)) return false;
+    if (four) {
+        if (a.x_dt != HAWQ_U4 || a.w_dt != HAWQ_S4) return false;
+    } else {
+        if (a.w_dt != HAWQ_S8) return false;
+        if (a.x_dt == HAWQ_U8 && x_hi > 127) return false;   // needs the signed INT8 operand range
+        if (a.x_dt != HAWQ_U8 && a.x_dt != HAWQ_S8) return false;
+    }
+    if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
+    return true;
+}
+
+template <int BC, int BP, int WC, int WP>
+static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s) {
+    const uint32_t n_ctiles = (a.K + BC - 1) / BC;
+    const uint32_t n_mtiles = (a.M + BP - 1) / BP;
+    const uint32_t nblocks = n_ctiles * n_mtiles;
+    if (is4(a.x_dt))
+        conv_mfma_kernel<BC, BP, WC, WP, true><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
+    else
+        conv_mfma_kernel<BC, BP, WC, WP, false><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
+    return check_launch();
+}
+
+hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    // vector epilogue needs 16-channel groups to be whole and every array 16-byte aligned
+    uintptr_t al = (uintptr_t)a.y | (uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.res_b | (uintptr_t)a.res;
+    al |= ((uintptr_t)a.c | (uintptr_t)a.res_c) & 3;
+    const int vec = (a.K % 16 == 0) && ((al & 15) == 0);
+    const int64_t tiles_big = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
+    if (a.K > 64 && tiles_big >= 512) return launch_cfg<128, 128, 2, 2>(a, vec, s);
+    const int64_t tiles_mid = (int64_t)((a.K + 63) / 64) * ((a.M + 127) / 128);
+    if (tiles_mid >= 512) return launch_cfg<64, 128, 1, 4>(a, vec, s);
+    return launch_cfg<64, 64, 2, 2>(a, vec, s);
+}
+
+}  // namespace hawq

@@ -1,0 +1,203 @@
+// Memory-bound integer kernels: stand-alone dyadic residual add, global average pool,
+// 3x3/2 max pool.  One thread handles 4 consecutive channels of one pixel when the channel
+// count allows it (dword loads/stores of packed 8-bit data), else one unit of 1 or 2 channels.
+#include "common.h"
+
+namespace hawq {
+
+// ---- residual add (Section 3.3): y = clamp(rq(m) + rq(r)) ----
+__global__ void __launch_bounds__(256)
+residual_add_kernel(const int64_t units, const int K, const int per, const int m_dt, const int r_dt, const int y_dt,
+                    const void *__restrict__ m, const int32_t *__restrict__ m_b, const uint8_t *__restrict__ m_c,
+                    const void *__restrict__ r, const int32_t *__restrict__ r_b, const uint8_t *__restrict__ r_c,
+                    const int lo, const int hi, void *__restrict__ y) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int64_t e0 = u * per;
+    const int k0 = (int)(e0 % K);
+    int32_t out[4];
+    for (int j = 0; j < per; ++j) {
+        const int k = k0 + j;
+        const int64_t v = rq64(load_elem(m, m_dt, e0 + j), m_b[k], m_c[k]) + rq64(load_elem(r, r_dt, e0 + j), r_b[k], r_c[k]);
+        out[j] = clamp64(v, lo, hi);
+    }
+    if (y_dt == HAWQ_S32) {
+        for (int j = 0; j < per; ++j) ((int32_t *)y)[e0 + j] = out[j];
+    } else if (is4(y_dt)) {
+        for (int j = 0; j < per; j += 2) ((uint8_t *)y)[(e0 + j) >> 1] = (uint8_t)((out[j] & 0xf) | ((out[j + 1] & 0xf) << 4));
+    } else if (per == 4) {
+        ((uint32_t *)y)[e0 >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
+    } else {
+        for (int j = 0; j < per; ++j) ((uint8_t *)y)[e0 + j] = (uint8_t)out[j];
+    }
+}
+
+hawq_status launch_residual_add(int64_t n_pixels, int K, int m_dt, int r_dt, int y_dt, const void *m, const int32_t *m_b,
+                                const uint8_t *m_c, const void *r, const int32_t *r_b, const uint8_t *r_c, int lo, int hi,
+                                void *y, hipStream_t s) {
+    const bool any4 = is4(m_dt) || is4(r_dt) || is4(y_dt);
+    int per = (K % 4 == 0 && ((uintptr_t)y & 3) == 0) ? 4 : (any4 ? 2 : 1);
+    const int64_t units = n_pixels * K / per;
+    if (units == 0) return HAWQ_OK;
+    const int64_t blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+    residual_add_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, K, per, m_dt, r_dt, y_dt, m, m_b, m_c, r, r_b, r_c, lo, hi, y);
+    return check_launch();
+}
+
+// ---- global average pool (Appendix E): INT32 sum over H*W, then one dyadic rescale ----
+// grid: (ceil(C/per/64), N); one thread sums `per` adjacent channels over all pixels, so a
+// wave reads 64*per consecutive bytes of every pixel.
+__global__ void __launch_bounds__(64)
+avgpool_kernel(const int HW, const int C, const int per, const int x_dt, const int y_dt, const void *__restrict__ x,
+               const int32_t *__restrict__ b, const uint8_t *__restrict__ c, const int lo, const int hi, void *__restrict__ y) {
+    const int n = blockIdx.y;
+    const int k0 = (blockIdx.x * 64 + threadIdx.x) * per;
+    if (k0 >= C) return;
+    int32_t sum[4] = {0, 0, 0, 0};
+    const int64_t base = (int64_t)n * HW * C + k0;
+    if (per == 4 && !is4(x_dt)) {
+        const uint8_t *xp = (const uint8_t *)x + base;
+        for (int i = 0; i < HW; ++i) {
+            const uint32_t v = *(const uint32_t *)(xp + (int64_t)i * C);
+            if (x_dt == HAWQ_U8) {
+                sum[0] += v & 0xff; sum[1] += (v >> 8) & 0xff; sum[2] += (v >> 16) & 0xff; sum[3] += v >> 24;
+            } else {
+                sum[0] += (int8_t)(v & 0xff); sum[1] += (int8_t)((v >> 8) & 0xff);
+                sum[2] += (int8_t)((v >> 16) & 0xff); sum[3] += (int8_t)(v >> 24);
+            }
+        }
+    } else {
+        for (int i = 0; i < HW; ++i)
+            for (int j = 0; j < per; ++j) sum[j] += load_elem(x, x_dt, base + (int64_t)i * C + j);
+    }
+    int32_t out[4];
+    for (int j = 0; j < per; ++j) out[j] = clamp64(rq64(sum[j], b[k0 + j], c[k0 + j]), lo, hi);
+    const int64_t o = (int64_t)n * C + k0;
+    if (y_dt == HAWQ_S32) {
+        for (int j = 0; j < per; ++j) ((int32_t *)y)[o + j] = out[j];
+    } else if (is4(y_dt)) {
+        for (int j = 0; j < per; j += 2) ((uint8_t *)y)[(o + j) >> 1] = (uint8_t)((out[j] & 0xf) | ((out[j + 1] & 0xf) << 4));
+    } else {
+        for (int j = 0; j < per; ++j) ((uint8_t *)y)[o + j] = (uint8_t)out[j];
+    }
+}
+
+hawq_status launch_avgpool(int N, int HW, int C, int x_dt, int y_dt, const void *x, const int32_t *b, const uint8_t *c,
+                           int lo, int hi, void *y, hipStream_t s) {
+    if (N == 0) return HAWQ_OK;
+    const bool any4 = is4(x_dt) || is4(y_dt);
+    const int per = (C % 4 == 0 && ((uintptr_t)x & 3) == 0) ? 4 : (any4 ? 2 : 1);
+    dim3 grid((C / per + 63) / 64, N);
+    avgpool_kernel<<<grid, 64, 0, s>>>(HW, C, per, x_dt, y_dt, x, b, c, lo, hi, y);
+    return check_launch();
+}
+
+// ---- max pool 3x3 / 2, pad 1 ----
+__device__ __forceinline__ uint32_t max_u8x4(uint32_t a, uint32_t b) {
+    // per-byte unsigned maximum through two 16-bit lanes
+    const uint32_t ae = a & 0x00ff00ffu, be = b & 0x00ff00ffu, ao = (a >> 8) & 0x00ff00ffu, bo = (b >> 8) & 0x00ff00ffu;
+    const uint32_t e = ((ae & 0xffff) > (be & 0xffff) ? (ae & 0xffff) : (be & 0xffff)) |
+                       ((ae >> 16) > (be >> 16) ? (ae & 0xffff0000u) : (be & 0xffff0000u));
+    const uint32_t o = ((ao & 0xffff) > (bo & 0xffff) ? (ao & 0xffff) : (bo & 0xffff)) |
+                       ((ao >> 16) > (bo >> 16) ? (ao & 0xffff0000u) : (bo & 0xffff0000u));
+    return e | (o << 8);
+}
+
+// fast path: U8 in, C % 16 == 0; one thread = 16 channels of one output pixel
+__global__ void __launch_bounds__(256)
+maxpool_u8_kernel(const int64_t units, const int H, const int W, const int C, const int P, const int Q,
+                  const uint8_t *__restrict__ x, const int lo, const int hi, const int y_dt, uint8_t *__restrict__ y) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int cg = C / 16;
+    const int g = (int)(u % cg);
+    int64_t t = u / cg;
+    const int q = (int)(t % Q); t /= Q;
+    const int p = (int)(t % P);
+    const int n = (int)(t / P);
+    uint4 best = make_uint4(0, 0, 0, 0);   // unsigned data: 0 is the identity, padding never wins
+    for (int r = 0; r < 3; ++r) {
+        const int ih = 2 * p - 1 + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int s = 0; s < 3; ++s) {
+            const int iw = 2 * q - 1 + s;
+            if (iw < 0 || iw >= W) continue;
+            const uint4 v = *(const uint4 *)(x + (((int64_t)n * H + ih) * W + iw) * C + g * 16);
+            best.x = max_u8x4(best.x, v.x); best.y = max_u8x4(best.y, v.y);
+            best.z = max_u8x4(best.z, v.z); best.w = max_u8x4(best.w, v.w);
+        }
+    }
+    uint32_t wv[4] = {best.x, best.y, best.z, best.w};
+    uint32_t ov[4];
+    uint32_t nib[2] = {0, 0};
+    for (int d = 0; d < 4; ++d) {
+        uint32_t o = 0, h = 0;
+        for (int j = 0; j < 4; ++j) {
+            int32_t v = (int32_t)((wv[d] >> (8 * j)) & 0xff);
+            v = v < lo ? lo : (v > hi ? hi : v);
+            o |= (uint32_t)(v & 0xff) << (8 * j);
+            h |= (uint32_t)(v & 0xf) << (4 * j);
+        }
+        ov[d] = o;
+        nib[d >> 1] |= h << (16 * (d & 1));
+    }
+    const int64_t oe = (((int64_t)n * P + p) * Q + q) * C + g * 16;
+    if (is4(y_dt)) *(uint2 *)(y + (oe >> 1)) = make_uint2(nib[0], nib[1]);
+    else *(uint4 *)(y + oe) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
+}
+
+__global__ void __launch_bounds__(256)
+maxpool_generic_kernel(const int64_t units, const int per, const int H, const int W, const int C, const int P, const int Q,
+                       const int x_dt, const int y_dt, const void *__restrict__ x, const int lo, const int hi,
+                       void *__restrict__ y) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int cu = C / per;
+    const int k0 = (int)(u % cu) * per;
+    int64_t t = u / cu;
+    const int q = (int)(t % Q); t /= Q;
+    const int p = (int)(t % P);
+    const int n = (int)(t / P);
+    int32_t out[2];
+    for (int j = 0; j < per; ++j) {
+        int32_t best = INT32_MIN;
+        for (int r = 0; r < 3; ++r) {
+            const int ih = 2 * p - 1 + r;
+            if (ih < 0 || ih >= H) continue;
+            for (int s = 0; s < 3; ++s) {
+                const int iw = 2 * q - 1 + s;
+                if (iw < 0 || iw >= W) continue;
+                const int32_t v = load_elem(x, x_dt, (((int64_t)n * H + ih) * W + iw) * C + k0 + j);
+                best = v > best ? v : best;
+            }
+        }
+        out[j] = best < lo ? lo : (best > hi ? hi : best);
+    }
+    const int64_t oe = (((int64_t)n * P + p) * Q + q) * C + k0;
+    if (is4(y_dt)) ((uint8_t *)y)[oe >> 1] = (uint8_t)((out[0] & 0xf) | ((out[1] & 0xf) << 4));
+    else ((uint8_t *)y)[oe] = (uint8_t)out[0];
+}
+
+hawq_status launch_maxpool(int N, int H, int W, int C, int x_dt, int y_dt, const void *x, int lo, int hi, void *y,
+                           hipStream_t s) {
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    if (N == 0) return HAWQ_OK;
+    const bool fast = x_dt == HAWQ_U8 && (y_dt == HAWQ_U8 || y_dt == HAWQ_U4) && C % 16 == 0 &&
+                      (((uintptr_t)x | (uintptr_t)y) & 15) == 0 && lo >= 0;
+    if (fast) {
+        const int64_t units = (int64_t)N * P * Q * (C / 16);
+        const int64_t blocks = (units + 255) / 256;
+        if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+        maxpool_u8_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, P, Q, (const uint8_t *)x, lo, hi, y_dt, (uint8_t *)y);
+    } else {
+        const int per = (is4(x_dt) || is4(y_dt)) ? 2 : 1;
+        const int64_t units = (int64_t)N * P * Q * (C / per);
+        const int64_t blocks = (units + 255) / 256;
+        if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+        maxpool_generic_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, per, H, W, C, P, Q, x_dt, y_dt, x, lo, hi, y);
+    }
+    return check_launch();
+}
+
+}  // namespace hawq

@@ -1,0 +1,147 @@
+// Fused epilogue of the matrix-core convolution kernels: bias add, dyadic requantisation,
+// dyadic-rescaled shortcut add, ReLU / clamp, packing and the NHWC store.
+//
+// Register layout it expects: a lane owns, for one output pixel, GROUPS*16 consecutive output
+// channels starting at `ch0`; acc[g][i] is channel ch0 + 16*g + i.  That makes every store a
+// contiguous 16-byte (8-bit outputs), 8-byte (4-bit) or 64-byte (INT32) run per group.
+#pragma once
+#include "common.h"
+
+namespace hawq {
+
+struct EpiParams4 {  // parameters of 4 consecutive channels
+    int32_t bias[4], b[4], c[4], rb[4], rc[4];
+};
+
+template <bool VEC>
+__device__ __forceinline__ void load_params4(const ConvArgs &a, int ch, bool has_rq, bool has_res, EpiParams4 &p) {
+    if (VEC) {
+        const v4i bv = *(const v4i *)(a.bias + ch);
+        p.bias[0] = bv[0]; p.bias[1] = bv[1]; p.bias[2] = bv[2]; p.bias[3] = bv[3];
+        if (has_rq) {
+            const v4i mv = *(const v4i *)(a.b + ch);
+            const uint32_t cv = *(const uint32_t *)(a.c + ch);
+            p.b[0] = mv[0]; p.b[1] = mv[1]; p.b[2] = mv[2]; p.b[3] = mv[3];
+            p.c[0] = cv & 0xff; p.c[1] = (cv >> 8) & 0xff; p.c[2] = (cv >> 16) & 0xff; p.c[3] = cv >> 24;
+        }
+        if (has_res) {
+            const v4i mv = *(const v4i *)(a.res_b + ch);
+            const uint32_t cv = *(const uint32_t *)(a.res_c + ch);
+            p.rb[0] = mv[0]; p.rb[1] = mv[1]; p.rb[2] = mv[2]; p.rb[3] = mv[3];
+            p.rc[0] = cv & 0xff; p.rc[1] = (cv >> 8) & 0xff; p.rc[2] = (cv >> 16) & 0xff; p.rc[3] = cv >> 24;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool ok = ch + j < a.K;
+            p.bias[j] = ok ? a.bias[ch + j] : 0;
+            p.b[j] = (ok && has_rq) ? a.b[ch + j] : 0;
+            p.c[j] = (ok && has_rq) ? a.c[ch + j] : 1;
+            p.rb[j] = (ok && has_res) ? a.res_b[ch + j] : 0;
+            p.rc[j] = (ok && has_res) ? a.res_c[ch + j] : 1;
+        }
+    }
+}
+
+// value of shortcut element j (0..3) of a group of 4 channels held in `word`
+// (8-bit: 4 bytes in one dword; 4-bit: 4 nibbles in the low 16 bits)
+__device__ __forceinline__ int32_t res_elem(uint32_t word, int j, int res_dt) {
+    switch (res_dt) {
+    case HAWQ_U8: return (int32_t)((word >> (8 * j)) & 0xff);
+    case HAWQ_S8: return (int32_t)(int8_t)((word >> (8 * j)) & 0xff);
+    case HAWQ_U4: return (int32_t)((word >> (4 * j)) & 0xf);
+    default: {
+        int32_t n = (int32_t)((word >> (4 * j)) & 0xf);
+        return n >= 8 ? n - 16 : n;
+    }
+    }
+}
+
+// One output value: accumulator -> stored integer.
+__device__ __forceinline__ int32_t finish(int32_t acc, const EpiParams4 &p, int j, bool has_rq, bool has_res, int32_t r,
+                                          int32_t lo, int32_t hi) {
+    const int32_t t = acc + p.bias[j];
+    if (!has_rq) return t;
+    int64_t v = rq64(t, p.b[j], p.c[j]);
+    if (has_res) v += rq64(r, p.rb[j], p.rc[j]);
+    return clamp64(v, lo, hi);
+}
+
+// Epilogue for one pixel `m` and GROUPS*16 channels starting at ch0 (ch0 % 16 == 0).
+// VEC: K % 16 == 0 and all arrays 16-byte aligned -> vector loads/stores; otherwise a guarded
+// element-wise path (still one lane per pixel x 16-channel group).
+template <int GROUPS, bool VEC>
+__device__ __forceinline__ void epilogue_pixel(const ConvArgs &a, int64_t m, int ch0, const v16i (&acc)[GROUPS]) {
+    const bool has_rq = a.b != nullptr;
+    const bool has_res = a.res != nullptr;
+    const int y_dt = a.y_dt, res_dt = a.res_dt;
+    const int64_t o = m * (int64_t)a.K + ch0;  // element offset of the lane's first channel
+    static_for<0, GROUPS>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        const int chg = ch0 + 16 * g;
+        if (chg >= a.K) return;
+        // shortcut values of the 16 channels, as 4 words of 4 channels
+        uint32_t rw[4] = {0, 0, 0, 0};
+        if (has_res) {
+            if (VEC) {
+                if (is4(res_dt)) {
+                    const uint2 t = *(const uint2 *)(a.res + ((o + 16 * g) >> 1));
+                    rw[0] = t.x & 0xffff; rw[1] = t.x >> 16; rw[2] = t.y & 0xffff; rw[3] = t.y >> 16;
+                } else {
+                    const uint4 t = *(const uint4 *)(a.res + (o + 16 * g));
+                    rw[0] = t.x; rw[1] = t.y; rw[2] = t.z; rw[3] = t.w;
+                }
+            }
+        }
+        uint32_t out8[4];   // 8-bit outputs: 4 dwords;  4-bit outputs: out8[0..1]
+        uint32_t out4[2] = {0, 0};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            EpiParams4 p;
+            load_params4<VEC>(a, chg + 4 * q, has_rq, has_res, p);
+            int32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int32_t r = 0;
+                if (has_res) {
+                    if (VEC) r = res_elem(rw[q], j, res_dt);
+                    else if (chg + 4 * q + j < a.K) r = load_elem(a.res, res_dt, o + 16 * g + 4 * q + j);
+                }
+                v[j] = finish(acc[g][4 * q + j], p, j, has_rq, has_res, r, a.lo, a.hi);
+            }
+            if (VEC) {
+                if (y_dt == HAWQ_S32) {
+                    v4i t = {v[0], v[1], v[2], v[3]};
+                    *(v4i *)(a.y + 4 * (o + 16 * g + 4 * q)) = t;
+                } else if (is4(y_dt)) {
+                    const uint32_t h = (v[0] & 0xf) | ((v[1] & 0xf) << 4) | ((v[2] & 0xf) << 8) | ((v[3] & 0xf) << 12);
+                    out4[q >> 1] |= h << (16 * (q & 1));
+                } else {
+                    out8[q] = (v[0] & 0xff) | ((v[1] & 0xff) << 8) | ((v[2] & 0xff) << 16) | ((uint32_t)v[3] << 24);
+                }
+            } else {
+                // guarded element-wise stores; 4-bit outputs are written a byte (2 channels) at a time,
+                // K is even for them so a pair never straddles the channel edge
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ch = chg + 4 * q + j;
+                    if (ch >= a.K) continue;
+                    const int64_t e = o + 16 * g + 4 * q + j;
+                    if (y_dt == HAWQ_S32) ((int32_t *)a.y)[e] = v[j];
+                    else if (is4(y_dt)) {
+                        if ((j & 1) == 0) a.y[e >> 1] = (uint8_t)((v[j] & 0xf) | ((v[j + 1] & 0xf) << 4));
+                    } else a.y[e] = (uint8_t)v[j];
+                }
+            }
+        }
+        if (VEC) {
+            if (is4(y_dt)) {
+                *(uint2 *)(a.y + ((o + 16 * g) >> 1)) = make_uint2(out4[0], out4[1]);
+            } else if (y_dt != HAWQ_S32) {
+                *(uint4 *)(a.y + (o + 16 * g)) = make_uint4(out8[0], out8[1], out8[2], out8[3]);
+            }
+        }
+    });
+}
+
+}  // namespace hawq

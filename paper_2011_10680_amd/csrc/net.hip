@@ -1,0 +1,471 @@
+// Whole-network plan for the integer-only ResNet18 / ResNet50 forward (Figure 2, Section 3.3):
+// topology, storage rule for mixed precision, workspace slot assignment, parameter arena and the
+// launch sequence.  Host code only; the kernels live in the other translation units.
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace hawq {
+hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                           const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,
+                           bool check_pointers, ConvArgs &a, int &x_hi_out);
+hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s);
+}  // namespace hawq
+
+using namespace hawq;
+
+namespace {
+
+struct LayerShape {
+    std::string name;
+    int C, K, R, S, stride, pad, H, W, P, Q;
+    bool has_residual, is_ds, is_c1, is_fc, is_stem;
+    int block;  // running block index, -1 for stem / fc
+};
+
+int conv_out(int h, int r, int s, int p) { return (h + 2 * p - r) / s + 1; }
+
+// Canonical layer list: conv1; per block c1, c2, [c3], [ds]; fc.
+bool build_topology(int arch, int hw, int classes, std::vector<LayerShape> &out) {
+    static const int widths[4] = {64, 128, 256, 512};
+    int depth18[4] = {2, 2, 2, 2}, depth50[4] = {3, 4, 6, 3};
+    const int *depth = arch == 18 ? depth18 : (arch == 50 ? depth50 : nullptr);
+    if (!depth || hw < 32 || classes <= 0) return false;
+    out.clear();
+    int p1 = conv_out(hw, 7, 2, 3);
+    out.push_back({"conv1", 3, 64, 7, 7, 2, 3, hw, hw, p1, p1, false, false, false, false, true, -1});
+    int h = conv_out(p1, 3, 2, 1);
+    int cin = 64, blk = 0;
+    for (int si = 0; si < 4; ++si)
+        for (int bi = 0; bi < depth[si]; ++bi, ++blk) {
+            const int wd = widths[si], s = (si > 0 && bi == 0) ? 2 : 1;
+            const int cout = wd * (arch == 50 ? 4 : 1);
+            const int ho = conv_out(h, 1, s, 0);
+            char pre[32];
+            snprintf(pre, sizeof pre, "layer%d.%d", si + 1, bi);
+            const std::string n(pre);
+            if (arch == 50) {
+                out.push_back({n + ".c1", cin, wd, 1, 1, s, 0, h, h, ho, ho, false, false, true, false, false, blk});
+                out.push_back({n + ".c2", wd, wd, 3, 3, 1, 1, ho, ho, ho, ho, false, false, false, false, false, blk});
+                out.push_back({n + ".c3", wd, cout, 1, 1, 1, 0, ho, ho, ho, ho, true, false, false, false, false, blk});
+            } else {
+                out.push_back({n + ".c1", cin, wd, 3, 3, s, 1, h, h, ho, ho, false, false, true, false, false, blk});
+                out.push_back({n + ".c2", wd, cout, 3, 3, 1, 1, ho, ho, ho, ho, true, false, false, false, false, blk});
+            }
+            if (s != 1 || cin != cout)
+                out.push_back({n + ".ds", cin, cout, 1, 1, s, 0, h, h, ho, ho, false, true, false, false, false, blk});
+            cin = cout;
+            h = ho;
+        }
+    out.push_back({"fc", cin, classes, 1, 1, 1, 0, 1, 1, 1, 1, false, false, false, true, false, -1});
+    return true;
+}
+
+enum StepKind { STEP_STEM, STEP_MAXPOOL, STEP_CONV, STEP_AVGPOOL, STEP_FC };
+
+struct Tensor {           // a stored activation
+    int64_t elems_per_image;
+    int dt;
+    int dims[3];          // P, Q, K
+    int slot = -1;
+    int last_use = -1;    // last step that reads it
+};
+
+struct Step {
+    StepKind kind;
+    std::string name;
+    int layer = -1;               // index into the canonical layer list
+    int in = -1, res = -1, out = -1;  // tensor ids (-1: external image / logits)
+    hawq_conv_desc desc{};        // N filled per call
+    const uint8_t *w = nullptr;   // device parameter pointers
+    const int32_t *bias = nullptr, *b = nullptr, *res_b = nullptr;
+    const uint8_t *c = nullptr, *res_c = nullptr;
+    double macs_per_image = 0, bytes_per_image = 0, bytes_fixed = 0;
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct hawq_net {
+    int arch, hw, classes, keep;
+    std::vector<LayerShape> layers;
+    std::vector<Tensor> tensors;
+    std::vector<Step> steps;
+    std::vector<int64_t> slot_bytes_per_image;
+    void *arena = nullptr;
+};
+
+namespace {
+
+int act_dt(int bits) { return bits == 8 ? HAWQ_U8 : HAWQ_U4; }
+int act_hi(int bits) { return bits == 8 ? 127 : 15; }
+
+// Assign workspace slots: a tensor's slot is free again after its last reader has run.
+void assign_slots(hawq_net *net) {
+    auto &T = net->tensors;
+    for (size_t s = 0; s < net->steps.size(); ++s) {
+        const Step &st = net->steps[s];
+        if (st.in >= 0) T[st.in].last_use = (int)s;
+        if (st.res >= 0) T[st.res].last_use = (int)s;
+    }
+    std::vector<int> owner;  // slot -> tensor currently in it (-1 free)
+    auto &sb = net->slot_bytes_per_image;
+    sb.clear();
+    for (size_t s = 0; s < net->steps.size(); ++s) {
+        const Step &st = net->steps[s];
+        if (st.out < 0) continue;
+        Tensor &t = T[st.out];
+        const int64_t need = tensor_bytes(t.elems_per_image, t.dt);
+        int pick = -1;
+        if (!net->keep) {
+            for (size_t i = 0; i < owner.size(); ++i) {
+                if (owner[i] >= 0 && T[owner[i]].last_use < (int)s) owner[i] = -1;  // dead before this step
+            }
+            // best fit among free slots, else the largest free one (it grows), else a new slot
+            int64_t best = -1;
+            for (size_t i = 0; i < owner.size(); ++i)
+                if (owner[i] < 0 && sb[i] >= need && (best < 0 || sb[i] < best)) { best = sb[i]; pick = (int)i; }
+            if (pick < 0)
+                for (size_t i = 0; i < owner.size(); ++i)
+                    if (owner[i] < 0 && (pick < 0 || sb[i] > sb[pick])) pick = (int)i;
+        }
+        if (pick < 0) { owner.push_back(-1); sb.push_back(0); pick = (int)owner.size() - 1; }
+        owner[pick] = st.out;
+        if (sb[pick] < need) sb[pick] = need;
+        t.slot = pick;
+    }
+}
+
+size_t slot_offset(const hawq_net *net, int slot, int N) {
+    size_t off = 0;
+    for (int i = 0; i < slot; ++i) off += align_up((size_t)net->slot_bytes_per_image[i] * N, 256);
+    return off;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t hawq_net_num_layers(int32_t arch) {
+    std::vector<LayerShape> L;
+    return build_topology(arch, 224, 1000, L) ? (int32_t)L.size() : 0;
+}
+
+hawq_status hawq_net_layer_info(int32_t arch, int32_t image_hw, int32_t num_classes, int32_t index, hawq_layer_info *out) {
+    if (!out) return HAWQ_ERR_NULL;
+    std::vector<LayerShape> L;
+    if (!build_topology(arch, image_hw, num_classes, L)) return HAWQ_ERR_SHAPE;
+    if (index < 0 || index >= (int)L.size()) return HAWQ_ERR_RANGE;
+    const LayerShape &l = L[index];
+    memset(out, 0, sizeof *out);
+    snprintf(out->name, sizeof out->name, "%s", l.name.c_str());
+    out->C = l.C; out->K = l.K; out->R = l.R; out->S = l.S; out->stride = l.stride; out->pad = l.pad;
+    out->H = l.H; out->W = l.W; out->P = l.P; out->Q = l.Q;
+    out->has_residual = l.has_residual; out->is_ds = l.is_ds;
+    return HAWQ_OK;
+}
+
+hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes, const hawq_layer_params *lp, int32_t n_layers,
+                            const int32_t *pool_b, const uint8_t *pool_c, int32_t keep_activations, hawq_net **out) {
+    if (!lp || !pool_b || !pool_c || !out) return HAWQ_ERR_NULL;
+    *out = nullptr;
+    hawq_net *net = new hawq_net();
+    net->arch = arch; net->hw = image_hw; net->classes = num_classes; net->keep = keep_activations != 0;
+    if (!build_topology(arch, image_hw, num_classes, net->layers)) { delete net; return HAWQ_ERR_SHAPE; }
+    auto &L = net->layers;
+    const int nl = (int)L.size();
+    if (n_layers != nl) { delete net; return HAWQ_ERR_SHAPE; }
+    auto fail = [&](hawq_status st) { delete net; return st; };
+
+    // ---- validate parameters (host data: ranges can be checked here) ----
+    for (int i = 0; i < nl; ++i) {
+        const hawq_layer_params &p = lp[i];
+        if (!p.w || !p.bias) return fail(HAWQ_ERR_NULL);
+        if (!L[i].is_fc && (!p.b || !p.c)) return fail(HAWQ_ERR_NULL);
+        if (L[i].has_residual && (!p.res_b || !p.res_c)) return fail(HAWQ_ERR_NULL);
+        if (p.bits != 4 && p.bits != 8) return fail(HAWQ_ERR_DTYPE);
+        if ((L[i].is_stem || L[i].is_fc) && p.bits != 8) return fail(HAWQ_ERR_DTYPE);
+        if (L[i].is_ds) {
+            int j = i;
+            while (j >= 0 && !(L[j].is_c1 && L[j].block == L[i].block)) --j;
+            if (j < 0 || lp[j].bits != p.bits) return fail(HAWQ_ERR_DTYPE);
+        }
+        if (!L[i].is_fc)
+            for (int k = 0; k < L[i].K; ++k) {
+                if (p.b[k] < 0 || p.c[k] < 1 || p.c[k] > 62) return fail(HAWQ_ERR_RANGE);
+                if (L[i].has_residual && (p.res_b[k] < 0 || p.res_c[k] < 1 || p.res_c[k] > 62)) return fail(HAWQ_ERR_RANGE);
+            }
+    }
+    const int c_last = L[nl - 1].C;
+    for (int k = 0; k < c_last; ++k)
+        if (pool_b[k] < 0 || pool_c[k] < 1 || pool_c[k] > 62) return fail(HAWQ_ERR_RANGE);
+
+    // ---- parameter arena layout ----
+    struct Off { size_t w, bias, b, c, rb, rc; };
+    std::vector<Off> off(nl);
+    size_t total = 0;
+    auto take = [&](size_t bytes) { size_t o = total; total = align_up(total + bytes, 256); return o; };
+    for (int i = 0; i < nl; ++i) {
+        const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
+        off[i].w = take((size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        off[i].bias = take(4 * (size_t)L[i].K);
+        off[i].b = take(4 * (size_t)L[i].K);
+        off[i].c = take((size_t)L[i].K);
+        off[i].rb = take(4 * (size_t)L[i].K);
+        off[i].rc = take((size_t)L[i].K);
+    }
+    const size_t off_pb = take(4 * (size_t)c_last), off_pc = take((size_t)c_last);
+    std::vector<uint8_t> host(total, 0);
+    for (int i = 0; i < nl; ++i) {
+        const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
+        memcpy(&host[off[i].w], lp[i].w, (size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        memcpy(&host[off[i].bias], lp[i].bias, 4 * (size_t)L[i].K);
+        if (!L[i].is_fc) {
+            memcpy(&host[off[i].b], lp[i].b, 4 * (size_t)L[i].K);
+            memcpy(&host[off[i].c], lp[i].c, (size_t)L[i].K);
+        }
+        if (L[i].has_residual) {
+            memcpy(&host[off[i].rb], lp[i].res_b, 4 * (size_t)L[i].K);
+            memcpy(&host[off[i].rc], lp[i].res_c, (size_t)L[i].K);
+        }
+    }
+    memcpy(&host[off_pb], pool_b, 4 * (size_t)c_last);
+    memcpy(&host[off_pc], pool_c, (size_t)c_last);
+    if (hipMalloc(&net->arena, total) != hipSuccess) return fail(HAWQ_ERR_DEVICE);
+    if (hipMemcpy(net->arena, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(net->arena);
+        return fail(HAWQ_ERR_DEVICE);
+    }
+    const uint8_t *A = (const uint8_t *)net->arena;
+
+    // ---- steps ----
+    auto new_tensor = [&](int P, int Q, int K, int dt) {
+        Tensor t;
+        t.elems_per_image = (int64_t)P * Q * K; t.dt = dt; t.dims[0] = P; t.dims[1] = Q; t.dims[2] = K;
+        net->tensors.push_back(t);
+        return (int)net->tensors.size() - 1;
+    };
+    // bit width of the conv that reads the tensor produced after layer i's block / stem
+    auto reader_bits_after = [&](int i) {
+        int j = i + 1;
+        while (j < nl && L[j].is_ds) ++j;
+        return (j >= nl || L[j].is_fc) ? 8 : lp[j].bits;
+    };
+    auto conv_step = [&](int i, int in_t, int in_dt, int in_hi, int res_t, int res_dt, int out_bits, bool signed_out,
+                         bool relu) {
+        Step st;
+        st.kind = L[i].is_stem ? STEP_STEM : STEP_CONV;
+        st.name = L[i].name; st.layer = i; st.in = in_t; st.res = res_t;
+        hawq_conv_desc &d = st.desc;
+        d.N = 1; d.H = L[i].H; d.W = L[i].W; d.C = L[i].C; d.K = L[i].K; d.R = L[i].R; d.S = L[i].S;
+        d.stride_h = d.stride_w = L[i].stride; d.pad_h = d.pad_w = L[i].pad;
+        d.x_dtype = in_dt; d.w_dtype = lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8;
+        d.y_dtype = signed_out ? HAWQ_S8 : (L[i].is_stem ? HAWQ_U8 : act_dt(out_bits));
+        d.res_dtype = res_dt; d.relu = relu; d.y_lo = signed_out ? -128 : 0; d.y_hi = signed_out ? 127 : act_hi(out_bits);
+        d.x_hi = in_hi;
+        st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
+        st.b = (const int32_t *)(A + off[i].b); st.c = A + off[i].c;
+        if (res_t >= 0) { st.res_b = (const int32_t *)(A + off[i].rb); st.res_c = A + off[i].rc; }
+        st.out = new_tensor(L[i].P, L[i].Q, L[i].K, d.y_dtype);
+        const double wbytes = (double)tensor_bytes((int64_t)L[i].K * L[i].R * L[i].S * L[i].C, d.w_dtype);
+        st.macs_per_image = (double)L[i].P * L[i].Q * L[i].K * L[i].R * L[i].S * L[i].C;
+        // input read once (a strided 1x1 touches only the sampled pixels), output and shortcut once
+        const double in_pix = (L[i].R == 1 && L[i].stride > 1) ? (double)L[i].P * L[i].Q : (double)L[i].H * L[i].W;
+        st.bytes_per_image = (double)tensor_bytes((int64_t)(in_pix * L[i].C), in_dt) +
+                             (double)tensor_bytes((int64_t)L[i].P * L[i].Q * L[i].K, d.y_dtype) +
+                             (res_t >= 0 ? (double)tensor_bytes((int64_t)L[i].P * L[i].Q * L[i].K, res_dt) : 0.0);
+        st.bytes_fixed = wbytes + 9.0 * L[i].K + (res_t >= 0 ? 5.0 * L[i].K : 0.0);
+        net->steps.push_back(st);
+        return st.out;
+    };
+
+    int li = 0;
+    int stage_bits = reader_bits_after(0);
+    int t = conv_step(0, -1, HAWQ_U8, 255, -1, HAWQ_U8, stage_bits, false, true);
+    {
+        Step st;
+        st.kind = STEP_MAXPOOL; st.name = "pool"; st.in = t;
+        const int P = conv_out(L[0].P, 3, 2, 1);
+        st.desc.H = L[0].P; st.desc.W = L[0].Q; st.desc.C = 64; st.desc.x_dtype = HAWQ_U8; st.desc.y_dtype = act_dt(stage_bits);
+        st.desc.y_lo = 0; st.desc.y_hi = act_hi(stage_bits);
+        st.out = new_tensor(P, P, 64, act_dt(stage_bits));
+        st.bytes_per_image = (double)L[0].P * L[0].Q * 64 + (double)tensor_bytes((int64_t)P * P * 64, act_dt(stage_bits));
+        net->steps.push_back(st);
+        t = st.out;
+    }
+    li = 1;
+    int in_bits = stage_bits;
+    while (li < nl && !L[li].is_fc) {
+        // one block: c1, c2, [c3], [ds]
+        const int blk = L[li].block;
+        std::vector<int> mids;
+        int last = -1, ds = -1;
+        int j = li;
+        for (; j < nl && L[j].block == blk && !L[j].is_fc; ++j) {
+            if (L[j].is_ds) ds = j;
+            else if (L[j].has_residual) last = j;
+            else mids.push_back(j);
+        }
+        if (lp[mids[0]].bits != in_bits) return fail(HAWQ_ERR_DTYPE);  // cannot happen: in_bits derives from it
+        const int out_bits = reader_bits_after(j - 1);
+        const int block_in = t, block_in_dt = act_dt(in_bits);
+        int u = block_in, u_dt = block_in_dt, u_bits = in_bits;
+        std::vector<int> chain = mids;
+        chain.push_back(last);
+        for (size_t q = 0; q < mids.size(); ++q) {
+            const int ob = lp[chain[q + 1]].bits;
+            u = conv_step(mids[q], u, u_dt, act_hi(u_bits), -1, HAWQ_U8, ob, false, true);
+            u_dt = act_dt(ob); u_bits = ob;
+        }
+        int sc = block_in, sc_dt = block_in_dt;
+        if (ds >= 0) {
+            sc = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, true, false);
+            sc_dt = HAWQ_S8;
+        }
+        t = conv_step(last, u, u_dt, act_hi(u_bits), sc, sc_dt, out_bits, false, true);
+        in_bits = out_bits;
+        li = j;
+    }
+    {
+        Step st;
+        st.kind = STEP_AVGPOOL; st.name = "avgpool"; st.in = t;
+        const LayerShape &pl = L[nl - 2].is_ds ? L[nl - 3] : L[nl - 2];
+        st.desc.H = pl.P; st.desc.W = pl.Q; st.desc.C = c_last; st.desc.x_dtype = HAWQ_U8; st.desc.y_dtype = HAWQ_U8;
+        st.desc.y_lo = 0; st.desc.y_hi = 127;
+        st.b = (const int32_t *)(A + off_pb); st.c = A + off_pc;
+        st.out = new_tensor(1, 1, c_last, HAWQ_U8);
+        st.bytes_per_image = (double)pl.P * pl.Q * c_last + c_last;
+        st.bytes_fixed = 5.0 * c_last;
+        net->steps.push_back(st);
+        t = st.out;
+    }
+    {
+        const int i = nl - 1;
+        Step st;
+        st.kind = STEP_FC; st.name = "fc"; st.layer = i; st.in = t;
+        hawq_conv_desc &d = st.desc;
+        d.N = 1; d.H = 1; d.W = 1; d.C = L[i].C; d.K = L[i].K; d.R = d.S = 1; d.stride_h = d.stride_w = 1;
+        d.x_dtype = HAWQ_U8; d.w_dtype = HAWQ_S8; d.y_dtype = HAWQ_S32; d.res_dtype = HAWQ_U8; d.x_hi = 127;
+        d.y_lo = INT32_MIN; d.y_hi = INT32_MAX;
+        st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
+        st.macs_per_image = (double)L[i].C * L[i].K;
+        st.bytes_per_image = (double)L[i].C + 4.0 * L[i].K;
+        st.bytes_fixed = (double)L[i].C * L[i].K + 4.0 * L[i].K;
+        net->steps.push_back(st);
+    }
+    assign_slots(net);
+    *out = net;
+    return HAWQ_OK;
+}
+
+void hawq_net_destroy(hawq_net *net) {
+    if (!net) return;
+    if (net->arena) (void)hipFree(net->arena);
+    delete net;
+}
+
+size_t hawq_net_workspace_bytes(const hawq_net *net, int32_t N) {
+    if (!net || N <= 0) return 0;
+    return slot_offset(net, (int)net->slot_bytes_per_image.size(), N);
+}
+
+int32_t hawq_net_num_steps(const hawq_net *net) { return net ? (int32_t)net->steps.size() : 0; }
+
+hawq_status hawq_net_step_output(const hawq_net *net, int32_t N, int32_t step, char *name, size_t *offset, size_t *bytes,
+                                 int32_t *dtype, int32_t *dims4) {
+    if (!net || !name || !offset || !bytes || !dtype || !dims4) return HAWQ_ERR_NULL;
+    if (step < 0 || step >= (int)net->steps.size() || N <= 0) return HAWQ_ERR_RANGE;
+    const Step &st = net->steps[step];
+    snprintf(name, 24, "%s", st.name.c_str());
+    if (st.out < 0) {  // fc: the caller's logits
+        *offset = 0; *bytes = 0; *dtype = HAWQ_S32;
+        dims4[0] = N; dims4[1] = 1; dims4[2] = 1; dims4[3] = net->classes;
+        return HAWQ_OK;
+    }
+    const Tensor &t = net->tensors[st.out];
+    *offset = slot_offset(net, t.slot, N);
+    *bytes = (size_t)tensor_bytes(t.elems_per_image * N, t.dt);
+    *dtype = t.dt;
+    dims4[0] = N; dims4[1] = t.dims[0]; dims4[2] = t.dims[1]; dims4[3] = t.dims[2];
+    return HAWQ_OK;
+}
+
+hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, double *macs, double *bytes) {
+    if (!net || !macs || !bytes) return HAWQ_ERR_NULL;
+    if (step < 0 || step >= (int)net->steps.size() || N <= 0) return HAWQ_ERR_RANGE;
+    const Step &st = net->steps[step];
+    *macs = st.macs_per_image * N;
+    *bytes = st.bytes_per_image * N + st.bytes_fixed;
+    return HAWQ_OK;
+}
+
+static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
+                               size_t workspace_bytes, hipStream_t stream, hipEvent_t *ev) {
+    if (!net || !x || !logits || !workspace) return HAWQ_ERR_NULL;
+    if (N <= 0) return HAWQ_ERR_SHAPE;
+    if (workspace_bytes < hawq_net_workspace_bytes(net, N)) return HAWQ_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 255) return HAWQ_ERR_UNSUPPORTED;
+    uint8_t *ws = (uint8_t *)workspace;
+    auto tptr = [&](int t) -> uint8_t * { return ws + slot_offset(net, net->tensors[t].slot, N); };
+    for (size_t s = 0; s < net->steps.size(); ++s) {
+        const Step &st = net->steps[s];
+        if (ev && hipEventRecord(ev[2 * s], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+        hawq_status rc = HAWQ_OK;
+        const uint8_t *in = st.in >= 0 ? tptr(st.in) : (const uint8_t *)x;
+        uint8_t *outp = st.out >= 0 ? tptr(st.out) : (uint8_t *)logits;
+        switch (st.kind) {
+        case STEP_STEM:
+        case STEP_CONV:
+        case STEP_FC: {
+            hawq_conv_desc d = st.desc;
+            if (st.kind == STEP_FC) { d.W = N; } else { d.N = N; }
+            ConvArgs a;
+            int x_hi;
+            const uint8_t *res = st.res >= 0 ? tptr(st.res) : nullptr;
+            const bool raw = st.kind == STEP_FC;
+            rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
+                                outp, true, a, x_hi);
+            if (rc == HAWQ_OK) rc = dispatch_conv(a, x_hi, stream);
+            break;
+        }
+        case STEP_MAXPOOL:
+            rc = launch_maxpool(N, st.desc.H, st.desc.W, st.desc.C, st.desc.x_dtype, st.desc.y_dtype, in, st.desc.y_lo,
+                                st.desc.y_hi, outp, stream);
+            break;
+        case STEP_AVGPOOL:
+            rc = launch_avgpool(N, st.desc.H * st.desc.W, st.desc.C, st.desc.x_dtype, st.desc.y_dtype, in, st.b, st.c,
+                                st.desc.y_lo, st.desc.y_hi, outp, stream);
+            break;
+        }
+        if (rc != HAWQ_OK) return rc;
+        if (ev && hipEventRecord(ev[2 * s + 1], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+    }
+    return HAWQ_OK;
+}
+
+hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
+                                size_t workspace_bytes, void *stream) {
+    return run_forward(net, x, N, logits, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+hawq_status hawq_forward_resnet_timed(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
+                                      size_t workspace_bytes, void *stream, float *step_ms) {
+    if (!net || !step_ms) return HAWQ_ERR_NULL;
+    const size_t ns = net->steps.size();
+    std::vector<hipEvent_t> ev(2 * ns);
+    for (auto &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return HAWQ_ERR_DEVICE;
+    hawq_status rc = run_forward(net, x, N, logits, workspace, workspace_bytes, (hipStream_t)stream, ev.data());
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess && rc == HAWQ_OK) rc = HAWQ_ERR_DEVICE;
+    if (rc == HAWQ_OK)
+        for (size_t s = 0; s < ns; ++s)
+            if (hipEventElapsedTime(&step_ms[s], ev[2 * s], ev[2 * s + 1]) != hipSuccess) rc = HAWQ_ERR_DEVICE;
+    for (auto &e : ev) (void)hipEventDestroy(e);
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,157 @@
+"""GPU parity: hawq_conv2d_int / hawq_gemm_int through the C interface vs the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hawq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2011_10680_amd as h
+    h.load_library()
+    return h
+
+
+def _scale_c(case, bits):
+    """Replace the literal shift distribution by one centred on the accumulator spread so outputs
+    are spread over the clamp range (keeps b per channel, c per channel jittered by 0/1)."""
+    import math
+    kdim = case["R"] * case["S"] * case["C"]
+    hi, wm = (127, 127) if bits == 8 else (15, 7)
+    sigma = math.sqrt(kdim * (hi * hi / 3.0) * (wm * (wm + 1) / 3.0)) + 1
+    c0 = int(math.floor(math.log2(1.5 * (1 << 14) / ((hi / 3.0) / sigma))))
+    g = np.random.default_rng(case["K"] + kdim)
+    case["c"] = (c0 + g.integers(0, 2, size=case["K"])).astype(np.uint8)
+    case["bias"] = np.rint(sigma * g.uniform(-0.5, 0.5, size=case["K"])).astype(np.int32)
+    return case
+
+
+def test_config0_single_conv_literal(hawq):
+    """The single-layer configuration exactly as specified (56x56x64 -> 64, 3x3, literal b/c/bias draws)."""
+    from gpu_util import run_conv_gpu, assert_same
+    case = wl.conv_case(seed=1000, N=1, H=56, W=56, C=64, K=64, R=3, S=3, stride=1, pad=1, bits=8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, x_hi=127)
+    assert_same(got, want, "config 0")
+
+
+# (N, H, W, C, K, R, S, stride, pad): several tiles plus ragged pixel and channel tails
+_SHAPES8 = [
+    (1, 56, 56, 64, 64, 3, 3, 1, 1),
+    (3, 13, 13, 64, 64, 3, 3, 1, 1),      # 507 pixels: ragged last pixel tile
+    (2, 13, 11, 128, 192, 3, 3, 2, 1),    # K not a multiple of 128
+    (2, 15, 15, 64, 80, 1, 1, 1, 0),      # K % 64 != 0, K % 16 == 0
+    (2, 9, 9, 64, 72, 1, 1, 1, 0),        # K % 16 != 0: element-wise epilogue
+    (5, 14, 14, 256, 64, 1, 1, 2, 0),     # strided 1x1
+    (1, 10, 12, 192, 96, 5, 3, 1, 2),     # non-square window, pad 2
+    (8, 64, 64, 64, 256, 1, 1, 1, 0),     # 512 tiles of 128x128: the large-tile kernel
+    (16, 64, 64, 64, 64, 3, 3, 1, 1),     # 512 tiles of 64x128: the K=64 kernel
+    (1, 7, 7, 512, 512, 3, 3, 1, 1),      # small M, deep K
+]
+
+
+@pytest.mark.parametrize("shape", _SHAPES8)
+def test_int8_conv_shapes(hawq, shape):
+    from gpu_util import run_conv_gpu, assert_same
+    N, H, W, C, K, R, S, stride, pad = shape
+    case = _scale_c(wl.conv_case(seed=sum(shape), N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=8), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, x_hi=127)
+    assert_same(got, want, str(shape))
+    assert 0.05 < (want > 0).mean() and (want == 127).mean() < 0.5
+
+
+@pytest.mark.parametrize("res_signed,y_dt,relu,lo,hi", [(False, 0, 1, 0, 127), (True, 0, 1, 0, 127), (True, 1, 0, -128, 127),
+                                                         (False, 4, 0, -100000, 100000), (False, 2, 1, 0, 15)])
+def test_int8_conv_residual_and_output_types(hawq, res_signed, y_dt, relu, lo, hi):
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=77, N=2, H=14, W=14, C=128, K=256, R=1, S=1, stride=1, pad=0, bits=8,
+                                 with_residual=True, res_signed=res_signed), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, y_dt, res_dt=hawq.S8 if res_signed else hawq.U8, relu=relu,
+                             y_lo=lo, y_hi=hi, x_hi=127)
+    assert_same(got, want)
+
+
+def test_raw_int32_accumulator_output(hawq):
+    from gpu_util import run_conv_gpu, assert_same
+    case = wl.conv_case(seed=5, N=2, H=8, W=8, C=64, K=48, R=3, S=3, stride=1, pad=1, bits=8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.S32, raw=True, y_lo=0, y_hi=0, x_hi=127)
+    assert_same(got, want)
+
+
+_SHAPES4 = [(n, N, H, W, C, K, R, S, st, pd) for (n, N, H, W, C, K, R, S, st, pd) in wl.int4_sweep_shapes(batch=2)]
+
+
+@pytest.mark.parametrize("shape", _SHAPES4, ids=[s[0] for s in _SHAPES4])
+def test_int4_sweep_shapes_small_batch(hawq, shape):
+    """ResNet18-shaped INT4 sweep (packed operands, packed output) at batch 2, centred scales."""
+    from gpu_util import run_conv_gpu, assert_same
+    name, N, H, W, C, K, R, S, stride, pad = shape
+    case = _scale_c(wl.conv_case(seed=len(name), N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=4), 4)
+    got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, y_hi=15)
+    assert_same(got, want, name)
+    v = oracle.unpack(want, oracle.U4)
+    assert 0.05 < (v > 0).mean() and (v == 15).mean() < 0.5
+
+
+@pytest.mark.parametrize("shape", [s for s in wl.int4_sweep_shapes(batch=8)], ids=[s[0] for s in wl.int4_sweep_shapes(batch=8)])
+def test_config1_int4_sweep_literal(hawq, shape):
+    """The INT4 sweep configuration as specified: batch 8, literal (b, c, bias) draws, clamp 0..15."""
+    from gpu_util import run_conv_gpu, assert_same
+    name, N, H, W, C, K, R, S, stride, pad = shape
+    case = wl.conv_case(seed=1001, N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=4)
+    got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, y_hi=15)
+    assert_same(got, want, name)
+
+
+def test_int4_conv_residual_u4_and_8bit_output(hawq):
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=9, N=2, H=14, W=14, C=64, K=128, R=3, S=3, stride=1, pad=1, bits=4, with_residual=True), 4)
+    got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, res_dt=hawq.U4, y_hi=15)
+    assert_same(got, want)
+    # 4-bit layer feeding an 8-bit consumer
+    case["c"] = (case["c"].astype(np.int32) - 3).astype(np.uint8)
+    got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U8, res_dt=hawq.U4, y_hi=127)
+    assert_same(got, want)
+
+
+@pytest.mark.parametrize("shape", [(2, 20, 20, 3, 64, 7, 7, 2, 3), (1, 9, 9, 24, 10, 3, 3, 1, 1), (2, 6, 6, 64, 32, 1, 1, 1, 0)])
+def test_direct_kernel_shapes_and_full_range_u8(hawq, shape):
+    """Shapes the matrix-core kernel does not take: C not a multiple of 64, and unsigned inputs up to 255."""
+    from gpu_util import run_conv_gpu, assert_same
+    N, H, W, C, K, R, S, stride, pad = shape
+    case = _scale_c(wl.conv_case(seed=3, N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=8), 8)
+    g = np.random.default_rng(1)
+    case["x"] = g.integers(0, 256, size=case["x"].shape, dtype=np.uint8)   # full unsigned range
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, x_hi=0)
+    assert_same(got, want, str(shape))
+
+
+def test_empty_batch_and_errors(hawq):
+    import torch
+    d = hawq.ConvDesc(N=0, H=8, W=8, C=64, K=64, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, x_dtype=hawq.U8,
+                      w_dtype=hawq.S8, y_dtype=hawq.U8, res_dtype=hawq.U8, relu=1, y_lo=0, y_hi=127, x_hi=127)
+    z8 = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    z32 = torch.zeros(64, dtype=torch.int32, device="cuda")
+    hawq.hawq_conv2d_int(d, z8, z8, z32, z32, z8, None, None, None, z8)   # N = 0: nothing to do
+    torch.cuda.synchronize()
+
+
+def test_gemm_fc_shape(hawq):
+    """The last layer: [N,2048] x [1000,2048]^T -> raw INT32 logits (1000 is not a multiple of 16)."""
+    import torch
+    from gpu_util import to_dev, assert_same
+    g = np.random.default_rng(12)
+    M, N, K = 37, 1000, 2048
+    x = g.integers(0, 128, size=(M, K), dtype=np.uint8)
+    w = g.integers(-127, 128, size=(N, K)).astype(np.int8)
+    bias = g.integers(-(1 << 15), 1 << 15, size=N).astype(np.int32)
+    y = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    hawq.hawq_gemm_int(M, N, K, hawq.U8, hawq.S8, hawq.S32, to_dev(x), to_dev(w), to_dev(bias), None, None, 0, 0, 0, y)
+    torch.cuda.synchronize()
+    want = oracle.gemm_int(x, w, bias, None, None, M=M, N=N, K=K, x_dt=oracle.U8, w_dt=oracle.S8, y_dt=oracle.S32)
+    assert_same(y.cpu().numpy(), want)
+    assert np.array_equal(want.astype(np.int64), x.astype(np.int64) @ w.astype(np.int64).T + bias)

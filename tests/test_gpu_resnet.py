@@ -1,0 +1,64 @@
+"""GPU parity: hawq_forward_resnet vs the oracle's network walk, every stored tensor and the INT32 logits."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import resnet as onet
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hawq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2011_10680_amd as h
+    h.load_library()
+    return h
+
+
+def _forward_gpu(hawq, net, x, keep):
+    import torch
+    N = x.shape[0]
+    hn = hawq.HawqNet(net["arch"], net["layers"], net["pool_b"], net["pool_c"], image_hw=net["image_hw"],
+                      num_classes=net["num_classes"], keep_activations=keep)
+    ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((N, net["num_classes"]), dtype=torch.int32, device="cuda")
+    xd = torch.from_numpy(x).cuda()
+    hn.hawq_forward_resnet(xd, N, logits, ws)
+    torch.cuda.synchronize()
+    acts = {}
+    if keep:
+        wsh = ws.cpu().numpy()
+        for s in range(hn.num_steps()):
+            o = hn.step_output(N, s)
+            if o["bytes"]:
+                acts[o["name"]] = (wsh[o["offset"]:o["offset"] + o["bytes"]], o["dtype"], o["dims"])
+    out = logits.cpu().numpy()
+    hn.close()
+    return out, acts
+
+
+@pytest.mark.parametrize("arch,mixed,N", [(18, False, 2), (50, False, 2), (18, True, 2), (50, True, 3)])
+def test_layerwise_and_logits(hawq, arch, mixed, N):
+    """Every layer's stored activation (as the paper's deployment check compares layer by layer) and
+    the final INT32 logits are identical to the oracle's."""
+    bits = wl.draw_bits(arch, 4000 + arch) if mixed else None
+    net = wl.make_resnet(arch, seed=1000 + arch, bits=bits)
+    x = wl.make_image_batch(7, N)
+    keep = {}
+    want = onet.forward(net, x, keep)
+    got, acts = _forward_gpu(hawq, net, x, True)
+    assert set(acts) == set(keep) - {"fc"}
+    for name, (raw, dt, dims) in acts.items():
+        w = np.ascontiguousarray(keep[name]).view(np.uint8).ravel()
+        assert raw.size == w.size, (name, raw.size, w.size, dims)
+        if not np.array_equal(raw, w):
+            bad = np.flatnonzero(raw != w)
+            raise AssertionError("%s: %d of %d bytes differ, first at %d (gpu %d, oracle %d)" % (
+                name, bad.size, w.size, bad[0], raw[bad[0]], w[bad[0]]))
+    assert np.array_equal(got, want)
+    # reusing workspace slots must not change anything
+    got2, _ = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got2, want)
