@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer-only inference hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--report FILE]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input.  The default
+workload is the one the headline metric is quoted on: the full ResNet50 integer-only forward,
+all layers INT8, batch 128 (3x224x224 uint8 images), random seeded folded weights.  Inputs and
+weights are resident in HBM before the timed region.  Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5033.0     # MI355X dense INT8 MFMA, published (5.0 POP/s)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+WORKLOADS = {
+    "resnet50_int8_b128": dict(arch=50, batch=128, mixed=False, seed=1003),
+    "resnet18_int8_b64": dict(arch=18, batch=64, mixed=False, seed=1002),
+    "resnet50_mixed_b256": dict(arch=50, batch=256, mixed=True, seed=1004),
+    "resnet50_int4_b128": dict(arch=50, batch=128, mixed="all4", seed=1005),
+}
+
+
+def cpu_baseline(net, images):
+    """Time the CPU oracle (as it stands) on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from oracle import resnet as onet
+    import workloads as wl
+    oracle.lib()
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    x = wl.make_image_batch(99, images, image_hw=net["image_hw"])
+    onet.forward(net, x[:1])  # page in
+    t0 = time.perf_counter()
+    onet.forward(net, x)
+    dt = time.perf_counter() - t0
+    return dict(value=images / dt, unit="images/s", cores=cores, kind="oracle",
+                sample="%d images of the same network and input distribution, %.1f s" % (images, dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50_int8_b128", choices=sorted(WORKLOADS))
+    ap.add_argument("--cpu-images", type=int, default=48, help="images in the CPU-oracle baseline sample (0: skip)")
+    ap.add_argument("--report", default=None, help="optional file for the per-layer table (JSON)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path shards by batch with no exchange; "
+              "see DESIGN.md) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2011_10680_amd as hawq
+
+    hawq.load_library()   # fails loudly if libhawq.so is not built: there is no fallback path
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wk = WORKLOADS[args.workload]
+    arch, N = wk["arch"], wk["batch"]
+    if wk["mixed"] == "all4":
+        bits = {g: (8 if g in ("conv1", "fc") else 4) for g in wl.resnet_group_names(arch)}
+    elif wk["mixed"]:
+        bits = wl.draw_bits(arch, 4000 + arch)
+    else:
+        bits = None
+    net = wl.make_resnet(arch, seed=wk["seed"], bits=bits)
+    x = torch.from_numpy(wl.make_image_batch(wk["seed"] + 1, N)).cuda()
+    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
+    ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((N, 1000), dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    for _ in range(args.warmup):
+        hn.hawq_forward_resnet(x, N, logits, ws, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        hn.hawq_forward_resnet(x, N, logits, ws, stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-launch device times (HIP events recorded by the library on the same stream), median of a few passes
+    reps = max(3, min(10, args.steps))
+    per = np.array([hn.hawq_forward_resnet_timed(x, N, logits, ws, stream) for _ in range(reps)])
+    step_ms = np.median(per, axis=0)
+    nsteps = hn.num_steps()
+    rows = []
+    for s in range(nsteps):
+        macs, nbytes = hn.step_cost(N, s)
+        o = hn.step_output(N, s)
+        rows.append(dict(step=s, name=o["name"], ms=float(step_ms[s]), gmac=macs / 1e9, mbytes=nbytes / 1e6,
+                         tops=2 * macs / (step_ms[s] * 1e-3) / 1e12 if macs else 0.0,
+                         gbs=nbytes / (step_ms[s] * 1e-3) / 1e9))
+    total_macs = sum(r["gmac"] for r in rows) * 1e9
+    conv_rows = [r for r in rows if r["gmac"] > 0 and r["name"] not in ("conv1", "fc")]
+    conv_ms = sum(r["ms"] for r in conv_rows)
+    conv_bytes = sum(r["mbytes"] for r in conv_rows) * 1e6
+    conv_ops = 2 * sum(r["gmac"] for r in conv_rows) * 1e9
+    # Roofline of the dominant kernel (the matrix-core convolution, all its launches of one forward):
+    # with every layer reading its input and writing its output once the ResNet50 forward moves more
+    # bytes-time than MFMA-time on this chip, so the bound is HBM.
+    t_mem = conv_bytes / (PEAK_HBM_GBS * 1e9)
+    t_mfma = conv_ops / (PEAK_INT8_TOPS * 1e12)
+    achieved_gbs = conv_bytes / (conv_ms * 1e-3) / 1e9
+    achieved_tops = conv_ops / (conv_ms * 1e-3) / 1e12
+    if t_mem >= t_mfma:
+        roof = dict(bound="hbm", achieved=achieved_gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=achieved_gbs / PEAK_HBM_GBS)
+    else:
+        roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
+    roof.update(traffic=None, kernel="conv_mfma_kernel (all %d launches of one forward)" % len(conv_rows),
+                launches_ms=conv_ms, mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
+                hbm_gbs=achieved_gbs, hbm_frac=achieved_gbs / PEAK_HBM_GBS)
+
+    out = {
+        "metric": "resnet%d_int_only_images_per_sec" % arch, "value": N / (ms_per_step * 1e-3), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8" if not wk["mixed"] else "int4/int8", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": N, "image": "3x224x224 uint8",
+                   "layers_int4": sum(l["bits"] == 4 for l in net["layers"])},
+        "tops": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
+        "frac_int8_mfma_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+        "sum_kernel_ms": float(step_ms.sum()),
+        "roofline": roof,
+    }
+    if args.cpu_images > 0:
+        out["cpu_baseline"] = cpu_baseline(net, args.cpu_images)
+    if args.report:
+        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+        with open(args.report, "w") as f:
+            json.dump(dict(summary=out, layers=rows), f, indent=1)
+    hn.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

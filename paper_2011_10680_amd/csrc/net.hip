@@ -13,6 +13,8 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
                            const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,
                            bool check_pointers, ConvArgs &a, int &x_hi_out);
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s);
+void stem_pack_weights(const int8_t *w, int8_t *out);
+bool conv_stem_eligible(const ConvArgs &a);
 }  // namespace hawq
 
 using namespace hawq;
@@ -81,6 +83,8 @@ struct Step {
     int in = -1, res = -1, out = -1;  // tensor ids (-1: external image / logits)
     hawq_conv_desc desc{};        // N filled per call
     const uint8_t *w = nullptr;   // device parameter pointers
+    const uint8_t *w_stem = nullptr;      // conv1 only: weights re-tiled for the stem kernel
+    const int32_t *bias_stem = nullptr;   //             bias + 128 * sum(w) (input offset correction)
     const int32_t *bias = nullptr, *b = nullptr, *res_b = nullptr;
     const uint8_t *c = nullptr, *res_c = nullptr;
     double macs_per_image = 0, bytes_per_image = 0, bytes_fixed = 0;
@@ -219,6 +223,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         off[i].rc = take((size_t)L[i].K);
     }
     const size_t off_pb = take(4 * (size_t)c_last), off_pc = take((size_t)c_last);
+    const size_t off_ws = take(64 * 256), off_bs = take(4 * 64);
     std::vector<uint8_t> host(total, 0);
     for (int i = 0; i < nl; ++i) {
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
@@ -231,6 +236,16 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         if (L[i].has_residual) {
             memcpy(&host[off[i].rb], lp[i].res_b, 4 * (size_t)L[i].K);
             memcpy(&host[off[i].rc], lp[i].res_c, (size_t)L[i].K);
+        }
+    }
+    {   // conv1 for the stem kernel: re-tiled weights, bias corrected for the -128 input offset
+        const int8_t *w0 = (const int8_t *)lp[0].w;
+        stem_pack_weights(w0, (int8_t *)&host[off_ws]);
+        int32_t *bs = (int32_t *)&host[off_bs];
+        for (int k = 0; k < 64; ++k) {
+            int64_t sum = 0;
+            for (int i = 0; i < 147; ++i) sum += w0[k * 147 + i];
+            bs[k] = (int32_t)(lp[0].bias[k] + 128 * sum);
         }
     }
     memcpy(&host[off_pb], pool_b, 4 * (size_t)c_last);
@@ -286,6 +301,8 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     int li = 0;
     int stage_bits = reader_bits_after(0);
     int t = conv_step(0, -1, HAWQ_U8, 255, -1, HAWQ_U8, stage_bits, false, true);
+    net->steps[0].w_stem = A + off_ws;
+    net->steps[0].bias_stem = (const int32_t *)(A + off_bs);
     {
         Step st;
         st.kind = STEP_MAXPOOL; st.name = "pool"; st.in = t;
@@ -429,7 +446,15 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
             const bool raw = st.kind == STEP_FC;
             rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
                                 outp, true, a, x_hi);
-            if (rc == HAWQ_OK) rc = dispatch_conv(a, x_hi, stream);
+            if (rc == HAWQ_OK) {
+                if (st.kind == STEP_STEM && conv_stem_eligible(a)) {
+                    a.w = st.w_stem;
+                    a.bias = st.bias_stem;
+                    rc = launch_conv_stem(a, stream);
+                } else {
+                    rc = dispatch_conv(a, x_hi, stream);
+                }
+            }
             break;
         }
         case STEP_MAXPOOL:
