@@ -35,6 +35,8 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     static_assert(BC % (WC * 32) == 0 && BP % (WP * 32) == 0, "tile shape");
 
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][(BC + BP) * 64];
+    __shared__ ChanMain par_m[BC];
+    __shared__ ChanRes par_r[BC];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -176,8 +178,12 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
 
     gload(0);
+    // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
+    const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
+    int wide = 0;
+    if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
     lstore(0);
-    __syncthreads();
+    wide = __syncthreads_or(wide);
     for (int step = 0; step < steps; ++step) {
         const int cur = step & 1;
         if (step + 1 < steps) gload(step + 1);
@@ -200,8 +206,20 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     }
 
     // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
-    const int ch0 = k0 + wc * (BC / WC) + khalf * 16 * TC;
+    const int chl = wc * (BC / WC) + khalf * 16 * TC;
+    const int ch0 = k0 + chl;
     if (ch0 >= a.K) return;
+    if (tile_epi) {
+        int64_t mm[TP];
+        bool valid[TP];
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            mm[tp] = m0 + wp * (BP / WP) + tp * 32 + rho;
+            valid[tp] = mm[tp] < a.M;
+        }
+        epilogue_tile<TC, TP>(a, par_m, par_r, mm, valid, k0, chl, acc, wide);
+        return;
+    }
     static_for<0, TP>([&](auto tpc) {
         constexpr int tp = decltype(tpc)::value;
         const int m = m0 + wp * (BP / WP) + tp * 32 + rho;

@@ -23,6 +23,8 @@ constexpr int STEM_W_BYTES = 64 * 256;
 __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, const int tiles_q, const int tiles_p) {
     __shared__ __attribute__((aligned(16))) uint8_t lw[STEM_W_BYTES];
     __shared__ __attribute__((aligned(16))) uint32_t lx[STEM_ROWS * STEM_COLS];
+    __shared__ ChanMain par_m[64];
+    __shared__ ChanRes par_r[64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int bid = blockIdx.x;
@@ -57,7 +59,10 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, const 
             if (col >= 0 && col < STEM_COLS) lx[rl * STEM_COLS + col] = px[k] ^ 0x00808080u;
         }
     }
-    __syncthreads();
+    const bool tile_epi = a.y_dt != HAWQ_S32;
+    int wide = 0;
+    if (tile_epi) wide = stage_params(a, 0, 64, par_m, par_r);
+    wide = __syncthreads_or(wide);
 
     // ---- MFMA: wave w owns output rows 4w..4w+3 of the tile (2 pixel tiles of 2 rows x 16 cols) ----
     const int rho = lane & 31, khalf = lane >> 5;
@@ -101,6 +106,18 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, const 
     }
 
     const int ch0 = khalf * 32;
+    if (tile_epi) {
+        int64_t mm[2];
+        bool valid[2];
+#pragma unroll
+        for (int tp = 0; tp < 2; ++tp) {
+            const int p = p0 + wave * 4 + tp * 2 + (rho >> 4), q = q0 + (rho & 15);
+            valid[tp] = p < a.P && q < a.Q;
+            mm[tp] = ((int64_t)n * a.P + p) * a.Q + q;
+        }
+        epilogue_tile<2, 2>(a, par_m, par_r, mm, valid, 0, ch0, acc, wide);
+        return;
+    }
     static_for<0, 2>([&](auto tpc) {
         constexpr int tp = decltype(tpc)::value;
         const int p = p0 + wave * 4 + tp * 2 + (rho >> 4), q = q0 + (rho & 15);

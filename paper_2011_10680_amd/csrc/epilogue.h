@@ -144,4 +144,136 @@ __device__ __forceinline__ void epilogue_pixel(const ConvArgs &a, int64_t m, int
     });
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Tile epilogue with per-channel parameters staged in LDS (the hot variant).
+//
+// stage_params() runs once per workgroup: thread i < n_ch prepares channel k0+i as
+//     main: { b, c, R = bias*b + 2^(c-1) (int64) }         so that  rq(acc+bias) = (acc*b + R) >> c
+//     res : { rb, rc, 2^(rc-1) }
+// and reports whether every channel of the workgroup allows the narrow evaluation:
+//     main: c <= 31 and b < 2^c      -> the requantised value fits int32; the 64-bit product is
+//                                        shifted with one funnel shift of its two halves
+//     res : rc <= 31 and rb < 2^22   -> |r| <= 255 keeps r*rb + 2^(rc-1) inside int32
+// Otherwise the workgroup takes the wide path: full 64-bit shift and 64-bit clamp.  Both paths
+// compute the same exact integer.
+struct ChanMain { int32_t b, c; int64_t R; };
+struct ChanRes { int32_t rb, rc, rround, pad; };
+
+__device__ __forceinline__ int stage_params(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanRes *pr) {
+    int wide = 0;
+    const int i = threadIdx.x;
+    if (i < n_ch && a.b != nullptr) {
+        const int k = k0 + i;
+        ChanMain m = {0, 1, 0};
+        ChanRes r = {0, 1, 1, 0};
+        if (k < a.K) {
+            m.b = a.b[k]; m.c = a.c[k];
+            m.R = (int64_t)a.bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
+            if (m.c > 31 || ((uint32_t)m.b >> m.c) != 0) wide = 1;
+            if (a.res != nullptr) {
+                r.rb = a.res_b[k]; r.rc = a.res_c[k];
+                if (r.rc > 31 || r.rb >= (1 << 22)) wide = 1;
+                r.rround = (int32_t)(1u << ((r.rc - 1) & 31));
+            }
+        }
+        pm[i] = m;
+        pr[i] = r;
+    }
+    return wide;
+}
+
+// Epilogue of one lane: TP pixels (m[tp], valid[tp]) x TC*16 consecutive channels starting at
+// workgroup-relative channel `chl` (absolute ch0 = k0 + chl).  8-bit or packed 4-bit outputs,
+// requantising, vector stores; requires K % 16 == 0.
+template <int TC, int TP>
+__device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
+                                              const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide) {
+    // uniform run-time flags, tested per 4-channel group: four specialised copies of this body would
+    // let the compiler hoist their common 64-bit products above the selection and hold all of them live
+    const bool FAST = !wide, HAS_RES = a.res != nullptr;
+    const int y_dt = a.y_dt, res_dt = a.res_dt;
+    const bool y4 = is4(y_dt), r4 = is4(res_dt), rsigned = (res_dt == HAWQ_S8 || res_dt == HAWQ_S4);
+    const int32_t lo = a.lo, hi = a.hi;
+    static_for<0, TC>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        const int chg = k0 + chl + 16 * g;
+        if (chg >= a.K) return;
+        // shortcut bytes of the 16 channels for every pixel of the lane
+        uint32_t rw[TP][4];
+        if (HAS_RES) {
+            static_for<0, TP>([&](auto tpc) {
+                constexpr int tp = decltype(tpc)::value;
+                rw[tp][0] = rw[tp][1] = rw[tp][2] = rw[tp][3] = 0;
+                if (valid[tp]) {
+                    const int64_t o = m[tp] * (int64_t)a.K + chg;
+                    if (r4) {
+                        const uint2 t = *(const uint2 *)(a.res + (o >> 1));
+                        rw[tp][0] = t.x & 0xffff; rw[tp][1] = t.x >> 16; rw[tp][2] = t.y & 0xffff; rw[tp][3] = t.y >> 16;
+                    } else {
+                        const uint4 t = *(const uint4 *)(a.res + o);
+                        rw[tp][0] = t.x; rw[tp][1] = t.y; rw[tp][2] = t.z; rw[tp][3] = t.w;
+                    }
+                }
+            });
+        }
+        uint32_t ow[TP][4];
+        static_for<0, TP>([&](auto tpc) { constexpr int tp = decltype(tpc)::value; ow[tp][0] = ow[tp][1] = ow[tp][2] = ow[tp][3] = 0; });
+        static_for<0, 4>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            // parameters of 4 channels at a time; the scheduling fence keeps the compiler from
+            // hoisting all 16 channels' LDS reads at once (register pressure)
+            ChanMain pmv[4];
+            ChanRes prv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pmv[j] = pm[chl + 16 * g + 4 * q + j];
+                if (HAS_RES) prv[j] = pr[chl + 16 * g + 4 * q + j];
+            }
+            static_for<0, TP>([&](auto tpc) {
+                constexpr int tp = decltype(tpc)::value;
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    constexpr int dummy = 0; (void)dummy;
+                    const int64_t v = (int64_t)acc[tp][g][4 * q + j] * (int64_t)pmv[j].b + pmv[j].R;
+                    int32_t r = 0;
+                    if (HAS_RES) {
+                        const uint32_t w = rw[tp][q];
+                        if (r4) {
+                            r = (int32_t)((w >> (4 * j)) & 0xf);
+                            if (rsigned) r = (r ^ 8) - 8;
+                        } else {
+                            r = rsigned ? (int32_t)(int8_t)((w >> (8 * j)) & 0xff) : (int32_t)((w >> (8 * j)) & 0xff);
+                        }
+                    }
+                    int32_t y;
+                    if (FAST) {
+                        y = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(v >> 32), (uint32_t)v, (uint32_t)pmv[j].c);
+                        if (HAS_RES) y += (__mul24(r, prv[j].rb) + prv[j].rround) >> prv[j].rc;
+                        y = y < lo ? lo : y;
+                        y = y > hi ? hi : y;
+                    } else {
+                        int64_t w64 = v >> pmv[j].c;
+                        if (HAS_RES) w64 += rq64(r, prv[j].rb, prv[j].rc);
+                        y = clamp64(w64, lo, hi);
+                    }
+                    if (y4) packed |= (uint32_t)(y & 0xf) << (4 * j);
+                    else packed |= (uint32_t)(y & 0xff) << (8 * j);
+                }
+                if (y4) ow[tp][q >> 1] |= packed << (16 * (q & 1));
+                else ow[tp][q] = packed;
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, TP>([&](auto tpc) {
+            constexpr int tp = decltype(tpc)::value;
+            if (!valid[tp]) return;
+            const int64_t o = m[tp] * (int64_t)a.K + chg;
+            if (y4) *(uint2 *)(a.y + (o >> 1)) = make_uint2(ow[tp][0], ow[tp][1]);
+            else *(uint4 *)(a.y + o) = make_uint4(ow[tp][0], ow[tp][1], ow[tp][2], ow[tp][3]);
+        });
+    });
+}
+
 }  // namespace hawq
