@@ -215,6 +215,11 @@ hawq_status hawq_forward_resnet_timed(const hawq_net *net, const void *x, int32_
  * (input once + weights + parameters + output once + shortcut once) at batch N. */
 hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, double *macs, double *bytes);
 
+/* Measurement hook for tile-shape sweeps: 0 = the built-in heuristic (default), 1..3 = force one of the
+ * matrix-core kernel's workgroup tiles (128x128, 64x128, 64x64 channels x pixels) for every later call
+ * in this process.  Results are identical for every setting. */
+void hawq_tune_set_tile(int32_t tile);
+
 const char *hawq_status_string(hawq_status s);
 
 #ifdef __cplusplus

@@ -80,6 +80,8 @@ def load_library():
     lib.hawq_forward_resnet.argtypes = [vp, vp, i32, vp, vp, sz, vp]
     lib.hawq_forward_resnet_timed.restype = ctypes.c_int
     lib.hawq_forward_resnet_timed.argtypes = [vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.hawq_tune_set_tile.restype = None
+    lib.hawq_tune_set_tile.argtypes = [i32]
     lib.hawq_status_string.restype = ctypes.c_char_p
     lib.hawq_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -134,6 +136,10 @@ def hawq_avgpool_int(N, H, W, C, x_dt, y_dt, x, b, c, y_lo, y_hi, y, stream=None
 def hawq_maxpool_int(N, H, W, C, x_dt, y_dt, x, y_lo, y_hi, y, stream=None):
     _check(load_library().hawq_maxpool_int(N, H, W, C, x_dt, y_dt, _p(x), y_lo, y_hi, _p(y), _stream(stream)),
            "hawq_maxpool_int")
+
+
+def hawq_tune_set_tile(tile):
+    load_library().hawq_tune_set_tile(int(tile))
 
 
 def hawq_net_num_layers(arch):

@@ -177,6 +177,8 @@ hawq_status hawq_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t
     return launch_maxpool(N, H, W, C, x_dt, y_dt, x, y_lo, y_hi, y, (hipStream_t)stream);
 }
 
+void hawq_tune_set_tile(int32_t tile) { set_tile_override(tile); }
+
 const char *hawq_status_string(hawq_status s) {
     switch (s) {
     case HAWQ_OK: return "ok";

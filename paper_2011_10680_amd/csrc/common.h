@@ -85,6 +85,7 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks) {
 // ---- launchers (host) ----
 hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s);     // requires conv_mfma_eligible
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi);
+void set_tile_override(int t);
 hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
 // bias corrected for the -128 input offset by the host (see net.cpp)

@@ -22,8 +22,10 @@ namespace hawq {
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
+// Minimum waves per SIMD the register allocation must leave room for: 2 for the 128x128 tile
+// (64 accumulator registers per lane), 4 for the smaller ones.
 template <int BC, int BP, int WC, int WP, bool INT4>
-__global__ void __launch_bounds__(WC *WP * 64)
+__global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC *BP >= 128 * 128 ? 2 : 4)))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr int T = WC * WP * 64;
     constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
@@ -52,22 +54,30 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
 
     // ---- per-thread load bookkeeping ----
+    // Operands are fetched with buffer loads: a lane whose row is past the tensor edge, or whose
+    // filter tap falls into the zero padding, presents an offset beyond num_records and the
+    // hardware returns zeros -- no branch, no select, and the address is one 32-bit add.
+    constexpr uint32_t kInvalid = 0x80000000u;     // >= any tensor size the interface accepts
+    const __amdgpu_buffer_rsrc_t rsrc_w =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * wrow_bytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.N * a.H * a.W * Cb), 0x00020000);
     int a_row[NA], a_ch[NA];
-    const uint8_t *a_ptr[NA];
-    bool a_ok[NA];
+    uint32_t a_voff[NA];
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
         const int i = tid + j * T;
         a_row[j] = i / CPR;
         a_ch[j] = i % CPR;
         const int k = k0 + a_row[j];
-        a_ok[j] = (i < BC * CPR) && (k < a.K);
-        a_ptr[j] = a.w + (int64_t)(a_ok[j] ? k : 0) * wrow_bytes + a_ch[j] * 16;
+        const bool ok = (i < BC * CPR) && (k < a.K);
+        a_voff[j] = ok ? (uint32_t)(k * (int)wrow_bytes + a_ch[j] * 16) : kInvalid;
     }
     int b_row[NB], b_ch[NB], b_ih0[NB], b_iw0[NB];
-    const uint8_t *b_ptr[NB];
+    uint32_t b_voff[NB];   // offset of tap (0,0), channel chunk 0 (may be "negative" inside the padding)
     bool b_ok[NB];
     const int PQ = a.P * a.Q;
+    const bool padded = (a.pad_h | a.pad_w) != 0;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int i = tid + j * T;
@@ -80,34 +90,42 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         const int p = pq / a.Q, q = pq - p * a.Q;
         b_ih0[j] = p * a.stride_h - a.pad_h;
         b_iw0[j] = q * a.stride_w - a.pad_w;
-        b_ptr[j] = a.x + (int64_t)n * a.H * a.W * Cb + b_ch[j] * 16;
+        b_voff[j] = (uint32_t)(((n * a.H + b_ih0[j]) * a.W + b_iw0[j]) * Cb + b_ch[j] * 16);
+        if (!b_ok[j] && !padded) b_voff[j] = kInvalid;   // unpadded: validity never changes with the tap
     }
 
-    v4i ra[NA], rb[NB];
+    // Two register sets: while K-step t is multiplied out of LDS, step t+1 sits in one set (issued one
+    // iteration ago, written to LDS at the end of this one) and step t+2 is being fetched into the other,
+    // so a global load has two iterations to land.  Loads are issued unconditionally in the steady state
+    // (past the last step they re-read it): under a branch the compiler could not count outstanding loads
+    // and would wait for all of them before every LDS write.
+    v4i ra[2][NA], rb[2][NB];
     int r = 0, s = 0, cc = 0;  // tap and channel chunk of the K-step being *loaded*
-
-    auto gload = [&](int step) {
+    auto gload = [&](int step, auto setc) {
+        constexpr int set = decltype(setc)::value;
+        const int a_soff = min(step, steps - 1) * BKB;                      // uniform -> SGPR offset
+        const int tapoff = (r * a.W + s) * Cb + cc * BKB;                   // uniform
 #pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            v4i v = {0, 0, 0, 0};
-            if (a_ok[j]) v = *(const v4i *)(a_ptr[j] + (int64_t)step * BKB);
-            ra[j] = v;
-        }
+        for (int j = 0; j < NA; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)a_voff[j], a_soff, 0);
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const int ih = b_ih0[j] + r, iw = b_iw0[j] + s;
-            v4i v = {0, 0, 0, 0};
-            if (b_ok[j] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-                v = *(const v4i *)(b_ptr[j] + ((int64_t)ih * a.W + iw) * Cb + cc * BKB);
-            rb[j] = v;
+            uint32_t off = b_voff[j] + (uint32_t)tapoff;
+            if (padded) {
+                const bool ok = b_ok[j] & ((unsigned)(b_ih0[j] + r) < (unsigned)a.H) & ((unsigned)(b_iw0[j] + s) < (unsigned)a.W);
+                off = ok ? off : kInvalid;
+            }
+            rb[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
         }
-        if (++cc == cchunks) {
-            cc = 0;
-            if (++s == a.S) { s = 0; ++r; }
+        if (step + 1 < steps) {
+            if (++cc == cchunks) {
+                cc = 0;
+                if (++s == a.S) { s = 0; ++r; }
+            }
         }
     };
 
-    auto lstore = [&](int buf) {
+    auto lstore = [&](int buf, auto setc) {
+        constexpr int set = decltype(setc)::value;
         uint8_t *la = lds[buf];
         uint8_t *lb = lds[buf] + BC * 64;
 #pragma unroll
@@ -118,7 +136,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 v4i lo, hi;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    uint32_t u = (uint32_t)ra[j][e];
+                    uint32_t u = (uint32_t)ra[set][j][e];
                     uint32_t l = u & 0x0F0F0F0Fu, h = (u >> 4) & 0x0F0F0F0Fu;
                     l |= (l & 0x08080808u) * 0x1Eu;   // sign-extend each nibble to a byte
                     h |= (h & 0x08080808u) * 0x1Eu;
@@ -127,7 +145,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 *(v4i *)(la + row * 64 + (((2 * a_ch[j]) ^ sw) << 4)) = lo;
                 *(v4i *)(la + row * 64 + (((2 * a_ch[j] + 1) ^ sw) << 4)) = hi;
             } else {
-                *(v4i *)(la + row * 64 + ((a_ch[j] ^ sw) << 4)) = ra[j];
+                *(v4i *)(la + row * 64 + ((a_ch[j] ^ sw) << 4)) = ra[set][j];
             }
         }
 #pragma unroll
@@ -138,14 +156,14 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 v4i lo, hi;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    uint32_t u = (uint32_t)rb[j][e];
+                    uint32_t u = (uint32_t)rb[set][j][e];
                     lo[e] = (int)(u & 0x0F0F0F0Fu);
                     hi[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
                 }
                 *(v4i *)(lb + row * 64 + (((2 * b_ch[j]) ^ sw) << 4)) = lo;
                 *(v4i *)(lb + row * 64 + (((2 * b_ch[j] + 1) ^ sw) << 4)) = hi;
             } else {
-                *(v4i *)(lb + row * 64 + ((b_ch[j] ^ sw) << 4)) = rb[j];
+                *(v4i *)(lb + row * 64 + ((b_ch[j] ^ sw) << 4)) = rb[set][j];
             }
         }
     };
@@ -177,17 +195,19 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
 
-    gload(0);
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    gload(0, S0{});
+    gload(1, S1{});
     // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
     if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
-    lstore(0);
+    lstore(0, S0{});
     wide = __syncthreads_or(wide);
-    for (int step = 0; step < steps; ++step) {
-        const int cur = step & 1;
-        if (step + 1 < steps) gload(step + 1);
-        const uint8_t *base = lds[cur];
+
+    auto compute = [&](int buf) {
+        const uint8_t *base = lds[buf];
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             v4i af[TC], bf[TP];
@@ -201,7 +221,17 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 for (int tc = 0; tc < TC; ++tc)
                     acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[tc], bf[tp], acc[tp][tc], 0, 0, 0);
         }
-        if (step + 1 < steps) lstore(cur ^ 1);
+    };
+    // iteration `step` (even: LDS buffer 0, step+1 waits in set 1, step+2 is fetched into set 0)
+    for (int step = 0; step < steps; step += 2) {
+        gload(step + 2, S0{});
+        compute(0);
+        if (step + 1 < steps) lstore(1, S1{});
+        __syncthreads();
+        if (step + 1 >= steps) break;
+        gload(step + 3, S1{});
+        compute(1);
+        if (step + 2 < steps) lstore(0, S0{});
         __syncthreads();
     }
 
@@ -256,16 +286,25 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s) {
     return check_launch();
 }
 
+static int g_tile_override = 0;   // 0: heuristic; 1..3: force a tile shape (measurement hook)
+void set_tile_override(int t) { g_tile_override = t; }
+
 hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     // vector epilogue needs 16-channel groups to be whole and every array 16-byte aligned
     uintptr_t al = (uintptr_t)a.y | (uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.res_b | (uintptr_t)a.res;
     al |= ((uintptr_t)a.c | (uintptr_t)a.res_c) & 3;
     const int vec = (a.K % 16 == 0) && ((al & 15) == 0);
+    if (g_tile_override == 1) return launch_cfg<128, 128, 2, 2>(a, vec, s);
+    if (g_tile_override == 2) return launch_cfg<64, 128, 1, 4>(a, vec, s);
+    if (g_tile_override == 3) return launch_cfg<64, 64, 2, 2>(a, vec, s);
+    // Measured on MI355X over the ResNet layer shapes: deep reductions want the large tile (operand
+    // reuse), shallow ones are latency bound and want many small workgroups in flight.
+    const int64_t kg = (int64_t)a.R * a.S * a.C;
     const int64_t tiles_big = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
-    if (a.K > 64 && tiles_big >= 512) return launch_cfg<128, 128, 2, 2>(a, vec, s);
     const int64_t tiles_mid = (int64_t)((a.K + 63) / 64) * ((a.M + 127) / 128);
-    if (tiles_mid >= 512) return launch_cfg<64, 128, 1, 4>(a, vec, s);
+    if (kg >= 2048 && a.K >= 256 && tiles_big >= 256) return launch_cfg<128, 128, 2, 2>(a, vec, s);
+    if (kg >= 1024 && tiles_mid >= 256) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     return launch_cfg<64, 64, 2, 2>(a, vec, s);
 }
 
