@@ -23,9 +23,9 @@ namespace hawq {
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
 // Minimum waves per SIMD the register allocation must leave room for: 2 for the 128x128 tile
-// (64 accumulator registers per lane), 4 for the smaller ones.
+// (64 accumulator registers per lane), 3 for 64x128, 6 for 64x64 (the latency-bound shapes live on occupancy).
 template <int BC, int BP, int WC, int WP, bool INT4>
-__global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC *BP >= 128 * 128 ? 2 : 4)))
+__global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP >= 128 * 128 ? 2 : (BC * BP >= 64 * 128 ? 3 : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr int T = WC * WP * 64;
     constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
@@ -116,56 +116,51 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             }
             rb[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
         }
-        if (step + 1 < steps) {
-            if (++cc == cchunks) {
-                cc = 0;
-                if (++s == a.S) { s = 0; ++r; }
-            }
-        }
+        // advance to the next K-step without branches (scalar selects); past the last step stay put
+        const int adv = (step + 1 < steps) ? 1 : 0;
+        cc += adv;
+        const int wrap_c = (cc == cchunks) ? 1 : 0;
+        cc = wrap_c ? 0 : cc;
+        s += wrap_c;
+        const int wrap_s = (s == a.S) ? 1 : 0;
+        s = wrap_s ? 0 : s;
+        r += wrap_s;
     };
 
-    auto lstore = [&](int buf, auto setc) {
+    // Write chunk `idx` (0..NA-1: weights, NA..NA+NB-1: pixels) of register set `set` to LDS buffer `buf`.
+    auto lstore_one = [&](int buf, auto setc, auto idxc) {
         constexpr int set = decltype(setc)::value;
-        uint8_t *la = lds[buf];
-        uint8_t *lb = lds[buf] + BC * 64;
+        constexpr int idx = decltype(idxc)::value;
+        constexpr bool isA = idx < NA;
+        constexpr int j = isA ? idx : idx - NA;
+        constexpr int rows = isA ? BC : BP;
+        if ((isA ? NA : NB) * T != rows * CPR && tid + j * T >= rows * CPR) return;
+        uint8_t *base = lds[buf] + (isA ? 0 : BC * 64);
+        int row, ch;
+        v4i v;
+        if constexpr (isA) { row = a_row[j]; ch = a_ch[j]; v = ra[set][j]; }
+        else { row = b_row[j]; ch = b_ch[j]; v = rb[set][j]; }
+        const int sw = swz(row);
+        if (INT4) {
+            v4i lo, hi;
 #pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            if (NA * T != BC * CPR && tid + j * T >= BC * CPR) continue;
-            const int row = a_row[j], sw = swz(row);
-            if (INT4) {
-                v4i lo, hi;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t u = (uint32_t)ra[set][j][e];
-                    uint32_t l = u & 0x0F0F0F0Fu, h = (u >> 4) & 0x0F0F0F0Fu;
-                    l |= (l & 0x08080808u) * 0x1Eu;   // sign-extend each nibble to a byte
+            for (int e = 0; e < 4; ++e) {
+                uint32_t u = (uint32_t)v[e];
+                uint32_t l = u & 0x0F0F0F0Fu, h = (u >> 4) & 0x0F0F0F0Fu;
+                if (isA) {   // weights: sign-extend each nibble to a byte
+                    l |= (l & 0x08080808u) * 0x1Eu;
                     h |= (h & 0x08080808u) * 0x1Eu;
-                    lo[e] = (int)l; hi[e] = (int)h;
                 }
-                *(v4i *)(la + row * 64 + (((2 * a_ch[j]) ^ sw) << 4)) = lo;
-                *(v4i *)(la + row * 64 + (((2 * a_ch[j] + 1) ^ sw) << 4)) = hi;
-            } else {
-                *(v4i *)(la + row * 64 + ((a_ch[j] ^ sw) << 4)) = ra[set][j];
+                lo[e] = (int)l; hi[e] = (int)h;
             }
+            *(v4i *)(base + row * 64 + (((2 * ch) ^ sw) << 4)) = lo;
+            *(v4i *)(base + row * 64 + (((2 * ch + 1) ^ sw) << 4)) = hi;
+        } else {
+            *(v4i *)(base + row * 64 + ((ch ^ sw) << 4)) = v;
         }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            if (NB * T != BP * CPR && tid + j * T >= BP * CPR) continue;
-            const int row = b_row[j], sw = swz(row);
-            if (INT4) {
-                v4i lo, hi;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t u = (uint32_t)rb[set][j][e];
-                    lo[e] = (int)(u & 0x0F0F0F0Fu);
-                    hi[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
-                }
-                *(v4i *)(lb + row * 64 + (((2 * b_ch[j]) ^ sw) << 4)) = lo;
-                *(v4i *)(lb + row * 64 + (((2 * b_ch[j] + 1) ^ sw) << 4)) = hi;
-            } else {
-                *(v4i *)(lb + row * 64 + ((b_ch[j] ^ sw) << 4)) = rb[set][j];
-            }
-        }
+    };
+    auto lstore = [&](int buf, auto setc) {
+        static_for<0, NA + NB>([&](auto ic) { lstore_one(buf, setc, ic); });
     };
 
     // ---- MFMA fragment addresses (loop invariant) ----
@@ -203,36 +198,75 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
     if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
+    // the lane's shortcut bytes are fetched now, a whole K loop ahead of their use in the epilogue
+    uint32_t resw[TP][TC][4] = {};
+    const bool has_res = tile_epi && a.res != nullptr;
+    if (has_res) {
+        const bool r4 = is4(a.res_dt);
+        const __amdgpu_buffer_rsrc_t rsrc_r =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.res, 0, (int)tensor_bytes((int64_t)a.M * a.K, a.res_dt), 0x00020000);
+        const int chq = k0 + wc * (BC / WC) + khalf * 16 * TC;
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            const int64_t m = m0 + wp * (BP / WP) + tp * 32 + rho;
+#pragma unroll
+            for (int tc = 0; tc < TC; ++tc) {
+                const int64_t e = m * (int64_t)a.K + chq + 16 * tc;
+                const uint32_t ro = (m < a.M && chq + 16 * tc < a.K) ? (uint32_t)(r4 ? (e >> 1) : e) : kInvalid;
+                if (r4) {
+                    const uint2 t = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_r, (int)ro, 0, 0));
+                    resw[tp][tc][0] = t.x; resw[tp][tc][1] = t.y; resw[tp][tc][2] = 0; resw[tp][tc][3] = 0;
+                } else {
+                    const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)ro, 0, 0);
+                    resw[tp][tc][0] = (uint32_t)t[0]; resw[tp][tc][1] = (uint32_t)t[1];
+                    resw[tp][tc][2] = (uint32_t)t[2]; resw[tp][tc][3] = (uint32_t)t[3];
+                }
+            }
+        }
+    }
     lstore(0, S0{});
     wide = __syncthreads_or(wide);
 
-    auto compute = [&](int buf) {
-        const uint8_t *base = lds[buf];
+    // One half-iteration, issued in an order that lets the asynchronous matrix pipe run under the memory
+    // instructions: fragment reads, the next-next step's global loads, then every first-half MFMA is followed
+    // by one LDS write of the step that arrived during the previous half (it goes to the buffer nobody reads),
+    // the remaining MFMAs trail into the barrier.  Scheduling fences pin that order.
+    auto half = [&](int step, auto curc) {
+        constexpr int cur = decltype(curc)::value;          // LDS buffer being multiplied
+        using SetLoad = std::integral_constant<int, cur>;     // register set receiving step+2
+        using SetStore = std::integral_constant<int, cur ^ 1>;  // register set holding step+1
+        const uint8_t *base = lds[cur];
+        v4i af[2][TC], bf[2][TP];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            v4i af[TC], bf[TP];
+        for (int tc = 0; tc < TC; ++tc) af[0][tc] = *(const v4i *)(base + a_off[tc][0]);
 #pragma unroll
-            for (int tc = 0; tc < TC; ++tc) af[tc] = *(const v4i *)(base + a_off[tc][kk]);
+        for (int tp = 0; tp < TP; ++tp) bf[0][tp] = *(const v4i *)(base + b_off[tp][0]);
+        gload(step + 2, SetLoad{});
 #pragma unroll
-            for (int tp = 0; tp < TP; ++tp) bf[tp] = *(const v4i *)(base + b_off[tp][kk]);
+        for (int tc = 0; tc < TC; ++tc) af[1][tc] = *(const v4i *)(base + a_off[tc][1]);
 #pragma unroll
-            for (int tp = 0; tp < TP; ++tp)
-#pragma unroll
-                for (int tc = 0; tc < TC; ++tc)
-                    acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[tc], bf[tp], acc[tp][tc], 0, 0, 0);
-        }
+        for (int tp = 0; tp < TP; ++tp) bf[1][tp] = *(const v4i *)(base + b_off[tp][1]);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, TP * TC>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            constexpr int tp = i / TC, tc = i % TC;
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][tc], bf[0][tp], acc[tp][tc], 0, 0, 0);
+            if constexpr (i < NA + NB) lstore_one(cur ^ 1, SetStore{}, ic);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<TP * TC, NA + NB>([&](auto ic) { lstore_one(cur ^ 1, SetStore{}, ic); });
+        static_for<0, TP * TC>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            constexpr int tp = i / TC, tc = i % TC;
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][tc], bf[1][tp], acc[tp][tc], 0, 0, 0);
+        });
+        __syncthreads();
     };
-    // iteration `step` (even: LDS buffer 0, step+1 waits in set 1, step+2 is fetched into set 0)
+    // even steps multiply buffer 0, odd steps buffer 1; the store after the last step fills an unused buffer
     for (int step = 0; step < steps; step += 2) {
-        gload(step + 2, S0{});
-        compute(0);
-        if (step + 1 < steps) lstore(1, S1{});
-        __syncthreads();
+        half(step, S0{});
         if (step + 1 >= steps) break;
-        gload(step + 3, S1{});
-        compute(1);
-        if (step + 2 < steps) lstore(0, S0{});
-        __syncthreads();
+        half(step + 1, S1{});
     }
 
     // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
@@ -247,7 +281,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             mm[tp] = m0 + wp * (BP / WP) + tp * 32 + rho;
             valid[tp] = mm[tp] < a.M;
         }
-        epilogue_tile<TC, TP>(a, par_m, par_r, mm, valid, k0, chl, acc, wide);
+        epilogue_tile<TC, TP, true>(a, par_m, par_r, mm, valid, k0, chl, acc, wide, resw);
         return;
     }
     static_for<0, TP>([&](auto tpc) {

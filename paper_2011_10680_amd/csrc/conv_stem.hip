@@ -115,7 +115,8 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, const 
             valid[tp] = p < a.P && q < a.Q;
             mm[tp] = ((int64_t)n * a.P + p) * a.Q + q;
         }
-        epilogue_tile<2, 2>(a, par_m, par_r, mm, valid, 0, ch0, acc, wide);
+        const uint32_t none[2][2][4] = {};
+        epilogue_tile<2, 2, false>(a, par_m, par_r, mm, valid, 0, ch0, acc, wide, none);
         return;
     }
     static_for<0, 2>([&](auto tpc) {

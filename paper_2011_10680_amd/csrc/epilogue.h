@@ -186,9 +186,13 @@ __device__ __forceinline__ int stage_params(const ConvArgs &a, int k0, int n_ch,
 // Epilogue of one lane: TP pixels (m[tp], valid[tp]) x TC*16 consecutive channels starting at
 // workgroup-relative channel `chl` (absolute ch0 = k0 + chl).  8-bit or packed 4-bit outputs,
 // requantising, vector stores; requires K % 16 == 0.
-template <int TC, int TP>
+// With PRE the caller has already fetched the lane's shortcut data into `pre`
+// (pre[tp][tc][0..3]: the 16 bytes, or 8 bytes for 4-bit data in [0..1], of channel group tc);
+// the array is taken by reference so it can stay in registers.
+template <int TC, int TP, bool PRE>
 __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
-                                              const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide) {
+                                              const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide,
+                                              const uint32_t (&pre)[TP][TC][4]) {
     // uniform run-time flags, tested per 4-channel group: four specialised copies of this body would
     // let the compiler hoist their common 64-bit products above the selection and hold all of them live
     const bool FAST = !wide, HAS_RES = a.res != nullptr;
@@ -205,7 +209,14 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
             static_for<0, TP>([&](auto tpc) {
                 constexpr int tp = decltype(tpc)::value;
                 rw[tp][0] = rw[tp][1] = rw[tp][2] = rw[tp][3] = 0;
-                if (valid[tp]) {
+                if (PRE) {
+                    if (r4) {
+                        rw[tp][0] = pre[tp][g][0] & 0xffff; rw[tp][1] = pre[tp][g][0] >> 16;
+                        rw[tp][2] = pre[tp][g][1] & 0xffff; rw[tp][3] = pre[tp][g][1] >> 16;
+                    } else {
+                        rw[tp][0] = pre[tp][g][0]; rw[tp][1] = pre[tp][g][1]; rw[tp][2] = pre[tp][g][2]; rw[tp][3] = pre[tp][g][3];
+                    }
+                } else if (valid[tp]) {
                     const int64_t o = m[tp] * (int64_t)a.K + chg;
                     if (r4) {
                         const uint2 t = *(const uint2 *)(a.res + (o >> 1));
@@ -264,7 +275,7 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                 if (y4) ow[tp][q >> 1] |= packed << (16 * (q & 1));
                 else ow[tp][q] = packed;
             });
-            __builtin_amdgcn_sched_barrier(0);
+            // (no scheduling fence)
         });
         static_for<0, TP>([&](auto tpc) {
             constexpr int tp = decltype(tpc)::value;

@@ -64,6 +64,52 @@ def test_int8_conv_shapes(hawq, shape):
     assert 0.05 < (want > 0).mean() and (want == 127).mean() < 0.5
 
 
+# 1x1 convolutions with C = 64 / 128 and many pixels: the persistent streaming kernel
+_SHAPES_PW = [
+    (3, 57, 59, 64, 80, 1, 1, 1, 0, 8, False),     # ragged pixel tail, K % 32 != 0
+    (4, 56, 56, 128, 512, 1, 1, 1, 0, 8, True),    # expanding 1x1 with shortcut
+    (4, 112, 112, 64, 128, 1, 1, 2, 0, 8, False),  # strided
+    (4, 56, 56, 64, 256, 1, 1, 1, 0, 4, True),     # packed 4-bit, 4-bit shortcut
+    (3, 60, 60, 128, 64, 1, 1, 2, 0, 4, False),    # packed 4-bit, strided, ragged
+    (9, 33, 31, 64, 64, 1, 1, 1, 0, 8, True),
+]
+
+
+@pytest.mark.parametrize("shape", _SHAPES_PW)
+def test_pointwise_streaming_shapes(hawq, shape):
+    from gpu_util import run_conv_gpu, assert_same
+    N, H, W, C, K, R, S, stride, pad, bits, res = shape
+    case = _scale_c(wl.conv_case(seed=sum(shape[:9]), N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=bits,
+                                 with_residual=res), bits)
+    if bits == 8:
+        got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    else:
+        got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, res_dt=hawq.U4, y_hi=15)
+    assert_same(got, want, str(shape))
+    v = want.astype(np.int32) if bits == 8 else oracle.unpack(want, oracle.U4)
+    assert 0.05 < (v > 0).mean() < 0.999
+
+
+def test_pointwise_streaming_signed_shortcut_and_wide_parameters(hawq):
+    """Signed 8-bit shortcut (a transition output), and multipliers outside the narrow path's range
+    (c > 31, b >= 2^c) which must take the exact 64-bit path."""
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=123, N=4, H=56, W=56, C=64, K=256, R=1, S=1, stride=1, pad=0, bits=8,
+                                 with_residual=True, res_signed=True), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.S8, x_hi=127)
+    assert_same(got, want, "signed shortcut")
+    wide = dict(case)
+    wide["b"] = (case["b"].astype(np.int64) << 14).astype(np.int32)      # b up to 2^29
+    wide["c"] = (case["c"].astype(np.int32) + 14).astype(np.uint8)       # same scale, c around 39
+    got, want2 = run_conv_gpu(wide, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.S8, x_hi=127)
+    assert_same(got, want2, "wide parameters")
+    assert np.array_equal(want, want2)   # scaling numerator and shift together leaves the result unchanged
+    huge = dict(case)
+    huge["c"] = np.full_like(case["c"], 3)                               # b / 2^c ~ 3000: saturates, needs 64 bits
+    got, want3 = run_conv_gpu(huge, hawq.U8, hawq.S8, hawq.S8, res_dt=hawq.S8, relu=0, y_lo=-128, y_hi=127, x_hi=127)
+    assert_same(got, want3, "saturating parameters")
+
+
 @pytest.mark.parametrize("res_signed,y_dt,relu,lo,hi", [(False, 0, 1, 0, 127), (True, 0, 1, 0, 127), (True, 1, 0, -128, 127),
                                                          (False, 4, 0, -100000, 100000), (False, 2, 1, 0, 15)])
 def test_int8_conv_residual_and_output_types(hawq, res_signed, y_dt, relu, lo, hi):
