@@ -186,104 +186,163 @@ __device__ __forceinline__ int stage_params(const ConvArgs &a, int k0, int n_ch,
 // Epilogue of one lane: TP pixels (m[tp], valid[tp]) x TC*16 consecutive channels starting at
 // workgroup-relative channel `chl` (absolute ch0 = k0 + chl).  8-bit or packed 4-bit outputs,
 // requantising, vector stores; requires K % 16 == 0.
-// With PRE the caller has already fetched the lane's shortcut data into `pre`
+// `pre` holds the lane's shortcut data already fetched by the caller when PRE is set
 // (pre[tp][tc][0..3]: the 16 bytes, or 8 bytes for 4-bit data in [0..1], of channel group tc);
-// the array is taken by reference so it can stay in registers.
+// arrays are taken by reference so they stay in registers.
+//
+// Exact general form (64-bit shift, 64-bit clamp, every type combination); also the wide path.
 template <int TC, int TP, bool PRE>
-__device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
-                                              const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide,
-                                              const uint32_t (&pre)[TP][TC][4]) {
-    // uniform run-time flags, tested per 4-channel group: four specialised copies of this body would
-    // let the compiler hoist their common 64-bit products above the selection and hold all of them live
-    const bool FAST = !wide, HAS_RES = a.res != nullptr;
+__device__ __forceinline__ void epilogue_tile_general(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr,
+                                                      const int64_t (&m)[TP], const bool (&valid)[TP], int k0, int chl,
+                                                      const v16i (&acc_in)[TP][TC], const uint32_t (&pre)[TP][TC][4]) {
     const int y_dt = a.y_dt, res_dt = a.res_dt;
-    const bool y4 = is4(y_dt), r4 = is4(res_dt), rsigned = (res_dt == HAWQ_S8 || res_dt == HAWQ_S4);
+    const bool y4 = is4(y_dt), r4 = is4(res_dt), has_res = a.res != nullptr;
     const int32_t lo = a.lo, hi = a.hi;
     static_for<0, TC>([&](auto gc) {
         constexpr int g = decltype(gc)::value;
         const int chg = k0 + chl + 16 * g;
         if (chg >= a.K) return;
-        // shortcut bytes of the 16 channels for every pixel of the lane
-        uint32_t rw[TP][4];
-        if (HAS_RES) {
-            static_for<0, TP>([&](auto tpc) {
-                constexpr int tp = decltype(tpc)::value;
+        static_for<0, TP>([&](auto tpc) {
+            constexpr int tp = decltype(tpc)::value;
+            if (!valid[tp]) return;
+            const int64_t o = m[tp] * (int64_t)a.K + chg;
+            uint32_t ow[4] = {0, 0, 0, 0};
+            static_for<0, 16>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const ChanMain pmv = pm[chl + 16 * g + i];
+                int32_t av = acc_in[tp][g][i];
+                // opaque copy: keeps this cold path's products from being merged with (and hoisted above) the
+                // narrow path's identical expressions
+                asm volatile("" : "+v"(av));
+                int64_t w64 = ((int64_t)av * (int64_t)pmv.b + pmv.R) >> pmv.c;
+                if (has_res) {
+                    const ChanRes prv = pr[chl + 16 * g + i];
+                    int32_t r;
+                    if (PRE) {
+                        const uint32_t w = r4 ? (pre[tp][g][i >> 3] >> (4 * (i & 7))) & 0xf : (pre[tp][g][i >> 2] >> (8 * (i & 3))) & 0xff;
+                        r = (int32_t)w;
+                        if (res_dt == HAWQ_S8) r = (int32_t)(int8_t)w;
+                        if (res_dt == HAWQ_S4) r = (r ^ 8) - 8;
+                    } else {
+                        r = load_elem(a.res, res_dt, o + i);
+                    }
+                    w64 += rq64(r, prv.rb, prv.rc);
+                }
+                const int32_t y = clamp64(w64, lo, hi);
+                if (y4) ow[i >> 3] |= (uint32_t)(y & 0xf) << (4 * (i & 7));
+                else ow[i >> 2] |= (uint32_t)(y & 0xff) << (8 * (i & 3));
+            });
+            if (y4) *(uint2 *)(a.y + (o >> 1)) = make_uint2(ow[0], ow[1]);
+            else *(uint4 *)(a.y + o) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        });
+    });
+}
+
+// Hot form.  Runs in three passes over the lane's outputs so that every type / path decision is one
+// uniform branch per pass instead of several per output:
+//   1. y = (acc * b + R) >> c        one 64-bit multiply-add and one funnel shift per output
+//   2. y += (r * rb + 2^(rc-1)) >> rc  per shortcut type (u8 / s8 / u4), 24-bit multiply-add
+//   3. clamp, pack 4 (or 8) outputs per dword, 16-byte (8-byte) store per 16 channels
+// `wide` (a channel outside the narrow range) or a signed 4-bit tensor take the general form.
+template <int TC, int TP, bool PRE>
+__device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
+                                              const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide,
+                                              const uint32_t (&pre)[TP][TC][4]) {
+    const int y_dt = a.y_dt, res_dt = a.res_dt;
+    const bool has_res = a.res != nullptr;
+    if (wide || y_dt == HAWQ_S4 || (has_res && res_dt == HAWQ_S4)) {
+        epilogue_tile_general<TC, TP, PRE>(a, pm, pr, m, valid, k0, chl, acc, pre);
+        return;
+    }
+    const bool y4 = is4(y_dt);
+    const int32_t lo = a.lo, hi = a.hi;
+    static_for<0, TC>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        const int chg = k0 + chl + 16 * g;
+        if (chg >= a.K) return;
+        int32_t y[TP][16];
+        // ---- pass 1: main branch ----
+        static_for<0, 16>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const ChanMain pmv = pm[chl + 16 * g + i];
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
+                const int64_t v = (int64_t)acc[tp][g][i] * (int64_t)pmv.b + pmv.R;
+                y[tp][i] = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(v >> 32), (uint32_t)v, (uint32_t)pmv.c);
+            }
+        });
+        // ---- pass 2: shortcut ----
+        if (has_res) {
+            uint32_t rw[TP][4];
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
                 rw[tp][0] = rw[tp][1] = rw[tp][2] = rw[tp][3] = 0;
                 if (PRE) {
-                    if (r4) {
-                        rw[tp][0] = pre[tp][g][0] & 0xffff; rw[tp][1] = pre[tp][g][0] >> 16;
-                        rw[tp][2] = pre[tp][g][1] & 0xffff; rw[tp][3] = pre[tp][g][1] >> 16;
-                    } else {
-                        rw[tp][0] = pre[tp][g][0]; rw[tp][1] = pre[tp][g][1]; rw[tp][2] = pre[tp][g][2]; rw[tp][3] = pre[tp][g][3];
-                    }
+                    rw[tp][0] = pre[tp][g][0]; rw[tp][1] = pre[tp][g][1]; rw[tp][2] = pre[tp][g][2]; rw[tp][3] = pre[tp][g][3];
                 } else if (valid[tp]) {
                     const int64_t o = m[tp] * (int64_t)a.K + chg;
-                    if (r4) {
+                    if (res_dt == HAWQ_U4) {
                         const uint2 t = *(const uint2 *)(a.res + (o >> 1));
-                        rw[tp][0] = t.x & 0xffff; rw[tp][1] = t.x >> 16; rw[tp][2] = t.y & 0xffff; rw[tp][3] = t.y >> 16;
+                        rw[tp][0] = t.x; rw[tp][1] = t.y;
                     } else {
                         const uint4 t = *(const uint4 *)(a.res + o);
                         rw[tp][0] = t.x; rw[tp][1] = t.y; rw[tp][2] = t.z; rw[tp][3] = t.w;
                     }
                 }
-            });
-        }
-        uint32_t ow[TP][4];
-        static_for<0, TP>([&](auto tpc) { constexpr int tp = decltype(tpc)::value; ow[tp][0] = ow[tp][1] = ow[tp][2] = ow[tp][3] = 0; });
-        static_for<0, 4>([&](auto qc) {
-            constexpr int q = decltype(qc)::value;
-            // parameters of 4 channels at a time; the scheduling fence keeps the compiler from
-            // hoisting all 16 channels' LDS reads at once (register pressure)
-            ChanMain pmv[4];
-            ChanRes prv[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                pmv[j] = pm[chl + 16 * g + 4 * q + j];
-                if (HAS_RES) prv[j] = pr[chl + 16 * g + 4 * q + j];
             }
-            static_for<0, TP>([&](auto tpc) {
-                constexpr int tp = decltype(tpc)::value;
-                uint32_t packed = 0;
+            auto add_res = [&](auto kindc) {
+                constexpr int kind = decltype(kindc)::value;   // 0: u8, 1: s8, 2: u4
+                static_for<0, 16>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    const ChanRes prv = pr[chl + 16 * g + i];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    constexpr int dummy = 0; (void)dummy;
-                    const int64_t v = (int64_t)acc[tp][g][4 * q + j] * (int64_t)pmv[j].b + pmv[j].R;
-                    int32_t r = 0;
-                    if (HAS_RES) {
-                        const uint32_t w = rw[tp][q];
-                        if (r4) {
-                            r = (int32_t)((w >> (4 * j)) & 0xf);
-                            if (rsigned) r = (r ^ 8) - 8;
-                        } else {
-                            r = rsigned ? (int32_t)(int8_t)((w >> (8 * j)) & 0xff) : (int32_t)((w >> (8 * j)) & 0xff);
-                        }
+                    for (int tp = 0; tp < TP; ++tp) {
+                        int32_t r;
+                        if (kind == 0) r = (int32_t)__builtin_amdgcn_ubfe(rw[tp][i >> 2], 8 * (i & 3), 8);
+                        else if (kind == 1) r = __builtin_amdgcn_sbfe((int32_t)rw[tp][i >> 2], 8 * (i & 3), 8);
+                        else r = (int32_t)__builtin_amdgcn_ubfe(rw[tp][i >> 3], 4 * (i & 7), 4);
+                        y[tp][i] += (__mul24(r, prv.rb) + prv.rround) >> prv.rc;
                     }
-                    int32_t y;
-                    if (FAST) {
-                        y = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(v >> 32), (uint32_t)v, (uint32_t)pmv[j].c);
-                        if (HAS_RES) y += (__mul24(r, prv[j].rb) + prv[j].rround) >> prv[j].rc;
-                        y = y < lo ? lo : y;
-                        y = y > hi ? hi : y;
-                    } else {
-                        int64_t w64 = v >> pmv[j].c;
-                        if (HAS_RES) w64 += rq64(r, prv[j].rb, prv[j].rc);
-                        y = clamp64(w64, lo, hi);
-                    }
-                    if (y4) packed |= (uint32_t)(y & 0xf) << (4 * j);
-                    else packed |= (uint32_t)(y & 0xff) << (8 * j);
+                });
+            };
+            if (res_dt == HAWQ_U8) add_res(std::integral_constant<int, 0>{});
+            else if (res_dt == HAWQ_S8) add_res(std::integral_constant<int, 1>{});
+            else add_res(std::integral_constant<int, 2>{});
+        }
+        // ---- pass 3: clamp, pack, store ----
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                int32_t v = y[tp][i];
+                v = v < lo ? lo : v;
+                y[tp][i] = v > hi ? hi : v;
+            }
+        }
+        if (y4) {
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {   // values are within 0..15 after the clamp (unsigned 4-bit output)
+                    w0 |= (uint32_t)y[tp][i] << (4 * i);
+                    w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
                 }
-                if (y4) ow[tp][q >> 1] |= packed << (16 * (q & 1));
-                else ow[tp][q] = packed;
-            });
-            // (no scheduling fence)
-        });
-        static_for<0, TP>([&](auto tpc) {
-            constexpr int tp = decltype(tpc)::value;
-            if (!valid[tp]) return;
-            const int64_t o = m[tp] * (int64_t)a.K + chg;
-            if (y4) *(uint2 *)(a.y + (o >> 1)) = make_uint2(ow[tp][0], ow[tp][1]);
-            else *(uint4 *)(a.y + o) = make_uint4(ow[tp][0], ow[tp][1], ow[tp][2], ow[tp][3]);
-        });
+                if (valid[tp]) *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+            }
+        } else {
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {   // low bytes of 4 values -> one dword (works for signed outputs too)
+                    const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 1], (uint32_t)y[tp][4 * q], 0x0c0c0400u);
+                    const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
+                    w[q] = t0 | t1;
+                }
+                if (valid[tp]) *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
     });
 }
 
