@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--workload", default="resnet50_int8_b128", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-images", type=int, default=48, help="images in the CPU-oracle baseline sample (0: skip)")
     ap.add_argument("--report", default=None, help="optional file for the per-layer table (JSON)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards by batch with no exchange; "
@@ -62,6 +65,14 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
+        return
     import workloads as wl
     import paper_2011_10680_amd as hawq
 

@@ -1,0 +1,120 @@
+"""CPU-side checks of the C interface: the library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hawq.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2011_10680_amd as hawq
+    from paper_2011_10680_amd import build
+    if build.is_stale():
+        build.build()
+    return hawq.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hawq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"hawq_conv2d_int", "hawq_gemm_int", "hawq_residual_add_dyadic", "hawq_avgpool_int",
+            "hawq_forward_resnet"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "libhawq.so does not export " + n
+
+
+def test_topology_queries_match_the_paper_workloads(lib):
+    import paper_2011_10680_amd as hawq
+    import workloads as wl
+    for arch in (18, 50):
+        shapes = wl.resnet_layers(arch)
+        assert hawq.hawq_net_num_layers(arch) == len(shapes)
+        macs = 0
+        for i, s in enumerate(shapes):
+            info = hawq.hawq_net_layer_info(arch, 224, 1000, i)
+            for k in ("name", "C", "K", "R", "S", "stride", "pad", "H", "W", "P", "Q"):
+                assert info[k] == s[k], (arch, i, k)
+            assert bool(info["has_residual"]) == s["has_residual"]
+            assert bool(info["is_ds"]) == (s["kind"] == "ds")
+            macs += info["P"] * info["Q"] * info["K"] * info["R"] * info["S"] * info["C"]
+        # Table 1 BOPS at W8A8: 116 G (ResNet18), 247 G (ResNet50)
+        assert round(macs * 64 / 1e9) == {18: 116, 50: 247}[arch]
+    assert hawq.hawq_net_num_layers(34) == 0
+
+
+def _desc(**kw):
+    import paper_2011_10680_amd as hawq
+    d = dict(N=1, H=8, W=8, C=64, K=64, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, x_dtype=hawq.U8,
+             w_dtype=hawq.S8, y_dtype=hawq.U8, res_dtype=hawq.U8, relu=1, y_lo=0, y_hi=127, x_hi=127)
+    d.update(kw)
+    return hawq.ConvDesc(**d)
+
+
+def test_conv_argument_validation_on_host(lib):
+    """Pointers are never dereferenced on the host, so small fake non-null addresses are enough to reach
+    the later checks; every case must fail before a launch."""
+    import paper_2011_10680_amd as hawq
+    P = ctypes.c_void_p(4096)
+    call = lambda d, x=P, w=P, bias=P, b=P, c=P, res=None, rb=None, rc=None, y=P: lib.hawq_conv2d_int(
+        ctypes.byref(d), x, w, bias, b, c, res, rb, rc, y, None)
+    assert call(_desc(), x=None) == 1                                  # HAWQ_ERR_NULL
+    assert call(_desc(), b=None) == 1                                  # b without c
+    assert call(_desc(), res=P) == 1                                   # residual without its multipliers
+    assert call(_desc(H=0)) == 2                                       # HAWQ_ERR_SHAPE
+    assert call(_desc(R=11, S=11, pad_h=0, pad_w=0)) == 2              # window larger than the image
+    assert call(_desc(x_dtype=hawq.U4, w_dtype=hawq.S4, C=63)) == 2    # odd packed channel count
+    assert call(_desc(y_dtype=hawq.U4, y_hi=15, K=63)) == 2
+    assert call(_desc(w_dtype=hawq.S4)) == 3                           # HAWQ_ERR_DTYPE: widths differ
+    assert call(_desc(x_dtype=hawq.S32)) == 3
+    assert call(_desc(y_dtype=hawq.U8), b=None, c=None) == 3           # raw output must be INT32
+    assert call(_desc(y_hi=300)) == 4                                  # HAWQ_ERR_RANGE
+    assert call(_desc(y_lo=5, y_hi=4)) == 4
+    assert call(_desc(x_hi=300)) == 4
+    assert call(_desc(C=65536 * 2, R=1, S=1, pad_h=0, pad_w=0, x_hi=255)) == 5   # HAWQ_ERR_OVERFLOW: 2^17*255*128 >= 2^31
+    assert call(_desc(N=1 << 20, H=64, W=64)) == 6                     # HAWQ_ERR_UNSUPPORTED: tensor >= 2 GiB
+    assert call(_desc(N=0)) == 0                                       # empty batch: nothing to do
+    assert lib.hawq_status_string(5).decode().lower().startswith("int32")
+
+
+def test_other_entry_points_validate_on_host(lib):
+    P = ctypes.c_void_p(4096)
+    assert lib.hawq_gemm_int(4, 0, 64, 0, 1, 4, P, P, P, None, None, 0, 0, 0, P, None) == 2
+    assert lib.hawq_gemm_int(4, 8, 64, 0, 1, 0, P, P, P, None, None, 0, 0, 127, P, None) == 3
+    assert lib.hawq_gemm_int(0, 8, 64, 0, 1, 4, P, P, P, None, None, 0, 0, 0, P, None) == 0
+    assert lib.hawq_residual_add_dyadic(10, 8, 4, 0, 0, P, P, P, None, P, P, 1, 0, 127, P, None) == 1
+    assert lib.hawq_residual_add_dyadic(10, 7, 2, 0, 0, P, P, P, P, P, P, 1, 0, 127, P, None) == 2
+    assert lib.hawq_residual_add_dyadic(10, 8, 4, 0, 0, P, P, P, P, P, P, 1, 0, 256, P, None) == 4
+    assert lib.hawq_avgpool_int(1, 7, 7, 64, 4, 0, P, P, P, 0, 127, P, None) == 3
+    assert lib.hawq_avgpool_int(1, 7, 7, 64, 0, 0, P, None, P, 0, 127, P, None) == 1
+    assert lib.hawq_maxpool_int(1, 8, 8, 63, 0, 2, P, 0, 15, P, None) == 2
+    assert lib.hawq_forward_resnet(None, P, 1, P, P, 0, None) == 1
+
+
+def test_net_create_rejects_bad_parameters_before_touching_the_gpu(lib):
+    import numpy as np
+    import paper_2011_10680_amd as hawq
+    import workloads as wl
+    net = wl.make_resnet(18, seed=1, image_hw=64, num_classes=10)
+    bad = [dict(l) for l in net["layers"]]
+    bad[3]["c"] = bad[3]["c"].copy(); bad[3]["c"][0] = 0          # shift of 0 is outside 1..62
+    with pytest.raises(hawq.HawqError) as e:
+        hawq.HawqNet(18, bad, net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
+    assert e.value.status == 4
+    bad = [dict(l) for l in net["layers"]]
+    bad[0]["bits"] = 4                                            # first layer must stay 8-bit
+    with pytest.raises(hawq.HawqError) as e:
+        hawq.HawqNet(18, bad, net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
+    assert e.value.status == 3
+    with pytest.raises(hawq.HawqError) as e:                      # wrong layer count
+        hawq.HawqNet(18, net["layers"][:-1], net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
+    assert e.value.status == 2
