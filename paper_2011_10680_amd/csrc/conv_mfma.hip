@@ -22,10 +22,11 @@ namespace hawq {
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
-// Minimum waves per SIMD the register allocation must leave room for: 2 for the 128x128 tile
-// (64 accumulator registers per lane), 3 for 64x128, 6 for 64x64 (the latency-bound shapes live on occupancy).
+// Minimum waves per SIMD the register allocation must leave room for, by the wave's share of the tile:
+// 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
+// shapes live on occupancy).
 template <int BC, int BP, int WC, int WP, bool INT4>
-__global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP >= 128 * 128 ? 2 : (BC * BP >= 64 * 128 ? 3 : 6))))
+__global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr int T = WC * WP * 64;
     constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
@@ -332,13 +333,18 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (g_tile_override == 1) return launch_cfg<128, 128, 2, 2>(a, vec, s);
     if (g_tile_override == 2) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     if (g_tile_override == 3) return launch_cfg<64, 64, 2, 2>(a, vec, s);
-    // Measured on MI355X over the ResNet layer shapes: deep reductions want the large tile (operand
-    // reuse), shallow ones are latency bound and want many small workgroups in flight.
+    if (g_tile_override == 4) return launch_cfg<128, 128, 2, 4>(a, vec, s);
+    // Measured on MI355X over the ResNet layer shapes (batch 8..256): with at least 128 output channels
+    // the 128x128 tile wins (operand reuse; every K-step costs a fixed latency chain, so more work per
+    // step is better), in its 8-wave form when the reduction is deep and there are too few tiles to give
+    // every CU two workgroups; 64-channel layers take 64x128, tiny problems 64x64.
     const int64_t kg = (int64_t)a.R * a.S * a.C;
     const int64_t tiles_big = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
-    const int64_t tiles_mid = (int64_t)((a.K + 63) / 64) * ((a.M + 127) / 128);
-    if (kg >= 2048 && a.K >= 256 && tiles_big >= 256) return launch_cfg<128, 128, 2, 2>(a, vec, s);
-    if (kg >= 1024 && tiles_mid >= 256) return launch_cfg<64, 128, 1, 4>(a, vec, s);
+    if (a.K >= 128 && a.M >= 1024) {
+        if (kg >= 2048 && tiles_big < 256) return launch_cfg<128, 128, 2, 4>(a, vec, s);
+        return launch_cfg<128, 128, 2, 2>(a, vec, s);
+    }
+    if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     return launch_cfg<64, 64, 2, 2>(a, vec, s);
 }
 

@@ -34,20 +34,13 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
     // ---- parameters of this wave's 32 channels -> wave-private LDS ----
     int wide = 0;
     {
-        ChanMain m = {0, 1, 0};
-        ChanRes r = {0, 1, 1, 0};
-        const int k = k0 + rho;
-        if (khalf == 0 && k < a.K) {
-            m.b = a.b[k]; m.c = a.c[k];
-            m.R = (int64_t)a.bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
-            if (m.c > 31 || ((uint32_t)m.b >> m.c) != 0) wide = 1;
-            if (a.res != nullptr) {
-                r.rb = a.res_b[k]; r.rc = a.res_c[k];
-                if (r.rc > 31 || r.rb >= (1 << 22)) wide = 1;
-                r.rround = (int32_t)(1u << ((r.rc - 1) & 31));
-            }
+        ChanMain m;
+        ChanRes r;
+        if (khalf == 0) {
+            wide = stage_channel(a, k0 + rho, m, r);
+            par_m[wave][rho] = m;
+            par_r[wave][rho] = r;
         }
-        if (khalf == 0) { par_m[wave][rho] = m; par_r[wave][rho] = r; }
         wide = __any(wide);
     }
 

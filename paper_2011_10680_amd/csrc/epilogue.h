@@ -148,35 +148,48 @@ __device__ __forceinline__ void epilogue_pixel(const ConvArgs &a, int64_t m, int
 // ------------------------------------------------------------------------------------------
 // Tile epilogue with per-channel parameters staged in LDS (the hot variant).
 //
-// stage_params() runs once per workgroup: thread i < n_ch prepares channel k0+i as
-//     main: { b, c, R = bias*b + 2^(c-1) (int64) }         so that  rq(acc+bias) = (acc*b + R) >> c
+// stage_channel() prepares one channel as
+//     main: { b, c, R = bias*b + 2^(c-1) }                   so that  rq(acc+bias) = (acc*b + R) >> c
+//           { bs = b << (32-c), Rs = R << (32-c) }            so that  rq(acc+bias) = high word of acc*bs + Rs
 //     res : { rb, rc, 2^(rc-1) }
-// and reports whether every channel of the workgroup allows the narrow evaluation:
-//     main: c <= 31 and b < 2^c      -> the requantised value fits int32; the 64-bit product is
-//                                        shifted with one funnel shift of its two halves
+// and reports whether the channel allows the narrow evaluation:
+//     main: c <= 32 and b < 2^(c-1)  -> bs fits a signed 32-bit operand, the result fits int32 and the
+//                                        shift disappears into "take the high word"
 //     res : rc <= 31 and rb < 2^22   -> |r| <= 255 keeps r*rb + 2^(rc-1) inside int32
-// Otherwise the workgroup takes the wide path: full 64-bit shift and 64-bit clamp.  Both paths
-// compute the same exact integer.
-struct ChanMain { int32_t b, c; int64_t R; };
+// A workgroup (or wave) with any other channel takes the general path: 64-bit shift and clamp.
+// Both paths compute the same exact integer.
+struct ChanMain { int32_t b, c; int64_t R; int32_t bs, pad; int64_t Rs; };
 struct ChanRes { int32_t rb, rc, rround, pad; };
+
+__device__ __forceinline__ int stage_channel(const ConvArgs &a, int k, ChanMain &m, ChanRes &r) {
+    int wide = 0;
+    m = ChanMain{0, 1, 0, 0, 0, 0};
+    r = ChanRes{0, 1, 1, 0};
+    if (k < a.K) {
+        m.b = a.b[k]; m.c = a.c[k];
+        m.R = (int64_t)a.bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
+        if (m.c > 32 || ((int64_t)m.b >> (m.c - 1)) != 0) {
+            wide = 1;
+        } else {
+            m.bs = (int32_t)((uint32_t)m.b << (32 - m.c));
+            m.Rs = (int64_t)((uint64_t)m.R << (32 - m.c));
+        }
+        if (a.res != nullptr) {
+            r.rb = a.res_b[k]; r.rc = a.res_c[k];
+            if (r.rc > 31 || r.rb >= (1 << 22)) wide = 1;
+            r.rround = (int32_t)(1u << ((r.rc - 1) & 31));
+        }
+    }
+    return wide;
+}
 
 __device__ __forceinline__ int stage_params(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanRes *pr) {
     int wide = 0;
     const int i = threadIdx.x;
     if (i < n_ch && a.b != nullptr) {
-        const int k = k0 + i;
-        ChanMain m = {0, 1, 0};
-        ChanRes r = {0, 1, 1, 0};
-        if (k < a.K) {
-            m.b = a.b[k]; m.c = a.c[k];
-            m.R = (int64_t)a.bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
-            if (m.c > 31 || ((uint32_t)m.b >> m.c) != 0) wide = 1;
-            if (a.res != nullptr) {
-                r.rb = a.res_b[k]; r.rc = a.res_c[k];
-                if (r.rc > 31 || r.rb >= (1 << 22)) wide = 1;
-                r.rround = (int32_t)(1u << ((r.rc - 1) & 31));
-            }
-        }
+        ChanMain m;
+        ChanRes r;
+        wide = stage_channel(a, k0 + i, m, r);
         pm[i] = m;
         pr[i] = r;
     }
@@ -255,7 +268,9 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
         return;
     }
     const bool y4 = is4(y_dt);
-    const int32_t lo = a.lo, hi = a.hi;
+    // clamp bounds in vector registers so the clamp is a single three-operand median
+    int32_t lo = a.lo, hi = a.hi;
+    asm volatile("" : "+v"(lo), "+v"(hi));
     static_for<0, TC>([&](auto gc) {
         constexpr int g = decltype(gc)::value;
         const int chg = k0 + chl + 16 * g;
@@ -264,12 +279,11 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
         // ---- pass 1: main branch ----
         static_for<0, 16>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
-            const ChanMain pmv = pm[chl + 16 * g + i];
+            const ChanMain &pc = pm[chl + 16 * g + i];
+            const int32_t bs = pc.bs;
+            const int64_t Rs = pc.Rs;
 #pragma unroll
-            for (int tp = 0; tp < TP; ++tp) {
-                const int64_t v = (int64_t)acc[tp][g][i] * (int64_t)pmv.b + pmv.R;
-                y[tp][i] = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(v >> 32), (uint32_t)v, (uint32_t)pmv.c);
-            }
+            for (int tp = 0; tp < TP; ++tp) y[tp][i] = (int32_t)(((int64_t)acc[tp][g][i] * (int64_t)bs + Rs) >> 32);
         });
         // ---- pass 2: shortcut ----
         if (has_res) {
@@ -314,9 +328,9 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
         for (int tp = 0; tp < TP; ++tp) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                int32_t v = y[tp][i];
-                v = v < lo ? lo : v;
-                y[tp][i] = v > hi ? hi : v;
+                int32_t t;   // lo <= hi is validated by the interface, so the median is the clamp
+                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(y[tp][i]), "v"(lo), "v"(hi));
+                y[tp][i] = t;
             }
         }
         if (y4) {
