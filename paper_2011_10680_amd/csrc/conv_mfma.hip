@@ -37,7 +37,22 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     constexpr int TP = BP / WP / 32;            //                        ... along pixels
     static_assert(BC % (WC * 32) == 0 && BP % (WP * 32) == 0, "tile shape");
 
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2][(BC + BP) * 64];
+    constexpr int kBufBytes = (BC + BP) * 64;
+    // INT8 operands go global -> LDS directly (LDS-DMA buffer loads); packed INT4 operands pass through
+    // registers to be unpacked.  The four pipeline buffers are separate objects so that the compiler's
+    // wait-count tracking of the asynchronous LDS writes is per buffer.
+    constexpr bool DMA = !INT4;
+    __shared__ __attribute__((aligned(1024))) uint8_t lds0[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds1[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds2[kBufBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds3[kBufBytes];
+    auto ldsbuf = [&](auto nc) -> uint8_t * {
+        constexpr int n = decltype(nc)::value;
+        if constexpr (n == 0) return lds0;
+        else if constexpr (n == 1) return lds1;
+        else if constexpr (n == 2) return lds2;
+        else return lds3;
+    };
     __shared__ ChanMain par_m[BC];
     __shared__ ChanRes par_r[BC];
 
@@ -69,7 +84,9 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     for (int j = 0; j < NA; ++j) {
         const int i = tid + j * T;
         a_row[j] = i / CPR;
-        a_ch[j] = i % CPR;
+        // LDS-DMA: lane i of the workgroup writes LDS chunk i, so it must fetch the logical chunk that the
+        // XOR swizzle places there; register path: lane i fetches logical chunk i%CPR and swizzles on write
+        a_ch[j] = DMA ? ((i % CPR) ^ swz(a_row[j])) : (i % CPR);
         const int k = k0 + a_row[j];
         const bool ok = (i < BC * CPR) && (k < a.K);
         a_voff[j] = ok ? (uint32_t)(k * (int)wrow_bytes + a_ch[j] * 16) : kInvalid;
@@ -83,7 +100,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     for (int j = 0; j < NB; ++j) {
         const int i = tid + j * T;
         b_row[j] = i / CPR;
-        b_ch[j] = i % CPR;
+        b_ch[j] = DMA ? ((i % CPR) ^ swz(b_row[j])) : (i % CPR);
         const int m = m0 + b_row[j];
         b_ok[j] = (i < BP * CPR) && (m < a.M);
         const int mm = b_ok[j] ? m : 0;
@@ -102,12 +119,26 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // and would wait for all of them before every LDS write.
     v4i ra[2][NA], rb[2][NB];
     int r = 0, s = 0, cc = 0;  // tap and channel chunk of the K-step being *loaded*
+    // gload(step, set): register path -- fetch K-step `step` into register set `set`.
+    // gload(step, buf) with DMA -- fetch K-step `step` straight into LDS buffer `buf`: every wave-instruction
+    // fills 64 consecutive 16-byte chunks (16 tile rows), the destination base is wave-uniform.
     auto gload = [&](int step, auto setc) {
         constexpr int set = decltype(setc)::value;
-        const int a_soff = min(step, steps - 1) * BKB;                      // uniform -> SGPR offset
+        // uniform -> SGPR offset; past the last K-step the offset leaves the buffer, the weights read as
+        // zeros and the padded iterations of the unrolled loop add nothing
+        const int a_soff = step < steps ? step * BKB : 0x40000000;
         const int tapoff = (r * a.W + s) * Cb + cc * BKB;                   // uniform
 #pragma unroll
-        for (int j = 0; j < NA; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)a_voff[j], a_soff, 0);
+        for (int j = 0; j < NA; ++j) {
+            if constexpr (DMA) {
+                if (NA * T != BC * CPR && tid + j * T >= BC * CPR) continue;   // (never for INT8: tiles divide evenly)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rsrc_w, (__attribute__((address_space(3))) void *)(ldsbuf(setc) + (j * (T / 64) + wave) * 1024), 16,
+                    (int)a_voff[j], a_soff, 0, 0);
+            } else {
+                ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)a_voff[j], a_soff, 0);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             uint32_t off = b_voff[j] + (uint32_t)tapoff;
@@ -115,7 +146,13 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 const bool ok = b_ok[j] & ((unsigned)(b_ih0[j] + r) < (unsigned)a.H) & ((unsigned)(b_iw0[j] + s) < (unsigned)a.W);
                 off = ok ? off : kInvalid;
             }
-            rb[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
+            if constexpr (DMA) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rsrc_x, (__attribute__((address_space(3))) void *)(ldsbuf(setc) + BC * 64 + (j * (T / 64) + wave) * 1024), 16,
+                    (int)off, 0, 0, 0);
+            } else {
+                rb[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
+            }
         }
         // advance to the next K-step without branches (scalar selects); past the last step stay put
         const int adv = (step + 1 < steps) ? 1 : 0;
@@ -128,20 +165,32 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         r += wrap_s;
     };
 
+    // LDS write addresses in buffer 0 (per chunk; INT4 writes two 16-byte pieces)
+    int a_wo[NA][2], b_wo[NB][2];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int row = a_row[j], sw = swz(row);
+        a_wo[j][0] = row * 64 + (((INT4 ? 2 * a_ch[j] : a_ch[j]) ^ sw) << 4);
+        a_wo[j][1] = row * 64 + (((2 * a_ch[j] + 1) ^ sw) << 4);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int row = b_row[j], sw = swz(row);
+        b_wo[j][0] = BC * 64 + row * 64 + (((INT4 ? 2 * b_ch[j] : b_ch[j]) ^ sw) << 4);
+        b_wo[j][1] = BC * 64 + row * 64 + (((2 * b_ch[j] + 1) ^ sw) << 4);
+    }
     // Write chunk `idx` (0..NA-1: weights, NA..NA+NB-1: pixels) of register set `set` to LDS buffer `buf`.
-    auto lstore_one = [&](int buf, auto setc, auto idxc) {
+    auto lstore_one = [&](auto bufc, auto setc, auto idxc) {
         constexpr int set = decltype(setc)::value;
         constexpr int idx = decltype(idxc)::value;
         constexpr bool isA = idx < NA;
         constexpr int j = isA ? idx : idx - NA;
         constexpr int rows = isA ? BC : BP;
         if ((isA ? NA : NB) * T != rows * CPR && tid + j * T >= rows * CPR) return;
-        uint8_t *base = lds[buf] + (isA ? 0 : BC * 64);
-        int row, ch;
+        uint8_t *p0, *p1;
         v4i v;
-        if constexpr (isA) { row = a_row[j]; ch = a_ch[j]; v = ra[set][j]; }
-        else { row = b_row[j]; ch = b_ch[j]; v = rb[set][j]; }
-        const int sw = swz(row);
+        if constexpr (isA) { p0 = ldsbuf(bufc) + a_wo[j][0]; p1 = ldsbuf(bufc) + a_wo[j][1]; v = ra[set][j]; }
+        else { p0 = ldsbuf(bufc) + b_wo[j][0]; p1 = ldsbuf(bufc) + b_wo[j][1]; v = rb[set][j]; }
         if (INT4) {
             v4i lo, hi;
 #pragma unroll
@@ -154,14 +203,14 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 }
                 lo[e] = (int)l; hi[e] = (int)h;
             }
-            *(v4i *)(base + row * 64 + (((2 * ch) ^ sw) << 4)) = lo;
-            *(v4i *)(base + row * 64 + (((2 * ch + 1) ^ sw) << 4)) = hi;
+            *(v4i *)p0 = lo;
+            *(v4i *)p1 = hi;
         } else {
-            *(v4i *)(base + row * 64 + ((ch ^ sw) << 4)) = v;
+            *(v4i *)p0 = v;
         }
     };
-    auto lstore = [&](int buf, auto setc) {
-        static_for<0, NA + NB>([&](auto ic) { lstore_one(buf, setc, ic); });
+    auto lstore = [&](auto bufc, auto setc) {
+        static_for<0, NA + NB>([&](auto ic) { lstore_one(bufc, setc, ic); });
     };
 
     // ---- MFMA fragment addresses (loop invariant) ----
@@ -169,18 +218,20 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // of lane half h = (rho>>2)&1; we want that register to be channel  h*16*TC + tc*16 + i  of the wave.
     const int rho = lane & 31, khalf = lane >> 5;
     const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
-    int a_off[TC][2], b_off[TP][2];
+    // byte offsets of the lane's fragments inside a buffer (the buffer's base is a link-time constant that
+    // folds into the instruction's immediate offset)
+    int a_fo[TC][2], b_fo[TP][2];
 #pragma unroll
     for (int tc = 0; tc < TC; ++tc) {
         const int row = wc * (BC / WC) + hsel * 16 * TC + tc * 16 + isel;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) a_off[tc][kk] = row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
+        for (int kk = 0; kk < 2; ++kk) a_fo[tc][kk] = row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
     }
 #pragma unroll
     for (int tp = 0; tp < TP; ++tp) {
         const int row = wp * (BP / WP) + tp * 32 + rho;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) b_off[tp][kk] = BC * 64 + row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
+        for (int kk = 0; kk < 2; ++kk) b_fo[tp][kk] = BC * 64 + row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
     }
 
     v16i acc[TP][TC];
@@ -193,8 +244,16 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
 
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
-    gload(0, S0{});
-    gload(1, S1{});
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+    if constexpr (DMA) {
+        gload(0, S0{});
+        gload(1, S1{});
+        gload(2, S2{});
+    } else {
+        gload(0, S0{});
+        gload(1, S1{});
+    }
     // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
@@ -225,49 +284,88 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             }
         }
     }
-    lstore(0, S0{});
+    // ---- software pipeline over four LDS buffers ----
+    // Register path (INT4), iteration t (LDS buffer t%4 is multiplied):
+    //   * K-step t+2, requested two iterations ago, is written from register set t%2 to buffer (t+2)%4
+    //     (last read in iteration t-2); K-step t+4 is requested into the freed register set.
+    // LDS-DMA path (INT8), iteration t:
+    //   * K-step t+3 is requested straight into buffer (t+3)%4 (last read in iteration t-1); before the closing
+    //     barrier every wave waits until its own requests of iteration t-1 have landed, so after the barrier
+    //     step t+2 is complete for all waves.
+    // Both: the first-half fragments of step t+1 are read while this step's MFMAs run, so after the closing
+    // barrier the next MFMAs issue at once.  One barrier per K-step.  The loop is unrolled four times with a
+    // single exit (the trip count is rounded up; padded steps multiply zero weights), so buffer and
+    // register-set indices are compile-time constants and the accumulators stay in place.
+    if constexpr (DMA) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NA + NB) : "memory");   // steps 0 and 1 have landed (step 2 may fly)
+    } else {
+        lstore(S0{}, S0{});
+        lstore(S1{}, S1{});
+        gload(2, S0{});
+        gload(3, S1{});
+    }
     wide = __syncthreads_or(wide);
+    v4i af0[TC], bf0[TP];   // first-half fragments of the step about to be multiplied
+#pragma unroll
+    for (int tc = 0; tc < TC; ++tc) af0[tc] = *(const v4i *)(lds0 + a_fo[tc][0]);
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp) bf0[tp] = *(const v4i *)(lds0 + b_fo[tp][0]);
 
-    // One half-iteration, issued in an order that lets the asynchronous matrix pipe run under the memory
-    // instructions: fragment reads, the next-next step's global loads, then every first-half MFMA is followed
-    // by one LDS write of the step that arrived during the previous half (it goes to the buffer nobody reads),
-    // the remaining MFMAs trail into the barrier.  Scheduling fences pin that order.
-    auto half = [&](int step, auto curc) {
-        constexpr int cur = decltype(curc)::value;          // LDS buffer being multiplied
-        using SetLoad = std::integral_constant<int, cur>;     // register set receiving step+2
-        using SetStore = std::integral_constant<int, cur ^ 1>;  // register set holding step+1
-        const uint8_t *base = lds[cur];
-        v4i af[2][TC], bf[2][TP];
+    auto iteration = [&](int step, auto phasec) {
+        constexpr int phase = decltype(phasec)::value;            // step % 4
+        using Cur = std::integral_constant<int, phase>;
+        using Nxt = std::integral_constant<int, (phase + 1) % 4>;
+        using Wr = std::integral_constant<int, (phase + 2) % 4>;
+        using Dma = std::integral_constant<int, (phase + 3) % 4>;
+        using Set = std::integral_constant<int, phase % 2>;
+        v4i af1[TC], bf1[TP];
 #pragma unroll
-        for (int tc = 0; tc < TC; ++tc) af[0][tc] = *(const v4i *)(base + a_off[tc][0]);
+        for (int tc = 0; tc < TC; ++tc) af1[tc] = *(const v4i *)(ldsbuf(Cur{}) + a_fo[tc][1]);
 #pragma unroll
-        for (int tp = 0; tp < TP; ++tp) bf[0][tp] = *(const v4i *)(base + b_off[tp][0]);
-        gload(step + 2, SetLoad{});
-#pragma unroll
-        for (int tc = 0; tc < TC; ++tc) af[1][tc] = *(const v4i *)(base + a_off[tc][1]);
-#pragma unroll
-        for (int tp = 0; tp < TP; ++tp) bf[1][tp] = *(const v4i *)(base + b_off[tp][1]);
+        for (int tp = 0; tp < TP; ++tp) bf1[tp] = *(const v4i *)(ldsbuf(Cur{}) + b_fo[tp][1]);
+        if constexpr (DMA) gload(step + 3, Dma{});
         __builtin_amdgcn_sched_barrier(0);
+        // first-half MFMAs (register path: each followed by one LDS write of step+2)
         static_for<0, TP * TC>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             constexpr int tp = i / TC, tc = i % TC;
-            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][tc], bf[0][tp], acc[tp][tc], 0, 0, 0);
-            if constexpr (i < NA + NB) lstore_one(cur ^ 1, SetStore{}, ic);
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af0[tc], bf0[tp], acc[tp][tc], 0, 0, 0);
+            if constexpr (!DMA && i < NA + NB) lstore_one(Wr{}, Set{}, ic);
             __builtin_amdgcn_sched_barrier(0);
         });
-        static_for<TP * TC, NA + NB>([&](auto ic) { lstore_one(cur ^ 1, SetStore{}, ic); });
+        if constexpr (!DMA) {
+            static_for<TP * TC, NA + NB>([&](auto ic) { lstore_one(Wr{}, Set{}, ic); });
+            gload(step + 4, Set{});
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // second-half MFMAs with the next step's first-half fragment reads in between
         static_for<0, TP * TC>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             constexpr int tp = i / TC, tc = i % TC;
-            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[1][tc], bf[1][tp], acc[tp][tc], 0, 0, 0);
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af1[tc], bf1[tp], acc[tp][tc], 0, 0, 0);
+            if constexpr (i == 0) {
+#pragma unroll
+                for (int t2 = 0; t2 < TC; ++t2) af0[t2] = *(const v4i *)(ldsbuf(Nxt{}) + a_fo[t2][0]);
+#pragma unroll
+                for (int t2 = 0; t2 < TP; ++t2) bf0[t2] = *(const v4i *)(ldsbuf(Nxt{}) + b_fo[t2][0]);
+            }
         });
-        __syncthreads();
+        if constexpr (DMA) {
+            // Wait until this wave's requests of the previous iteration are in LDS (the NA+NB just issued may
+            // still fly) and its LDS reads are done, then meet the other waves.  A plain barrier instruction
+            // is used instead of __syncthreads(): that one carries a workgroup fence, which would wait for
+            // *all* outstanding LDS-DMA writes and expose their full latency every K-step.  The memory clobber
+            // keeps the compiler from moving LDS accesses across it.
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NA + NB) : "memory");
+        } else {
+            __syncthreads();
+        }
     };
-    // even steps multiply buffer 0, odd steps buffer 1; the store after the last step fills an unused buffer
-    for (int step = 0; step < steps; step += 2) {
-        half(step, S0{});
-        if (step + 1 >= steps) break;
-        half(step + 1, S1{});
+    for (int step = 0; step < steps; step += 4) {
+        iteration(step, S0{});
+        iteration(step + 1, S1{});
+        iteration(step + 2, S2{});
+        iteration(step + 3, S3{});
     }
 
     // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
@@ -334,16 +432,12 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (g_tile_override == 2) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     if (g_tile_override == 3) return launch_cfg<64, 64, 2, 2>(a, vec, s);
     if (g_tile_override == 4) return launch_cfg<128, 128, 2, 4>(a, vec, s);
-    // Measured on MI355X over the ResNet layer shapes (batch 8..256): with at least 128 output channels
-    // the 128x128 tile wins (operand reuse; every K-step costs a fixed latency chain, so more work per
-    // step is better), in its 8-wave form when the reduction is deep and there are too few tiles to give
-    // every CU two workgroups; 64-channel layers take 64x128, tiny problems 64x64.
-    const int64_t kg = (int64_t)a.R * a.S * a.C;
-    const int64_t tiles_big = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
-    if (a.K >= 128 && a.M >= 1024) {
-        if (kg >= 2048 && tiles_big < 256) return launch_cfg<128, 128, 2, 4>(a, vec, s);
-        return launch_cfg<128, 128, 2, 2>(a, vec, s);
-    }
+    // Measured on MI355X over the ResNet layer shapes: with at least 128 output channels the 128x128 tile
+    // wins (operand reuse: a CU's vector-memory path delivers ~60 B/clk and its LDS accepts ~70 B/clk of
+    // writes, which a 128x128x64 step of INT8 MFMA consumes in exactly the time it takes to multiply), in
+    // its 8-wave form (half the accumulators per wave, four waves per SIMD); 64-channel layers take 64x128,
+    // tiny problems 64x64.
+    if (a.K >= 128 && a.M >= 1024) return launch_cfg<128, 128, 2, 4>(a, vec, s);
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     return launch_cfg<64, 64, 2, 2>(a, vec, s);
 }
