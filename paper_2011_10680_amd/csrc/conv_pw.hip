@@ -15,7 +15,7 @@
 namespace hawq {
 
 template <int KC, int TP, bool INT4>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KC == 2 ? 2 : 3)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KC == 2 && TP == 2 ? 2 : 3)))
 conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
     constexpr int BKB = INT4 ? 32 : 64;             // bytes of 64 reduction elements in memory
     constexpr int NL = INT4 ? 1 : 2;                // 16-byte loads per lane per 64 elements
@@ -191,7 +191,7 @@ static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
     const int n_groups = (a.M + 32 * TP - 1) / (32 * TP);
     // fill every SIMD of the 256 CUs with as many waves as the register budget allows (3 for C = 64,
     // 2 for C = 128), each walking over several pixel groups
-    int n_seq = ((KC == 2 ? 2 : 3) * 4 * 256 + n_ct - 1) / n_ct;
+    int n_seq = ((KC == 2 && TP == 2 ? 2 : 3) * 4 * 256 + n_ct - 1) / n_ct;
     if (n_seq > n_groups) n_seq = n_groups;
     const int waves = n_seq * n_ct;
     const uint32_t blocks = (uint32_t)((waves + 3) / 4);

@@ -62,3 +62,35 @@ def test_layerwise_and_logits(hawq, arch, mixed, N):
     # reusing workspace slots must not change anything
     got2, _ = _forward_gpu(hawq, net, x, False)
     assert np.array_equal(got2, want)
+
+
+@pytest.mark.parametrize("arch,batch,mixed,seed", [(18, 64, False, 1002), (50, 128, False, 1003), (50, 256, True, 1004)])
+def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed):
+    """The network configurations at their full batch, in the launch configuration the benchmark times
+    (reused workspace slots).  The oracle computes a sample of images one by one (images are independent, so
+    a row of the batched logits must equal the single-image result); on top of that: run-to-run identical
+    bits, and the same image gives the same logits wherever it sits in the batch."""
+    import torch
+    bits = wl.draw_bits(arch, 4000 + arch) if mixed else None
+    net = wl.make_resnet(arch, seed=seed, bits=bits)
+    x = wl.make_image_batch(seed + 1, batch)
+    x[batch - 1] = x[0]                      # duplicate image at the other end of the batch
+    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
+    ws = torch.empty(hn.workspace_bytes(batch), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((batch, 1000), dtype=torch.int32, device="cuda")
+    xd = torch.from_numpy(x).cuda()
+    hn.hawq_forward_resnet(xd, batch, logits, ws)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    ws.fill_(0x5A)
+    logits.zero_()
+    hn.hawq_forward_resnet(xd, batch, logits, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), got), "two runs differ"
+    assert np.array_equal(got[0], got[batch - 1]), "same image, different logits at another batch position"
+    sample = sorted({0, 1, batch // 2 - 1, batch // 2, batch - 2})
+    want = onet.forward(net, x[sample])
+    for j, i in enumerate(sample):
+        assert np.array_equal(got[i], want[j]), "image %d of the full batch differs from the oracle" % i
+    assert len({got[i].tobytes() for i in range(batch - 1)}) == batch - 1   # distinct images, distinct logits
+    hn.close()
