@@ -432,12 +432,14 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (g_tile_override == 2) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     if (g_tile_override == 3) return launch_cfg<64, 64, 2, 2>(a, vec, s);
     if (g_tile_override == 4) return launch_cfg<128, 128, 2, 4>(a, vec, s);
+    if (g_tile_override == 5) return launch_cfg<128, 128, 4, 2>(a, vec, s);
     // Measured on MI355X over the ResNet layer shapes: with at least 128 output channels the 128x128 tile
     // wins (operand reuse: a CU's vector-memory path delivers ~60 B/clk and its LDS accepts ~70 B/clk of
     // writes, which a 128x128x64 step of INT8 MFMA consumes in exactly the time it takes to multiply), in
-    // its 8-wave form (half the accumulators per wave, four waves per SIMD); 64-channel layers take 64x128,
+    // its 8-wave form (a wave owns 32 channels x 64 pixels: half the accumulators, four waves per SIMD, and every
+    // per-channel parameter read in the epilogue serves two pixels); 64-channel layers take 64x128,
     // tiny problems 64x64.
-    if (a.K >= 128 && a.M >= 1024) return launch_cfg<128, 128, 2, 4>(a, vec, s);
+    if (a.K >= 128 && a.M >= 1024) return launch_cfg<128, 128, 4, 2>(a, vec, s);
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     return launch_cfg<64, 64, 2, 2>(a, vec, s);
 }
