@@ -20,7 +20,7 @@ constexpr int STEM_ROWS = 2 * STEM_TILE + 5;     // 37 input rows
 constexpr int STEM_COLS = 40;                    // patch width in pixels (38 used), origin = 2*q0 - 3
 constexpr int STEM_W_BYTES = 64 * 256;
 
-__global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, const int tiles_q, const int tiles_p) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) conv_stem_kernel(const ConvArgs a, const int tiles_q, const int tiles_p) {
     __shared__ __attribute__((aligned(16))) uint8_t lw[STEM_W_BYTES];
     __shared__ __attribute__((aligned(16))) uint32_t lx[STEM_ROWS * STEM_COLS];
     __shared__ ChanMain par_m[64];
