@@ -83,9 +83,46 @@ avgpool_kernel(const int HW, const int C, const int per, const int x_dt, const i
     }
 }
 
+// fast path: unsigned 8-bit input, 8-bit output, C % 256 == 0.  A workgroup owns 256 channels of one image:
+// 16 channel groups (16 bytes each) x 16 pixel slices; every thread adds up its slice's pixels with 16-byte
+// loads, the 16 partial sums of a channel group meet in LDS, one thread per channel requantises.
+__global__ void __launch_bounds__(256)
+avgpool_u8_kernel(const int HW, const int C, const uint8_t *__restrict__ x, const int32_t *__restrict__ b,
+                  const uint8_t *__restrict__ c, const int lo, const int hi, uint8_t *__restrict__ y) {
+    __shared__ int32_t part[16][256 + 8];
+    const int n = blockIdx.y, cbase = blockIdx.x * 256;
+    const int g = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    int32_t sum[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) sum[j] = 0;
+    const uint8_t *xp = x + (int64_t)n * HW * C + cbase + g * 16;
+    for (int i = sl; i < HW; i += 16) {
+        const uint4 v = *(const uint4 *)(xp + (int64_t)i * C);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            sum[4 * d + 0] += w[d] & 0xff; sum[4 * d + 1] += (w[d] >> 8) & 0xff;
+            sum[4 * d + 2] += (w[d] >> 16) & 0xff; sum[4 * d + 3] += w[d] >> 24;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) part[sl][g * 16 + j] = sum[j];
+    __syncthreads();
+    const int k = threadIdx.x;   // one channel per thread
+    int32_t t = 0;
+#pragma unroll
+    for (int s2 = 0; s2 < 16; ++s2) t += part[s2][k];
+    y[(int64_t)n * C + cbase + k] = (uint8_t)clamp64(rq64(t, b[cbase + k], c[cbase + k]), lo, hi);
+}
+
 hawq_status launch_avgpool(int N, int HW, int C, int x_dt, int y_dt, const void *x, const int32_t *b, const uint8_t *c,
                            int lo, int hi, void *y, hipStream_t s) {
     if (N == 0) return HAWQ_OK;
+    if (x_dt == HAWQ_U8 && (y_dt == HAWQ_U8 || y_dt == HAWQ_S8) && C % 256 == 0 && ((uintptr_t)x & 15) == 0) {
+        dim3 grid(C / 256, N);
+        avgpool_u8_kernel<<<grid, 256, 0, s>>>(HW, C, (const uint8_t *)x, b, c, lo, hi, (uint8_t *)y);
+        return check_launch();
+    }
     const bool any4 = is4(x_dt) || is4(y_dt);
     const int per = (C % 4 == 0 && ((uintptr_t)x & 3) == 0) ? 4 : (any4 ? 2 : 1);
     dim3 grid((C / per + 63) / 64, N);
