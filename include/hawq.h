@@ -198,7 +198,9 @@ hawq_status hawq_net_step_output(const hawq_net *net, int32_t N, int32_t step, c
 /*
  * Integer-only forward: x uint8 [N,image_hw,image_hw,3] (values 0..255) -> logits int32
  * [N,num_classes].  x, logits and workspace are device memory; workspace must hold
- * hawq_net_workspace_bytes(net, N) bytes, 256-byte aligned.  Enqueues every layer on `stream`.
+ * hawq_net_workspace_bytes(net, N) bytes, 256-byte aligned; x must be 16-byte aligned.  Enqueues every layer on
+ * `stream`.  Unless the network keeps its activations, conv1 and the max pool run as one kernel and the conv1
+ * tensor is never written to memory (its step reports an empty output).
  */
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream);

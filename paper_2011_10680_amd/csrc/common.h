@@ -73,6 +73,17 @@ __device__ __forceinline__ void static_for(F &&f) {
     }
 }
 
+// per-byte unsigned maximum of two packed dwords (through two 16-bit lanes)
+__device__ __forceinline__ uint32_t max_u8x4(uint32_t a, uint32_t b) {
+    // per-byte unsigned maximum through two 16-bit lanes
+    const uint32_t ae = a & 0x00ff00ffu, be = b & 0x00ff00ffu, ao = (a >> 8) & 0x00ff00ffu, bo = (b >> 8) & 0x00ff00ffu;
+    const uint32_t e = ((ae & 0xffff) > (be & 0xffff) ? (ae & 0xffff) : (be & 0xffff)) |
+                       ((ae >> 16) > (be >> 16) ? (ae & 0xffff0000u) : (be & 0xffff0000u));
+    const uint32_t o = ((ao & 0xffff) > (bo & 0xffff) ? (ao & 0xffff) : (bo & 0xffff)) |
+                       ((ao >> 16) > (bo >> 16) ? (ao & 0xffff0000u) : (bo & 0xffff0000u));
+    return e | (o << 8);
+}
+
 // XCD-aware remap of a linear workgroup id.  Workgroups are dealt round-robin to the 8 XCDs
 // (each with its own L2); this gives every XCD one contiguous range of logical tile ids so
 // neighbouring tiles (shared input halo, shared activation rows) meet in the same L2.
@@ -93,6 +104,8 @@ hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
 // bias corrected for the -128 input offset by the host (see net.cpp)
 hawq_status launch_conv_stem(const ConvArgs &a, hipStream_t s);
+// conv1 fused with the 3x3/2 max pool: writes only the pooled tensor (U8 or packed U4)
+hawq_status launch_conv_stem_pool(const ConvArgs &a, int pool_y_dt, int pool_lo, int pool_hi, void *pool_y, hipStream_t s);
 hawq_status launch_residual_add(int64_t n_pixels, int K, int m_dt, int r_dt, int y_dt, const void *m,
                                 const int32_t *m_b, const uint8_t *m_c, const void *r, const int32_t *r_b,
                                 const uint8_t *r_c, int lo, int hi, void *y, hipStream_t s);

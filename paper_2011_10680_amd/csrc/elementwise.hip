@@ -131,15 +131,6 @@ hawq_status launch_avgpool(int N, int HW, int C, int x_dt, int y_dt, const void 
 }
 
 // ---- max pool 3x3 / 2, pad 1 ----
-__device__ __forceinline__ uint32_t max_u8x4(uint32_t a, uint32_t b) {
-    // per-byte unsigned maximum through two 16-bit lanes
-    const uint32_t ae = a & 0x00ff00ffu, be = b & 0x00ff00ffu, ao = (a >> 8) & 0x00ff00ffu, bo = (b >> 8) & 0x00ff00ffu;
-    const uint32_t e = ((ae & 0xffff) > (be & 0xffff) ? (ae & 0xffff) : (be & 0xffff)) |
-                       ((ae >> 16) > (be >> 16) ? (ae & 0xffff0000u) : (be & 0xffff0000u));
-    const uint32_t o = ((ao & 0xffff) > (bo & 0xffff) ? (ao & 0xffff) : (bo & 0xffff)) |
-                       ((ao >> 16) > (bo >> 16) ? (ao & 0xffff0000u) : (bo & 0xffff0000u));
-    return e | (o << 8);
-}
 
 // fast path: U8 in, C % 16 == 0; one thread = 16 channels of one output pixel
 __global__ void __launch_bounds__(256)

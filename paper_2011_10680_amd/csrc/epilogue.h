@@ -257,7 +257,8 @@ __device__ __forceinline__ void epilogue_tile_general(const ConvArgs &a, const C
 //   2. y += (r * rb + 2^(rc-1)) >> rc  per shortcut type (u8 / s8 / u4), 24-bit multiply-add
 //   3. clamp, pack 4 (or 8) outputs per dword, 16-byte (8-byte) store per 16 channels
 // `wide` (a channel outside the narrow range) or a signed 4-bit tensor take the general form.
-template <int TC, int TP, bool PRE>
+// YLDS: a.y points into LDS (a kernel that keeps the requantised tile on chip); stores use LDS instructions.
+template <int TC, int TP, bool PRE, bool YLDS = false>
 __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
                                               const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide,
                                               const uint32_t (&pre)[TP][TC][4]) {
@@ -354,7 +355,14 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                     const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
                     w[q] = t0 | t1;
                 }
-                if (valid[tp]) *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+                if (valid[tp]) {
+                    if (YLDS) {
+                        typedef __attribute__((address_space(3))) v4i lds_v4i;
+                        *(lds_v4i *)(a.y + (m[tp] * (int64_t)a.K + chg)) = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                    } else {
+                        *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                }
             }
         }
     });

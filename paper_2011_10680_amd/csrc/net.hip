@@ -88,6 +88,8 @@ struct Step {
     const int32_t *bias = nullptr, *b = nullptr, *res_b = nullptr;
     const uint8_t *c = nullptr, *res_c = nullptr;
     double macs_per_image = 0, bytes_per_image = 0, bytes_fixed = 0;
+    bool fused_pool = false;      // conv1 step: the max pool is computed in the same kernel (writes the pool's tensor)
+    bool skip = false;            // max-pool step when conv1 has absorbed it: nothing to launch
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -311,6 +313,16 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         st.desc.y_lo = 0; st.desc.y_hi = act_hi(stage_bits);
         st.out = new_tensor(P, P, 64, act_dt(stage_bits));
         st.bytes_per_image = (double)L[0].P * L[0].Q * 64 + (double)tensor_bytes((int64_t)P * P * 64, act_dt(stage_bits));
+        // Unless every activation must be kept for inspection, conv1 and the pool run as one kernel and the
+        // conv1 tensor is never materialised: it needs no workspace and the pool step launches nothing.
+        if (!net->keep && image_hw % 4 == 0) {
+            st.skip = true;
+            st.bytes_per_image = 0;
+            Step &c1 = net->steps[0];
+            c1.fused_pool = true;
+            net->tensors[c1.out].elems_per_image = 0;
+            c1.bytes_per_image = (double)image_hw * image_hw * 3 + (double)tensor_bytes((int64_t)P * P * 64, act_dt(stage_bits));
+        }
         net->steps.push_back(st);
         t = st.out;
     }
@@ -447,7 +459,14 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
             rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
                                 outp, true, a, x_hi);
             if (rc == HAWQ_OK) {
-                if (st.kind == STEP_STEM && conv_stem_eligible(a)) {
+                if (st.kind == STEP_STEM && st.fused_pool && conv_stem_eligible(a)) {
+                    const Step &pool = net->steps[s + 1];
+                    a.w = st.w_stem;
+                    a.bias = st.bias_stem;
+                    rc = launch_conv_stem_pool(a, pool.desc.y_dtype, pool.desc.y_lo, pool.desc.y_hi, tptr(pool.out), stream);
+                } else if (st.kind == STEP_STEM && st.fused_pool) {
+                    rc = HAWQ_ERR_UNSUPPORTED;   // the image pointer is not 16-byte aligned
+                } else if (st.kind == STEP_STEM && conv_stem_eligible(a)) {
                     a.w = st.w_stem;
                     a.bias = st.bias_stem;
                     rc = launch_conv_stem(a, stream);
@@ -458,6 +477,7 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
             break;
         }
         case STEP_MAXPOOL:
+            if (st.skip && net->steps[s - 1].fused_pool) break;   // done inside conv1's kernel
             rc = launch_maxpool(N, st.desc.H, st.desc.W, st.desc.C, st.desc.x_dtype, st.desc.y_dtype, in, st.desc.y_lo,
                                 st.desc.y_hi, outp, stream);
             break;
