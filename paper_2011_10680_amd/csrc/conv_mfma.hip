@@ -20,7 +20,10 @@
 
 namespace hawq {
 
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
+// XOR swizzle of the four 16-byte chunks of a 64-byte tile row: with this choice of row bits every
+// 128-bit LDS fragment read of the MFMA layouts below (both operands, every tile shape) is free of bank
+// conflicts (checked with the LDS bank-conflict counter).
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 // Minimum waves per SIMD the register allocation must leave room for, by the wave's share of the tile:
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
