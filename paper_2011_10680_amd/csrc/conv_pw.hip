@@ -14,8 +14,10 @@
 
 namespace hawq {
 
-template <int KC, int TP, bool INT4>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(KC == 2 && TP == 2 ? 2 : 3)))
+// KC: 64-element chunks of the reduction (C / 64); TP: 32-pixel tiles per group; NS: groups in flight per wave
+// (ring of register stages); WPE: waves per SIMD the register allocation is held to.
+template <int KC, int TP, int NS, int WPE, bool INT4>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE)))
 conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
     constexpr int BKB = INT4 ? 32 : 64;             // bytes of 64 reduction elements in memory
     constexpr int NL = INT4 ? 1 : 2;                // 16-byte loads per lane per 64 elements
@@ -24,7 +26,8 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
     __shared__ ChanRes par_r[4][32];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int g = blockIdx.x * 4 + wave;
+    // workgroups that share pixels (consecutive channel tiles of one sequence) stay on one XCD and its L2
+    const int g = (int)xcd_remap(blockIdx.x, gridDim.x) * 4 + wave;
     const int ct = g % n_ct, seq = g / n_ct;
     if (seq >= n_seq) return;                        // whole wave; the kernel has no workgroup barrier
     const int rho = lane & 31, khalf = lane >> 5;
@@ -158,19 +161,35 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
         epilogue_tile<1, TP, true>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
     };
 
-    // two stages in flight: while group i is processed, group i + n_seq is landing
-    Stage s0, s1;
+    // NS - 1 groups in flight: while group i is processed, groups i + n_seq .. i + (NS-1) n_seq are landing
+    // (issue() past the last group presents out-of-range offsets and fetches nothing)
+    static_assert(NS >= 2 && NS <= 4, "ring depth");
+    Stage st0, st1, st2, st3;   // separate objects, named explicitly, so that each stays in registers
     int grp = seq;
-    issue(grp, s0);
+    issue(grp, st0);
+    if constexpr (NS >= 3) issue(grp + n_seq, st1);
+    if constexpr (NS >= 4) issue(grp + 2 * n_seq, st2);
+#define HAWQ_PW_STEP(cur, nxt)                      \
+    issue(grp + (NS - 1) * n_seq, nxt);             \
+    process(grp, cur);                              \
+    grp += n_seq;                                   \
+    if (grp >= n_groups) break;
     while (grp < n_groups) {
-        issue(grp + n_seq, s1);
-        process(grp, s0);
-        grp += n_seq;
-        if (grp >= n_groups) break;
-        issue(grp + n_seq, s0);
-        process(grp, s1);
-        grp += n_seq;
+        if constexpr (NS == 2) {
+            HAWQ_PW_STEP(st0, st1)
+            HAWQ_PW_STEP(st1, st0)
+        } else if constexpr (NS == 3) {
+            HAWQ_PW_STEP(st0, st2)
+            HAWQ_PW_STEP(st1, st0)
+            HAWQ_PW_STEP(st2, st1)
+        } else {
+            HAWQ_PW_STEP(st0, st3)
+            HAWQ_PW_STEP(st1, st0)
+            HAWQ_PW_STEP(st2, st1)
+            HAWQ_PW_STEP(st3, st2)
+        }
     }
+#undef HAWQ_PW_STEP
 }
 
 bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
@@ -185,25 +204,28 @@ bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
     return (int64_t)a.M >= 8192;   // enough pixels for persistent waves to reach a steady state
 }
 
-template <int KC, int TP>
+template <int KC, int TP, int NS, int WPE>
 static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
     const int n_ct = (a.K + 31) / 32;
     const int n_groups = (a.M + 32 * TP - 1) / (32 * TP);
-    // fill every SIMD of the 256 CUs with as many waves as the register budget allows (3 for C = 64,
-    // 2 for C = 128), each walking over several pixel groups
-    int n_seq = ((KC == 2 && TP == 2 ? 2 : 3) * 4 * 256 + n_ct - 1) / n_ct;
+    // fill every SIMD of the 256 CUs with as many waves as the register budget allows, each walking over
+    // several pixel groups
+    int n_seq = (WPE * 4 * 256 + n_ct - 1) / n_ct;
     if (n_seq > n_groups) n_seq = n_groups;
     const int waves = n_seq * n_ct;
     const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-    if (is4(a.x_dt)) conv_pw_kernel<KC, TP, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
-    else conv_pw_kernel<KC, TP, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    if (is4(a.x_dt)) conv_pw_kernel<KC, TP, NS, WPE, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    else conv_pw_kernel<KC, TP, NS, WPE, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
     return check_launch();
 }
 
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
-    if (a.C == 64) return launch_pw<1, 2>(a, s);
-    return launch_pw<2, 2>(a, s);
+    // measured: at C = 64 one pixel tile per group and four waves per SIMD hide the epilogue's integer work
+    // behind the memory stream best; at C = 128 two tiles per group (two waves per SIMD) are as good as any
+    // deeper or wider arrangement
+    if (a.C == 64) return launch_pw<1, 1, 2, 4>(a, s);
+    return launch_pw<2, 2, 2, 2>(a, s);
 }
 
 }  // namespace hawq
