@@ -10,6 +10,7 @@
 namespace hawq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // Everything a convolution kernel needs; passed by value as the kernel argument.

@@ -5,25 +5,40 @@
 // traffic and by the integer epilogue.  A tile-per-workgroup kernel spends its life in start-up
 // latency there.  Here a wave is persistent instead: it keeps the weights of its 32 output channels in
 // registers (they are only C/8 registers per lane) and its channels' requantisation parameters in a
-// wave-private LDS slot, then walks over pixel tiles with the next tile's activations and shortcut
+// wave-private LDS slot, then walks over pixel tiles with the next tiles' activations and shortcut
 // bytes already in flight while the current tile is multiplied, requantised and stored.  No
-// workgroup barrier, no LDS staging of operands; every activation byte is fetched straight into the
-// MFMA operand layout.
+// workgroup barrier.
+//
+// Activations travel global -> LDS (LDS-DMA buffer loads into a wave-private ring) -> MFMA fragments.
+// Fetching them straight into the MFMA operand layout would make every lane of a load instruction touch
+// its own cache line, which the vector memory path serves at a quarter of its rate (measured: ~16 instead
+// of ~60 bytes per clock per CU); the DMA form reads 64 contiguous bytes per four lanes.
 #include "common.h"
 #include "epilogue.h"
 
 namespace hawq {
 
 // KC: 64-element chunks of the reduction (C / 64); TP: 32-pixel tiles per group; NS: groups in flight per wave
-// (ring of register stages); WPE: waves per SIMD the register allocation is held to.
-template <int KC, int TP, int NS, int WPE, bool INT4>
+// (ring of LDS stages); WPE: waves per SIMD the register allocation is held to; RES: a shortcut is added.
+template <int KC, int TP, int NS, int WPE, bool RES, bool INT4>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE)))
 conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
-    constexpr int BKB = INT4 ? 32 : 64;             // bytes of 64 reduction elements in memory
-    constexpr int NL = INT4 ? 1 : 2;                // 16-byte loads per lane per 64 elements
+    static_assert(NS == 2 || NS == 3, "ring depth");
+    constexpr int BKB = INT4 ? 32 : 64;             // bytes of 64 reduction elements in memory = LDS row length
+    constexpr int SUB = 32 * BKB;                   // one 32-pixel x 64-element sub-tile
+    constexpr int STAGE = TP * KC * SUB;            // LDS bytes of one group of one wave
+    constexpr int ND = INT4 ? 1 : 2;                // DMA instructions (1 KB each) per sub-tile
+    // vector-memory instructions every wave issues per group, in program order: D loads into LDS and R
+    // shortcut loads (issue), later S stores (process).  The counts are the same for every wave and group,
+    // so the wait for a stage's arrival is an exact outstanding-operations count.
+    constexpr int D = TP * KC * ND, R = RES ? TP : 0, S = TP;
     constexpr uint32_t kInvalid = 0x80000000u;
     __shared__ ChanMain par_m[4][32];
     __shared__ ChanRes par_r[4][32];
+    // one array per ring slot: the compiler tracks asynchronous LDS writes per object
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[4 * STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs1[4 * STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs2[NS >= 3 ? 4 * STAGE : 1024];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // workgroups that share pixels (consecutive channel tiles of one sequence) stay on one XCD and its L2
@@ -77,58 +92,69 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
         }
     }
 
-    const bool has_res = a.res != nullptr;
     const bool r4 = is4(a.res_dt);
     const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(has_res ? a.res : a.x), 0, has_res ? (int)tensor_bytes((int64_t)a.M * a.K, a.res_dt) : 0, 0x00020000);
+        (void *)(RES ? a.res : a.x), 0, RES ? (int)tensor_bytes((int64_t)a.M * a.K, a.res_dt) : 0, 0x00020000);
     const bool unit = a.stride_h == 1 && a.stride_w == 1;   // 1x1, no padding: output pixel m reads input pixel m
     const int PQ = a.P * a.Q;
-
-    // raw operand loads of one group of TP pixel tiles (NL x 16 bytes per 64 elements) and its shortcut bytes
-    struct Stage {
-        v4i b[TP][KC][NL];
-        uint32_t r[TP][1][4];
+    auto pixel_offset = [&](int grp, int64_t m) -> uint32_t {   // byte offset of output pixel m's input row
+        if (grp >= n_groups || m >= a.M) return kInvalid;
+        if (unit) return (uint32_t)m * (uint32_t)Cb;
+        const int mi = (int)m;
+        const int n = mi / PQ, pq = mi - n * PQ;
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        return (uint32_t)(((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * Cb);
     };
-    auto issue = [&](int grp, Stage &st) {
+
+    // LDS layout of a sub-tile: 32 rows (pixels) of BKB bytes.  INT8: the four 16-byte chunks of a row are
+    // XOR-swizzled with (row >> 2) & 3, which makes the fragment reads below free of bank conflicts; a DMA
+    // instruction fills 16 rows, lane i writing slot i (row i/4, chunk i%4) with the chunk that belongs there.
+    // INT4: 32-byte rows, one instruction fills all 32 rows.
+    const int d_row = INT4 ? lane >> 1 : lane >> 2;                     // row within the instruction's rows
+    const int d_chunk = INT4 ? (lane & 1) : ((lane & 3) ^ ((d_row >> 2) & 3));
+    // (row >> 2) & 3 is the same for row and row + 16, so one chunk index serves both halves
+    struct Stage {
+        uint32_t r[TP][1][4];   // the lane's 16 shortcut bytes per tile
+    };
+    auto issue = [&](int grp, uint8_t *xs, Stage &st) {
 #pragma unroll
         for (int tp = 0; tp < TP; ++tp) {
-            const int64_t m = ((int64_t)grp * TP + tp) * 32 + rho;
-            const bool ok = grp < n_groups && m < a.M;
-            uint32_t off = kInvalid;
-            if (ok) {
-                if (unit) {
-                    off = (uint32_t)m * (uint32_t)Cb;
-                } else {
-                    const int mi = (int)m;
-                    const int n = mi / PQ, pq = mi - n * PQ;
-                    const int p = pq / a.Q, q = pq - p * a.Q;
-                    off = (uint32_t)(((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * Cb);
+            const int64_t mbase = ((int64_t)grp * TP + tp) * 32;
+#pragma unroll
+            for (int h = 0; h < ND; ++h) {
+                const uint32_t po = pixel_offset(grp, mbase + h * 16 + d_row);
+#pragma unroll
+                for (int kc = 0; kc < KC; ++kc) {
+                    const uint32_t off = po == kInvalid ? kInvalid : po + kc * BKB + d_chunk * 16;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rsrc_x, (__attribute__((address_space(3))) void *)(xs + wave * STAGE + (tp * KC + kc) * SUB + h * 1024),
+                        16, (int)off, 0, 0, 0);
                 }
             }
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-                for (int l = 0; l < NL; ++l)
-                    st.b[tp][kc][l] = __builtin_amdgcn_raw_buffer_load_b128(
-                        rsrc_x, (int)(off + kc * BKB + (INT4 ? khalf * 16 : l * 32 + khalf * 16)), 0, 0);
-            st.r[tp][0][0] = st.r[tp][0][1] = st.r[tp][0][2] = st.r[tp][0][3] = 0;
-            if (has_res) {
+            if (RES) {
                 // the lane's 16 channels of pixel m: 16 bytes (8 for 4-bit data)
+                const int64_t m = mbase + rho;
+                const bool ok = grp < n_groups && m < a.M;
                 const int64_t e = m * (int64_t)a.K + k0 + khalf * 16;
                 const uint32_t ro = (ok && k0 + khalf * 16 < a.K) ? (uint32_t)(r4 ? (e >> 1) : e) : kInvalid;
-                if (r4) {
-                    const uint2 t = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rsrc_r, (int)ro, 0, 0));
-                    st.r[tp][0][0] = t.x; st.r[tp][0][1] = t.y; st.r[tp][0][2] = 0; st.r[tp][0][3] = 0;
-                } else {
-                    const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)ro, 0, 0);
-                    st.r[tp][0][0] = (uint32_t)t[0]; st.r[tp][0][1] = (uint32_t)t[1];
-                    st.r[tp][0][2] = (uint32_t)t[2]; st.r[tp][0][3] = (uint32_t)t[3];
-                }
+                // one 16-byte load for either width (4-bit data uses the first 8 bytes; bytes past the end of the
+                // buffer read as zero), so that the count of outstanding operations is static
+                const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)ro, 0, 0);
+                st.r[tp][0][0] = (uint32_t)t[0]; st.r[tp][0][1] = (uint32_t)t[1];
+                st.r[tp][0][2] = (uint32_t)t[2]; st.r[tp][0][3] = (uint32_t)t[3];
+            } else {
+                st.r[tp][0][0] = st.r[tp][0][1] = st.r[tp][0][2] = st.r[tp][0][3] = 0;
             }
         }
     };
 
-    auto process = [&](int grp, const Stage &st) {
+    // the exact general epilogue issues a data-dependent number of stores; after it everything is drained,
+    // which keeps the static operation counts below valid
+    const bool slow_epilogue = wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4);
+    const int swz = (rho >> 2) & 3;
+    auto process = [&](int grp, const uint8_t *xs, const Stage &st, auto nwaitc) {
+        // wait until at most NWAIT vector-memory operations issued after this stage's loads are outstanding
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(nwaitc)::value) : "memory");
         v16i acc[TP][1];
         int64_t mm[TP];
         bool valid[TP];
@@ -143,53 +169,74 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
         for (int tp = 0; tp < TP; ++tp)
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) {
+                const uint8_t *sub = xs + wave * STAGE + (tp * KC + kc) * SUB + rho * BKB;
                 v4i b0, b1;
                 if (INT4) {
+                    const v4i raw = *(const v4i *)(sub + khalf * 16);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const uint32_t u = (uint32_t)st.b[tp][kc][0][e];
+                        const uint32_t u = (uint32_t)raw[e];
                         b0[e] = (int)(u & 0x0F0F0F0Fu);
                         b1[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
                     }
                 } else {
-                    b0 = st.b[tp][kc][0];
-                    b1 = st.b[tp][kc][NL - 1];
+                    b0 = *(const v4i *)(sub + ((khalf ^ swz) << 4));
+                    b1 = *(const v4i *)(sub + (((2 + khalf) ^ swz) << 4));
                 }
                 acc[tp][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc[tp][0], 0, 0, 0);
                 acc[tp][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[tp][0], 0, 0, 0);
             }
-        epilogue_tile<1, TP, true>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
+        epilogue_tile<1, TP, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
+        if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
 
-    // NS - 1 groups in flight: while group i is processed, groups i + n_seq .. i + (NS-1) n_seq are landing
-    // (issue() past the last group presents out-of-range offsets and fetches nothing)
-    static_assert(NS >= 2 && NS <= 4, "ring depth");
-    Stage st0, st1, st2, st3;   // separate objects, named explicitly, so that each stays in registers
+    // Ring of NS stages: while group i is processed, groups i + n_seq .. i + (NS-1) n_seq are landing
+    // (issue() past the last group presents out-of-range offsets and fetches nothing, but still counts).
+    // Operations issued after a stage's own loads when its turn comes: the loads of the NS-1 later stages and
+    // the stores of the groups processed since -- none for the first group, up to NS-1 groups' worth later.
+    Stage st0, st1, st2;   // separate named objects so that each stays in registers
+    using W0 = std::integral_constant<int, (NS - 1) * (D + R)>;
+    using W1 = std::integral_constant<int, (NS - 1) * (D + R) + S>;
+    using WN = std::integral_constant<int, (NS - 1) * (D + R) + (NS - 1) * S>;
     int grp = seq;
-    issue(grp, st0);
-    if constexpr (NS >= 3) issue(grp + n_seq, st1);
-    if constexpr (NS >= 4) issue(grp + 2 * n_seq, st2);
-#define HAWQ_PW_STEP(cur, nxt)                      \
-    issue(grp + (NS - 1) * n_seq, nxt);             \
-    process(grp, cur);                              \
-    grp += n_seq;                                   \
-    if (grp >= n_groups) break;
-    while (grp < n_groups) {
-        if constexpr (NS == 2) {
-            HAWQ_PW_STEP(st0, st1)
-            HAWQ_PW_STEP(st1, st0)
-        } else if constexpr (NS == 3) {
-            HAWQ_PW_STEP(st0, st2)
-            HAWQ_PW_STEP(st1, st0)
-            HAWQ_PW_STEP(st2, st1)
-        } else {
-            HAWQ_PW_STEP(st0, st3)
-            HAWQ_PW_STEP(st1, st0)
-            HAWQ_PW_STEP(st2, st1)
-            HAWQ_PW_STEP(st3, st2)
+    if constexpr (NS == 2) {
+        issue(grp, xs0, st0);
+        issue(grp + n_seq, xs1, st1);
+        process(grp, xs0, st0, W0{});
+        grp += n_seq;
+        while (grp < n_groups) {
+            issue(grp + n_seq, xs0, st0);
+            process(grp, xs1, st1, WN{});
+            grp += n_seq;
+            if (grp >= n_groups) break;
+            issue(grp + n_seq, xs1, st1);
+            process(grp, xs0, st0, WN{});
+            grp += n_seq;
+        }
+    } else {
+        issue(grp, xs0, st0);
+        issue(grp + n_seq, xs1, st1);
+        issue(grp + 2 * n_seq, xs2, st2);
+        process(grp, xs0, st0, W0{});
+        grp += n_seq;
+        if (grp >= n_groups) return;
+        issue(grp + 2 * n_seq, xs0, st0);
+        process(grp, xs1, st1, W1{});
+        grp += n_seq;
+        while (grp < n_groups) {
+            issue(grp + 2 * n_seq, xs1, st1);
+            process(grp, xs2, st2, WN{});
+            grp += n_seq;
+            if (grp >= n_groups) break;
+            issue(grp + 2 * n_seq, xs2, st2);
+            process(grp, xs0, st0, WN{});
+            grp += n_seq;
+            if (grp >= n_groups) break;
+            issue(grp + 2 * n_seq, xs0, st0);
+            process(grp, xs1, st1, WN{});
+            grp += n_seq;
         }
     }
-#undef HAWQ_PW_STEP
 }
 
 bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
@@ -204,8 +251,8 @@ bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
     return (int64_t)a.M >= 8192;   // enough pixels for persistent waves to reach a steady state
 }
 
-template <int KC, int TP, int NS, int WPE>
-static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
+template <int KC, int TP, int NS, int WPE, bool RES>
+static hawq_status launch_pw_res(const ConvArgs &a, hipStream_t s) {
     const int n_ct = (a.K + 31) / 32;
     const int n_groups = (a.M + 32 * TP - 1) / (32 * TP);
     // fill every SIMD of the 256 CUs with as many waves as the register budget allows, each walking over
@@ -214,9 +261,14 @@ static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
     if (n_seq > n_groups) n_seq = n_groups;
     const int waves = n_seq * n_ct;
     const uint32_t blocks = (uint32_t)((waves + 3) / 4);
-    if (is4(a.x_dt)) conv_pw_kernel<KC, TP, NS, WPE, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
-    else conv_pw_kernel<KC, TP, NS, WPE, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    if (is4(a.x_dt)) conv_pw_kernel<KC, TP, NS, WPE, RES, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    else conv_pw_kernel<KC, TP, NS, WPE, RES, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
     return check_launch();
+}
+
+template <int KC, int TP, int NS, int WPE>
+static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
+    return a.res != nullptr ? launch_pw_res<KC, TP, NS, WPE, true>(a, s) : launch_pw_res<KC, TP, NS, WPE, false>(a, s);
 }
 
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {

@@ -257,8 +257,11 @@ __device__ __forceinline__ void epilogue_tile_general(const ConvArgs &a, const C
 //   2. y += (r * rb + 2^(rc-1)) >> rc  per shortcut type (u8 / s8 / u4), 24-bit multiply-add
 //   3. clamp, pack 4 (or 8) outputs per dword, 16-byte (8-byte) store per 16 channels
 // `wide` (a channel outside the narrow range) or a signed 4-bit tensor take the general form.
-// YLDS: a.y points into LDS (a kernel that keeps the requantised tile on chip); stores use LDS instructions.
-template <int TC, int TP, bool PRE, bool YLDS = false>
+// YMODE 0: plain global stores of the valid pixels.  1: a.y points into LDS (a kernel that keeps the requantised
+// tile on chip); stores use LDS instructions.  2: every lane issues its store as a buffer store, invalid pixels
+// with an out-of-range offset that the hardware drops -- the number of memory instructions is then the same
+// for every wave, which lets a caller count outstanding operations exactly.
+template <int TC, int TP, bool PRE, int YMODE = 0>
 __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain *pm, const ChanRes *pr, const int64_t (&m)[TP],
                                               const bool (&valid)[TP], int k0, int chl, const v16i (&acc)[TP][TC], int wide,
                                               const uint32_t (&pre)[TP][TC][4]) {
@@ -269,6 +272,8 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
         return;
     }
     const bool y4 = is4(y_dt);
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.y, 0, YMODE == 2 ? (int)tensor_bytes((int64_t)a.M * a.K, y_dt) : 0, 0x00020000);
     // clamp bounds in vector registers so the clamp is a single three-operand median
     int32_t lo = a.lo, hi = a.hi;
     asm volatile("" : "+v"(lo), "+v"(hi));
@@ -343,7 +348,12 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                     w0 |= (uint32_t)y[tp][i] << (4 * i);
                     w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
                 }
-                if (valid[tp]) *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+                if (YMODE == 2) {
+                    const uint32_t off = valid[tp] ? (uint32_t)((m[tp] * (int64_t)a.K + chg) >> 1) : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, make_uint2(w0, w1)), yrs, (int)off, 0, 0);
+                } else if (valid[tp]) {
+                    *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+                }
             }
         } else {
 #pragma unroll
@@ -355,8 +365,11 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                     const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
                     w[q] = t0 | t1;
                 }
-                if (valid[tp]) {
-                    if (YLDS) {
+                if (YMODE == 2) {
+                    const uint32_t off = valid[tp] ? (uint32_t)(m[tp] * (int64_t)a.K + chg) : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, yrs, (int)off, 0, 0);
+                } else if (valid[tp]) {
+                    if (YMODE == 1) {
                         typedef __attribute__((address_space(3))) v4i lds_v4i;
                         *(lds_v4i *)(a.y + (m[tp] * (int64_t)a.K + chg)) = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
                     } else {
