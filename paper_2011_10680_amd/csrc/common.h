@@ -99,7 +99,7 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s);     // requires 
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi);
 void set_tile_override(int t);
 hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
-// persistent streaming kernel for 1x1 convolutions with C = 64 / 128 and many pixels
+// persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the

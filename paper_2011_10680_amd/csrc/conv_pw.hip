@@ -1,4 +1,4 @@
-// Pointwise (1x1) quantised convolution for shallow reductions (C = 64 or 128), streaming form.
+// Pointwise (1x1) quantised convolution for shallow reductions (C = 64, 128 or 256), streaming form.
 //
 // These layers (the expanding 1x1 of a bottleneck with its residual, the stride-1 transition
 // convolution, the first reducing 1x1) do a handful of MFMAs per output tile and are bound by HBM
@@ -242,7 +242,9 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
 bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
     if (!conv_mfma_eligible(a, x_hi)) return false;
     if (a.R != 1 || a.S != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
-    if (a.C != 64 && a.C != 128) return false;   // measured: at C = 256 the tiled kernel is as fast or faster
+    // measured: at C = 256 this form wins for narrow outputs (few channel tiles re-read the pixels); from
+    // K = 256 on the tiled kernel is as fast or faster
+    if (a.C != 64 && a.C != 128 && !(a.C == 256 && a.K <= 128)) return false;
     if (a.b == nullptr || a.y_dt == HAWQ_S32) return false;
     if (a.K % 16 != 0) return false;
     uintptr_t al = (uintptr_t)a.y | (uintptr_t)a.res;
@@ -277,6 +279,7 @@ hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {
     // behind the memory stream best; at C = 128 two tiles per group (two waves per SIMD) are as good as any
     // deeper or wider arrangement
     if (a.C == 64) return launch_pw<1, 1, 2, 4>(a, s);
+    if (a.C == 256) return launch_pw<4, 1, 2, 2>(a, s);
     return launch_pw<2, 2, 2, 2>(a, s);
 }
 

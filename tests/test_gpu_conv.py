@@ -72,7 +72,7 @@ _SHAPES_PW = [
     (4, 56, 56, 64, 256, 1, 1, 1, 0, 4, True),     # packed 4-bit, 4-bit shortcut
     (3, 60, 60, 128, 64, 1, 1, 2, 0, 4, False),    # packed 4-bit, strided, ragged
     (9, 33, 31, 64, 64, 1, 1, 1, 0, 8, True),
-    (5, 56, 56, 256, 128, 1, 1, 2, 0, 8, False),   # C = 256, strided
+    (11, 56, 56, 256, 128, 1, 1, 2, 0, 8, False),  # C = 256, strided
     (3, 59, 59, 256, 96, 1, 1, 1, 0, 8, True),     # C = 256, ragged, shortcut
     (5, 56, 56, 256, 64, 1, 1, 1, 0, 4, False),    # C = 256, packed 4-bit
 ]
