@@ -98,6 +98,7 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks) {
 hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s);     // requires conv_mfma_eligible
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi);
 void set_tile_override(int t);
+int tile_override();
 hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
 // persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);

@@ -25,6 +25,8 @@ namespace hawq {
 // conflicts (checked with the LDS bank-conflict counter).
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
+constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-out) the step table holds
+
 // Minimum waves per SIMD the register allocation must leave room for, by the wave's share of the tile:
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
 // shapes live on occupancy).
@@ -58,9 +60,14 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     };
     __shared__ ChanMain par_m[BC];
     __shared__ ChanRes par_r[BC];
+    // Per K-step addressing, tabulated once per workgroup: {weight offset, activation tap offset, r | s << 16}.
+    // Deriving these in the loop costs each wave some twenty scalar instructions per step, and the one scalar
+    // unit of a CU serves all its waves: with sixteen waves resident that alone approaches the duration of
+    // the step's MFMAs.
+    __shared__ int4 steptab[kMaxSteps];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: LDS-DMA bases stay in SGPRs
     const int wc = wave % WC, wp = wave / WC;
 
     const uint32_t L = xcd_remap(blockIdx.x, nblocks);
@@ -71,6 +78,15 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int cchunks = a.C / 64;                 // K-steps per tap
     const int steps = a.R * a.S * cchunks;
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
+    for (int i = tid; i < steps + 8; i += T) {
+        const int st = i < steps ? i : steps - 1;      // past the last step the activation address stays put ...
+        const int cc = st % cchunks, t = st / cchunks;
+        const int s_ = t % a.S, r_ = t / a.S;
+        // ... and the weight offset leaves the buffer: the weights read as zeros, padded iterations add nothing
+        steptab[i] = make_int4(i < steps ? i * (INT4 ? 32 : 64) : 0x40000000, (r_ * a.W + s_) * Cb + cc * (INT4 ? 32 : 64),
+                               r_ | (s_ << 16), 0);
+    }
+    __syncthreads();
 
     // ---- per-thread load bookkeeping ----
     // Operands are fetched with buffer loads: a lane whose row is past the tensor edge, or whose
@@ -121,30 +137,32 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // (past the last step they re-read it): under a branch the compiler could not count outstanding loads
     // and would wait for all of them before every LDS write.
     v4i ra[2][NA], rb[2][NB];
-    int r = 0, s = 0, cc = 0;  // tap and channel chunk of the K-step being *loaded*
+    // K-steps are fetched strictly in order; `ent` is the table entry of the next step to fetch, itself read
+    // one fetch ahead so that its LDS latency is never waited for
+    int tab_i = 0;
+    int4 ent = steptab[0];
     // gload(step, set): register path -- fetch K-step `step` into register set `set`.
     // gload(step, buf) with DMA -- fetch K-step `step` straight into LDS buffer `buf`: every wave-instruction
     // fills 64 consecutive 16-byte chunks (16 tile rows), the destination base is wave-uniform.
     auto gload = [&](int step, auto setc) {
         constexpr int set = decltype(setc)::value;
-        // uniform -> SGPR offset; past the last K-step the offset leaves the buffer, the weights read as
-        // zeros and the padded iterations of the unrolled loop add nothing
-        const int a_soff = step < steps ? step * BKB : 0x40000000;
-        const int tapoff = (r * a.W + s) * Cb + cc * BKB;                   // uniform
+        (void)step;
+        const uint32_t a_off = (uint32_t)ent.x, tapoff = (uint32_t)ent.y;
+        const int r = ent.z & 0xffff, s = ent.z >> 16;
 #pragma unroll
         for (int j = 0; j < NA; ++j) {
             if constexpr (DMA) {
                 if (NA * T != BC * CPR && tid + j * T >= BC * CPR) continue;   // (never for INT8: tiles divide evenly)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     rsrc_w, (__attribute__((address_space(3))) void *)(ldsbuf(setc) + (j * (T / 64) + wave) * 1024), 16,
-                    (int)a_voff[j], a_soff, 0, 0);
+                    (int)(a_voff[j] + a_off), 0, 0, 0);
             } else {
-                ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)a_voff[j], a_soff, 0);
+                ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)(a_voff[j] + a_off), 0, 0);
             }
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            uint32_t off = b_voff[j] + (uint32_t)tapoff;
+            uint32_t off = b_voff[j] + tapoff;
             if (padded) {
                 const bool ok = b_ok[j] & ((unsigned)(b_ih0[j] + r) < (unsigned)a.H) & ((unsigned)(b_iw0[j] + s) < (unsigned)a.W);
                 off = ok ? off : kInvalid;
@@ -157,15 +175,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 rb[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
             }
         }
-        // advance to the next K-step without branches (scalar selects); past the last step stay put
-        const int adv = (step + 1 < steps) ? 1 : 0;
-        cc += adv;
-        const int wrap_c = (cc == cchunks) ? 1 : 0;
-        cc = wrap_c ? 0 : cc;
-        s += wrap_c;
-        const int wrap_s = (s == a.S) ? 1 : 0;
-        s = wrap_s ? 0 : s;
-        r += wrap_s;
+        ent = steptab[++tab_i];
     };
 
     // LDS write addresses in buffer 0 (per chunk; INT4 writes two 16-byte pieces)
@@ -407,6 +417,7 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
         if (a.x_dt != HAWQ_U8 && a.x_dt != HAWQ_S8) return false;
     }
     if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
+    if ((int64_t)a.R * a.S * (a.C / 64) + 8 > kMaxSteps) return false;   // the per-step address table is in LDS
     return true;
 }
 
@@ -424,6 +435,7 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s) {
 
 static int g_tile_override = 0;   // 0: heuristic; 1..3: force a tile shape (measurement hook)
 void set_tile_override(int t) { g_tile_override = t; }
+int tile_override() { return g_tile_override; }
 
 hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
