@@ -11,6 +11,7 @@ weights are resident in HBM before the timed region.  Prints ONE JSON line on st
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -44,6 +45,18 @@ def cpu_baseline(net, images):
     dt = time.perf_counter() - t0
     return dict(value=images / dt, unit="images/s", cores=cores, kind="oracle",
                 sample="%d images of the same network and input distribution, %.1f s" % (images, dt))
+
+
+def profiled_traffic(workload):
+    """HBM bytes one forward moved under rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel
+    calibration), read from the committed summary of that profile; None if there is none for this workload."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "forward_%s.md" % workload)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"all kernels of one forward, scaled by the copy factors: read ([0-9.]+) MB, written ([0-9.]+) MB", text)
+    return (float(m.group(1)) + float(m.group(2))) * 1e6 if m else None
 
 
 def main():
@@ -97,11 +110,17 @@ def main():
     for _ in range(args.warmup):
         hn.hawq_forward_resnet(x, N, logits, ws, stream)
     torch.cuda.synchronize()
+    # the K timed steps, bracketed by synchronisation (wall clock) and by two HIP events recorded on the
+    # stream the library launches on (device time of the whole region)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         hn.hawq_forward_resnet(x, N, logits, ws, stream)
+    ev1.record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
     # per-launch device times (HIP events recorded by the library on the same stream), median of a few passes
     reps = max(3, min(10, args.steps))
@@ -120,20 +139,29 @@ def main():
     conv_ms = sum(r["ms"] for r in conv_rows)
     conv_bytes = sum(r["mbytes"] for r in conv_rows) * 1e6
     conv_ops = 2 * sum(r["gmac"] for r in conv_rows) * 1e9
-    # Roofline of the dominant kernel (the matrix-core convolution, all its launches of one forward):
-    # with every layer reading its input and writing its output once the ResNet50 forward moves more
-    # bytes-time than MFMA-time on this chip, so the bound is HBM.
-    t_mem = conv_bytes / (PEAK_HBM_GBS * 1e9)
-    t_mfma = conv_ops / (PEAK_INT8_TOPS * 1e12)
-    achieved_gbs = conv_bytes / (conv_ms * 1e-3) / 1e9
-    achieved_tops = conv_ops / (conv_ms * 1e-3) / 1e12
+    # Roofline of the path.  One "launch" is one forward: the chain of kernels (fused conv1 + max pool, the
+    # matrix-core convolutions, average pool, FC) over one batch.  Algorithmic bytes: every layer reads its
+    # input (and shortcut) once and writes its output once, weights and per-channel parameters once.  At
+    # 8 TB/s those bytes take longer than the forward's MACs at the INT8 MFMA peak, so the bound is HBM.
+    # Duration: the two HIP events around the timed region, per step.
+    total_bytes = sum(r["mbytes"] for r in rows) * 1e6
+    total_ops = 2 * total_macs
+    t_mem = total_bytes / (PEAK_HBM_GBS * 1e9)
+    t_mfma = total_ops / (PEAK_INT8_TOPS * 1e12)
+    achieved_gbs = total_bytes / (ev_ms_per_step * 1e-3) / 1e9
+    achieved_tops = total_ops / (ev_ms_per_step * 1e-3) / 1e12
     if t_mem >= t_mfma:
         roof = dict(bound="hbm", achieved=achieved_gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=achieved_gbs / PEAK_HBM_GBS)
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
-    roof.update(traffic=None, kernel="conv_mfma_kernel (all %d launches of one forward)" % len(conv_rows),
-                launches_ms=conv_ms, mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
-                hbm_gbs=achieved_gbs, hbm_frac=achieved_gbs / PEAK_HBM_GBS)
+    roof.update(traffic=profiled_traffic(args.workload),
+                kernel="one forward = %d launches (conv_stem_pool, conv_mfma, conv_pw, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
+                launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
+                mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
+                # the matrix-core convolutions alone, from per-launch events (each interval also holds a few
+                # microseconds of launch and event overhead that the untimed forward does not pay)
+                conv_kernels=dict(launches=len(conv_rows), launches_ms=conv_ms, gbs=conv_bytes / (conv_ms * 1e-3) / 1e9,
+                                  tops=conv_ops / (conv_ms * 1e-3) / 1e12))
 
     out = {
         "metric": "resnet%d_int_only_images_per_sec" % arch, "value": N / (ms_per_step * 1e-3), "unit": "images/s",
