@@ -99,6 +99,9 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s);     // requires 
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi);
 void set_tile_override(int t);
 int tile_override();
+// 3x3 / stride 1 / pad 1, 64 -> 64 channels, INT8: weights resident in LDS, pixel operand kept across the taps
+bool conv3x3_c64_eligible(const ConvArgs &a, int x_hi);
+hawq_status launch_conv3x3_c64(const ConvArgs &a, hipStream_t s);
 hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
 // persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);

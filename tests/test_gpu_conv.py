@@ -113,6 +113,43 @@ def test_pointwise_streaming_signed_shortcut_and_wide_parameters(hawq):
     assert_same(got, want3, "saturating parameters")
 
 
+# 3x3 / stride 1 / pad 1 with 64 -> 64 channels and many pixels: the persistent kernel with resident weights
+@pytest.mark.parametrize("N,H,W,res,res_signed,y_dt,y_hi", [
+    (11, 56, 56, False, False, 0, 127),     # ResNet50 stage-1 shape
+    (11, 56, 56, True, False, 0, 127),      # ResNet18 stage-1 shape: shortcut added
+    (13, 53, 51, True, True, 0, 127),       # ragged tile tail, odd image size, signed shortcut
+    (40, 30, 29, False, False, 2, 15),      # narrow images (several image rows per tile), packed 4-bit output
+    (70, 22, 23, True, False, 1, 127),      # many small images: tiles straddle images; signed output
+])
+def test_conv3x3_64_channels_resident_weights(hawq, N, H, W, res, res_signed, y_dt, y_hi):
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=N + H + W, N=N, H=H, W=W, C=64, K=64, R=3, S=3, stride=1, pad=1, bits=8,
+                                 with_residual=res, res_signed=res_signed), 8)
+    if y_hi == 15:
+        case["c"] = (case["c"] + 3).astype(np.uint8)     # 4-bit output range: eight times coarser
+    signed_out = y_dt == 1
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, y_dt, res_dt=hawq.S8 if res_signed else hawq.U8,
+                             relu=0 if signed_out else 1, y_lo=-128 if signed_out else 0, y_hi=y_hi, x_hi=127)
+    assert_same(got, want, str((N, H, W)))
+    v = oracle.unpack(want, oracle.U4) if y_dt == 2 else want.astype(np.int32)
+    assert 0.05 < (v != 0).mean() and (v == y_hi).mean() < 0.5
+
+
+def test_conv3x3_64_channels_wide_parameters(hawq):
+    """Multipliers outside the narrow epilogue's range take the exact 64-bit path inside the persistent kernel."""
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=31, N=11, H=56, W=56, C=64, K=64, R=3, S=3, stride=1, pad=1, bits=8,
+                                 with_residual=True), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want, "narrow")
+    wide = dict(case)
+    wide["b"] = (case["b"].astype(np.int64) << 14).astype(np.int32)
+    wide["c"] = (case["c"].astype(np.int32) + 14).astype(np.uint8)
+    got, want2 = run_conv_gpu(wide, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want2, "wide parameters")
+    assert np.array_equal(want, want2)
+
+
 @pytest.mark.parametrize("res_signed,y_dt,relu,lo,hi", [(False, 0, 1, 0, 127), (True, 0, 1, 0, 127), (True, 1, 0, -128, 127),
                                                          (False, 4, 0, -100000, 100000), (False, 2, 1, 0, 15)])
 def test_int8_conv_residual_and_output_types(hawq, res_signed, y_dt, relu, lo, hi):
