@@ -101,6 +101,7 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     if (conv_pw_eligible(a, x_hi)) return launch_conv_pw(a, s);
+    if (tile_override() == 0 && conv_pws_eligible(a, x_hi)) return launch_conv_pws(a, s);
     if (tile_override() == 0 && conv3x3_c64_eligible(a, x_hi)) return launch_conv3x3_c64(a, s);
     if (conv_mfma_eligible(a, x_hi)) return launch_conv_mfma(a, s);
     return launch_conv_direct(a, s);

@@ -106,6 +106,9 @@ hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid
 // persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);
+// same, for C = 256 with K >= 256 a multiple of 128: the activation stage is shared by a workgroup's four waves
+bool conv_pws_eligible(const ConvArgs &a, int x_hi);
+hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s);
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
 // bias corrected for the -128 input offset by the host (see net.cpp)
 hawq_status launch_conv_stem(const ConvArgs &a, hipStream_t s);

@@ -239,6 +239,173 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
     }
 }
 
+// Variant for C = 256 with many output channels: the four waves of a workgroup work on
+// four consecutive channel tiles of the *same* pixels, so the activation stage is fetched once per workgroup
+// (each wave a quarter of it) into a ring of four shared LDS stages, three groups ahead.  With a stage per wave
+// the LDS budget allows a ring of two only, and a wave's walk then advances one memory latency per group.
+// One workgroup barrier per group (a stage's arrival; it also orders the stage's reuse).  INT8 operands.
+template <int KC, int WPE, bool RES>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE)))
+conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
+    constexpr int NS = 4;
+    constexpr int STAGE = KC * 2048;                // 32 pixels x C bytes
+    constexpr int DW = KC * 2 / 4;                  // LDS-DMA instructions (1 KB) per wave and stage
+    static_assert(KC % 2 == 0, "stage split");
+    constexpr int R = RES ? 1 : 0, S = 1;           // shortcut loads, stores per wave and group
+    constexpr uint32_t kInvalid = 0x80000000u;
+    __shared__ ChanMain par_m[4][32];
+    __shared__ ChanRes par_r[4][32];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs1[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs2[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs3[STAGE];
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // the launch makes n_ct a multiple of 4 and the grid exactly n_seq * n_ct / 4 workgroups: the four waves
+    // of a workgroup share `seq` (so every wave reaches every barrier the same number of times)
+    const int g = (int)xcd_remap(blockIdx.x, gridDim.x) * 4 + wave;
+    const int ct = g % n_ct, seq = g / n_ct;
+    const int rho = lane & 31, khalf = lane >> 5;
+    const int k0 = ct * 32;
+    const int Cb = a.C;
+
+    int wide = 0;
+    {
+        ChanMain m;
+        ChanRes r;
+        if (khalf == 0) {
+            wide = stage_channel(a, k0 + rho, m, r);
+            par_m[wave][rho] = m;
+            par_r[wave][rho] = r;
+        }
+        wide = __any(wide);
+    }
+    const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * Cb), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.N * a.H * a.W * Cb), 0x00020000);
+    // The wave's 32 x C weight bytes reach its registers through LDS: fetched with coalesced LDS-DMA loads into
+    // the stage buffer of the same number as the wave (a stage is exactly 32 rows x C bytes), then read as MFMA
+    // row fragments.  Loading them straight into the fragment layout makes every lane touch its own cache line,
+    // and with a dozen waves per CU starting at once that alone costs microseconds.
+    v4i A[KC][2];
+    {
+        uint8_t *wst = wave == 0 ? xs0 : (wave == 1 ? xs1 : (wave == 2 ? xs2 : xs3));
+        const int w_row = lane >> 2;
+        const int w_chunk = (lane & 3) ^ ((w_row >> 2) & 3);
+#pragma unroll
+        for (int inst = 0; inst < 2 * KC; ++inst) {
+            const int kc = inst >> 1, h = inst & 1;
+            const int k = k0 + h * 16 + w_row;
+            const uint32_t off = k < a.K ? (uint32_t)(k * Cb + kc * 64 + w_chunk * 16) : kInvalid;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, (__attribute__((address_space(3))) void *)(wst + inst * 1024), 16,
+                                                     (int)off, 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int row = hsel * 16 + isel;
+        const int sw = (row >> 2) & 3;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+                A[kc][kk] = *(const v4i *)(wst + kc * 2048 + row * 64 + (((kk * 2 + khalf) ^ sw) << 4));
+        __syncthreads();    // every wave has its weights (and parameters) before the stage buffers are reused
+    }
+    const bool r4 = is4(a.res_dt);
+    const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(RES ? a.res : a.x), 0, RES ? (int)tensor_bytes((int64_t)a.M * a.K, a.res_dt) : 0, 0x00020000);
+    const bool unit = a.stride_h == 1 && a.stride_w == 1;
+    const int PQ = a.P * a.Q;
+    auto pixel_offset = [&](int grp, int64_t m) -> uint32_t {
+        if (grp >= n_groups || m >= a.M) return kInvalid;
+        if (unit) return (uint32_t)m * (uint32_t)Cb;
+        const int mi = (int)m;
+        const int n = mi / PQ, pq = mi - n * PQ;
+        const int p = pq / a.Q, q = pq - p * a.Q;
+        return (uint32_t)(((n * a.H + p * a.stride_h) * a.W + q * a.stride_w) * Cb);
+    };
+    // stage layout: KC sub-tiles of 32 rows x 64 B (chunks XOR-swizzled with (row >> 2) & 3); the 2 KC fetch
+    // instructions of a stage (16 rows of one sub-tile each) are dealt round-robin to the four waves
+    const int d_row = lane >> 2;
+    const int d_chunk = (lane & 3) ^ ((d_row >> 2) & 3);
+    struct Stage {
+        uint32_t r[1][1][4];
+    };
+    auto issue = [&](int grp, uint8_t *xs, Stage &st) {
+        const int64_t mbase = (int64_t)grp * 32;
+#pragma unroll
+        for (int j = 0; j < DW; ++j) {
+            const int inst = wave + 4 * j;            // 0 .. 2 KC - 1: sub-tile inst / 2, row half inst % 2
+            const int kc = inst >> 1, h = inst & 1;
+            const uint32_t po = pixel_offset(grp, mbase + h * 16 + d_row);
+            const uint32_t off = po == kInvalid ? kInvalid : po + kc * 64 + d_chunk * 16;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (__attribute__((address_space(3))) void *)(xs + inst * 1024), 16,
+                                                     (int)off, 0, 0, 0);
+        }
+        if (RES) {
+            const int64_t m = mbase + rho;
+            const bool ok = grp < n_groups && m < a.M;
+            const int64_t e = m * (int64_t)a.K + k0 + khalf * 16;
+            const uint32_t ro = (ok && k0 + khalf * 16 < a.K) ? (uint32_t)(r4 ? (e >> 1) : e) : kInvalid;
+            const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)ro, 0, 0);
+            st.r[0][0][0] = (uint32_t)t[0]; st.r[0][0][1] = (uint32_t)t[1];
+            st.r[0][0][2] = (uint32_t)t[2]; st.r[0][0][3] = (uint32_t)t[3];
+        } else {
+            st.r[0][0][0] = st.r[0][0][1] = st.r[0][0][2] = st.r[0][0][3] = 0;
+        }
+    };
+    const bool slow_epilogue = wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4);
+    const int swz = (rho >> 2) & 3;
+    auto compute = [&](int grp, const uint8_t *xs, const Stage &st) {
+        v16i acc[1][1];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[0][0][i] = 0;
+        const int64_t mm[1] = {(int64_t)grp * 32 + rho};
+        const bool valid[1] = {mm[0] < a.M};
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const uint8_t *sub = xs + kc * 2048 + rho * 64;
+            const v4i b0 = *(const v4i *)(sub + ((khalf ^ swz) << 4));
+            const v4i b1 = *(const v4i *)(sub + (((2 + khalf) ^ swz) << 4));
+            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc[0][0], 0, 0, 0);
+            acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[0][0], 0, 0, 0);
+        }
+        epilogue_tile<1, 1, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
+        if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    // Per group and wave, in program order: [wait for the stage] [barrier] DW stage loads + R shortcut loads for
+    // the group three ahead, then this group's S stores.  Operations issued after a stage's own loads when its turn
+    // comes: the loads of the two later stages and the stores of the groups processed since (none for the first
+    // group, up to three groups' worth from the fourth on).
+    auto arrive = [&](int it) {
+        constexpr int L = (NS - 2) * (DW + R);
+        if (it == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L) : "memory");
+        else if (it == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + S) : "memory");
+        else if (it == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + 2 * S) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + 3 * S) : "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+    Stage st0, st1, st2, st3;
+    int grp = seq, it = 0;
+    issue(grp, xs0, st0);
+    issue(grp + n_seq, xs1, st1);
+    issue(grp + 2 * n_seq, xs2, st2);
+#define HAWQ_PWS_STEP(curx, curs, nxtx, nxts)        \
+    arrive(it);                                      \
+    issue(grp + 3 * n_seq, nxtx, nxts);              \
+    compute(grp, curx, curs);                        \
+    grp += n_seq;                                    \
+    ++it;                                            \
+    if (grp >= n_groups) break;
+    while (grp < n_groups) {
+        HAWQ_PWS_STEP(xs0, st0, xs3, st3)
+        HAWQ_PWS_STEP(xs1, st1, xs0, st0)
+        HAWQ_PWS_STEP(xs2, st2, xs1, st1)
+        HAWQ_PWS_STEP(xs3, st3, xs2, st2)
+    }
+#undef HAWQ_PWS_STEP
+}
+
 bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
     if (!conv_mfma_eligible(a, x_hi)) return false;
     if (a.R != 1 || a.S != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
@@ -271,6 +438,36 @@ static hawq_status launch_pw_res(const ConvArgs &a, hipStream_t s) {
 template <int KC, int TP, int NS, int WPE>
 static hawq_status launch_pw(const ConvArgs &a, hipStream_t s) {
     return a.res != nullptr ? launch_pw_res<KC, TP, NS, WPE, true>(a, s) : launch_pw_res<KC, TP, NS, WPE, false>(a, s);
+}
+
+bool conv_pws_eligible(const ConvArgs &a, int x_hi) {
+    if (!conv_mfma_eligible(a, x_hi) || is4(a.x_dt)) return false;
+    if (a.R != 1 || a.S != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
+    if (a.C != 256) return false;                        // measured: at C = 512 the tiled kernel is faster
+    if (a.K % 128 != 0 || a.K < 256) return false;       // four channel tiles per workgroup share the pixels
+    if (a.b == nullptr || a.y_dt == HAWQ_S32) return false;
+    uintptr_t al = (uintptr_t)a.y | (uintptr_t)a.res;
+    if (al & 15) return false;
+    if (((uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.res_b) & 3) return false;
+    return (int64_t)a.M >= 8192;
+}
+
+template <int KC, int WPE>
+static hawq_status launch_pws(const ConvArgs &a, hipStream_t s) {
+    const int n_ct = a.K / 32;                           // a multiple of 4
+    const int n_groups = (a.M + 31) / 32;
+    int n_seq = (WPE * 4 * 256) / n_ct;
+    if (n_seq < 1) n_seq = 1;
+    if (n_seq > n_groups) n_seq = n_groups;
+    const uint32_t blocks = (uint32_t)(n_seq * (n_ct / 4));   // exactly: every wave of the grid has work
+    if (a.res != nullptr) conv_pws_kernel<KC, WPE, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    else conv_pws_kernel<KC, WPE, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    return check_launch();
+}
+
+hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    return launch_pws<4, 3>(a, s);   // measured: three waves per SIMD (a fourth spills registers)
 }
 
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {

@@ -113,6 +113,41 @@ def test_pointwise_streaming_signed_shortcut_and_wide_parameters(hawq):
     assert_same(got, want3, "saturating parameters")
 
 
+# 1x1 with C = 256 and K >= 256 (a multiple of 128), many pixels: the streaming kernel whose four waves share a stage
+@pytest.mark.parametrize("N,H,W,K,stride,res,res_signed,y_dt,y_hi", [
+    (11, 28, 28, 1024, 1, True, False, 0, 127),     # the expanding 1x1 of ResNet50 stage 3
+    (3, 57, 55, 384, 1, False, False, 0, 127),      # ragged pixel tail, three workgroups per pixel group
+    (11, 56, 56, 512, 2, False, False, 1, 127),     # strided transition, signed output
+    (12, 27, 29, 256, 1, True, True, 2, 15),        # signed shortcut, packed 4-bit output
+])
+def test_pointwise_shared_stage_shapes(hawq, N, H, W, K, stride, res, res_signed, y_dt, y_hi):
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=N + H + K, N=N, H=H, W=W, C=256, K=K, R=1, S=1, stride=stride, pad=0, bits=8,
+                                 with_residual=res, res_signed=res_signed), 8)
+    if y_hi == 15:
+        case["c"] = (case["c"] + 3).astype(np.uint8)
+    signed_out = y_dt == 1
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, y_dt, res_dt=hawq.S8 if res_signed else hawq.U8,
+                             relu=0 if signed_out else 1, y_lo=-128 if signed_out else 0, y_hi=y_hi, x_hi=127)
+    assert_same(got, want, str((N, H, W, K)))
+    v = oracle.unpack(want, oracle.U4) if y_dt == 2 else want.astype(np.int32)
+    assert 0.05 < (v != 0).mean() and (v == y_hi).mean() < 0.5
+
+
+def test_pointwise_shared_stage_wide_parameters(hawq):
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=91, N=11, H=28, W=28, C=256, K=512, R=1, S=1, stride=1, pad=0, bits=8,
+                                 with_residual=True), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want, "narrow")
+    wide = dict(case)
+    wide["b"] = (case["b"].astype(np.int64) << 14).astype(np.int32)
+    wide["c"] = (case["c"].astype(np.int32) + 14).astype(np.uint8)
+    got, want2 = run_conv_gpu(wide, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want2, "wide parameters")
+    assert np.array_equal(want, want2)
+
+
 # 3x3 / stride 1 / pad 1 with 64 -> 64 channels and many pixels: the persistent kernel with resident weights
 @pytest.mark.parametrize("N,H,W,res,res_signed,y_dt,y_hi", [
     (11, 56, 56, False, False, 0, 127),     # ResNet50 stage-1 shape
