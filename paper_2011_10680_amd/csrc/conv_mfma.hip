@@ -30,7 +30,8 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // Minimum waves per SIMD the register allocation must leave room for, by the wave's share of the tile:
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
 // shapes live on occupancy).
-template <int BC, int BP, int WC, int WP, bool INT4>
+// NBUF: LDS buffers in the operand ring (4, or 8 for the LDS-DMA path when one workgroup has a CU to itself)
+template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4>
 __global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr int T = WC * WP * 64;
@@ -51,12 +52,21 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     __shared__ __attribute__((aligned(1024))) uint8_t lds1[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds2[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds3[kBufBytes];
+    static_assert(NBUF == 4 || (NBUF == 8 && !INT4), "ring depth");
+    __shared__ __attribute__((aligned(1024))) uint8_t lds4[NBUF == 8 ? kBufBytes : 16];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds5[NBUF == 8 ? kBufBytes : 16];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds6[NBUF == 8 ? kBufBytes : 16];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds7[NBUF == 8 ? kBufBytes : 16];
     auto ldsbuf = [&](auto nc) -> uint8_t * {
         constexpr int n = decltype(nc)::value;
         if constexpr (n == 0) return lds0;
         else if constexpr (n == 1) return lds1;
         else if constexpr (n == 2) return lds2;
-        else return lds3;
+        else if constexpr (n == 3) return lds3;
+        else if constexpr (n == 4) return lds4;
+        else if constexpr (n == 5) return lds5;
+        else if constexpr (n == 6) return lds6;
+        else return lds7;
     };
     __shared__ ChanMain par_m[BC];
     __shared__ ChanRes par_r[BC];
@@ -78,7 +88,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int cchunks = a.C / 64;                 // K-steps per tap
     const int steps = a.R * a.S * cchunks;
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
-    for (int i = tid; i < steps + 8; i += T) {
+    for (int i = tid; i < steps + NBUF + 4; i += T) {
         const int st = i < steps ? i : steps - 1;      // past the last step the activation address stays put ...
         const int cc = st % cchunks, t = st / cchunks;
         const int s_ = t % a.S, r_ = t / a.S;
@@ -260,9 +270,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     using S2 = std::integral_constant<int, 2>;
     using S3 = std::integral_constant<int, 3>;
     if constexpr (DMA) {
-        gload(0, S0{});
-        gload(1, S1{});
-        gload(2, S2{});
+        static_for<0, NBUF - 1>([&](auto ic) { gload(decltype(ic)::value, ic); });
     } else {
         gload(0, S0{});
         gload(1, S1{});
@@ -297,7 +305,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             }
         }
     }
-    // ---- software pipeline over four LDS buffers ----
+    // ---- software pipeline over a ring of LDS buffers (described for the ring of four) ----
     // Register path (INT4), iteration t (LDS buffer t%4 is multiplied):
     //   * K-step t+2, requested two iterations ago, is written from register set t%2 to buffer (t+2)%4
     //     (last read in iteration t-2); K-step t+4 is requested into the freed register set.
@@ -310,7 +318,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // single exit (the trip count is rounded up; padded steps multiply zero weights), so buffer and
     // register-set indices are compile-time constants and the accumulators stay in place.
     if constexpr (DMA) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NA + NB) : "memory");   // steps 0 and 1 have landed (step 2 may fly)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NBUF - 3) * (NA + NB)) : "memory");   // steps 0 and 1 have landed (later ones may fly)
     } else {
         lstore(S0{}, S0{});
         lstore(S1{}, S1{});
@@ -327,16 +335,16 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     auto iteration = [&](int step, auto phasec) {
         constexpr int phase = decltype(phasec)::value;            // step % 4
         using Cur = std::integral_constant<int, phase>;
-        using Nxt = std::integral_constant<int, (phase + 1) % 4>;
+        using Nxt = std::integral_constant<int, (phase + 1) % NBUF>;
         using Wr = std::integral_constant<int, (phase + 2) % 4>;
-        using Dma = std::integral_constant<int, (phase + 3) % 4>;
+        using Dma = std::integral_constant<int, (phase + NBUF - 1) % NBUF>;
         using Set = std::integral_constant<int, phase % 2>;
         v4i af1[TC], bf1[TP];
 #pragma unroll
         for (int tc = 0; tc < TC; ++tc) af1[tc] = *(const v4i *)(ldsbuf(Cur{}) + a_fo[tc][1]);
 #pragma unroll
         for (int tp = 0; tp < TP; ++tp) bf1[tp] = *(const v4i *)(ldsbuf(Cur{}) + b_fo[tp][1]);
-        if constexpr (DMA) gload(step + 3, Dma{});
+        if constexpr (DMA) gload(step + NBUF - 1, Dma{});
         __builtin_amdgcn_sched_barrier(0);
         // first-half MFMAs (register path: each followed by one LDS write of step+2)
         static_for<0, TP * TC>([&](auto ic) {
@@ -369,17 +377,13 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             // is used instead of __syncthreads(): that one carries a workgroup fence, which would wait for
             // *all* outstanding LDS-DMA writes and expose their full latency every K-step.  The memory clobber
             // keeps the compiler from moving LDS accesses across it.
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NA + NB) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NBUF - 3) * (NA + NB)) : "memory");
         } else {
             __syncthreads();
         }
     };
-    for (int step = 0; step < steps; step += 4) {
-        iteration(step, S0{});
-        iteration(step + 1, S1{});
-        iteration(step + 2, S2{});
-        iteration(step + 3, S3{});
-    }
+    for (int step = 0; step < steps; step += NBUF)
+        static_for<0, NBUF>([&](auto ic) { iteration(step + decltype(ic)::value, ic); });
 
     // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
     const int chl = wc * (BC / WC) + khalf * 16 * TC;
@@ -417,15 +421,21 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
         if (a.x_dt != HAWQ_U8 && a.x_dt != HAWQ_S8) return false;
     }
     if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
-    if ((int64_t)a.R * a.S * (a.C / 64) + 8 > kMaxSteps) return false;   // the per-step address table is in LDS
+    if ((int64_t)a.R * a.S * (a.C / 64) + 12 > kMaxSteps) return false;   // the per-step address table is in LDS
     return true;
 }
 
 template <int BC, int BP, int WC, int WP>
-static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s) {
+static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s, bool deep = false) {
     const uint32_t n_ctiles = (a.K + BC - 1) / BC;
     const uint32_t n_mtiles = (a.M + BP - 1) / BP;
     const uint32_t nblocks = n_ctiles * n_mtiles;
+    if constexpr (BC == 128 && BP == 128 && WC == 4) {
+        if (deep && !is4(a.x_dt)) {
+            conv_mfma_kernel<BC, BP, WC, WP, false, 8><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
+            return check_launch();
+        }
+    }
     if (is4(a.x_dt))
         conv_mfma_kernel<BC, BP, WC, WP, true><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
     else
@@ -454,7 +464,16 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     // its 8-wave form (a wave owns 32 channels x 64 pixels: half the accumulators, four waves per SIMD, and every
     // per-channel parameter read in the epilogue serves two pixels); 64-channel layers take 64x128,
     // tiny problems 64x64.
-    if (a.K >= 128 && a.M >= 1024) return launch_cfg<128, 128, 4, 2>(a, vec, s);
+    if (a.K >= 128 && a.M >= 1024) {
+        // At most one workgroup per CU and a long reduction (the 7x7 layers of a ResNet at batch 128): nothing
+        // else on the CU hides a late operand, and the weights come cold from HBM, so the ring is eight buffers
+        // deep there (operands requested seven K-steps ahead instead of three).  A small gain only: the 3x3
+        // 512 -> 512 layer takes 19.9 us with weights resident in cache, 27.6 us with cold weights and the ring of
+        // four, 26.2 us with the ring of eight.
+        const int64_t nblocks = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
+        const int steps = a.R * a.S * (a.C / 64);
+        return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16);
+    }
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     return launch_cfg<64, 64, 2, 2>(a, vec, s);
 }

@@ -113,6 +113,24 @@ def test_pointwise_streaming_signed_shortcut_and_wide_parameters(hawq):
     assert_same(got, want3, "saturating parameters")
 
 
+# few tiles and a long reduction: the tiled kernel's eight-buffer operand ring
+@pytest.mark.parametrize("shape", [
+    (8, 14, 14, 256, 256, 3, 3, 1, 1, False),     # 36 K-steps
+    (9, 13, 11, 192, 384, 3, 3, 1, 1, True),      # 27 K-steps (padded to 32), ragged tiles, shortcut
+    (6, 14, 14, 1024, 128, 1, 1, 1, 0, False),    # 16 K-steps, pointwise
+    (24, 14, 14, 512, 256, 3, 3, 2, 1, False),    # strided, 72 K-steps
+    (128, 7, 7, 512, 512, 3, 3, 1, 1, False),     # the 7x7 layer of ResNet50 at batch 128: 196 tiles
+])
+def test_tiled_kernel_deep_ring(hawq, shape):
+    from gpu_util import run_conv_gpu, assert_same
+    N, H, W, C, K, R, S, stride, pad, res = shape
+    case = _scale_c(wl.conv_case(seed=sum(shape[:9]), N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=8,
+                                 with_residual=res), 8)
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want, str(shape))
+    assert 0.05 < (want > 0).mean() and (want == 127).mean() < 0.5
+
+
 # 1x1 with C = 256 and K >= 256 (a multiple of 128), many pixels: the streaming kernel whose four waves share a stage
 @pytest.mark.parametrize("N,H,W,K,stride,res,res_signed,y_dt,y_hi", [
     (11, 28, 28, 1024, 1, True, False, 0, 127),     # the expanding 1x1 of ResNet50 stage 3
