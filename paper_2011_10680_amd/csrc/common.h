@@ -74,15 +74,25 @@ __device__ __forceinline__ void static_for(F &&f) {
     }
 }
 
-// per-byte unsigned maximum of two packed dwords (through two 16-bit lanes)
+// Per-byte unsigned maximum / minimum of packed dwords through the packed 16-bit ALU: the even bytes and the odd
+// bytes of a dword are compared as two 16-bit lanes each (odd bytes in place, in the high byte of a lane whose low
+// byte is zero).
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
 __device__ __forceinline__ uint32_t max_u8x4(uint32_t a, uint32_t b) {
-    // per-byte unsigned maximum through two 16-bit lanes
-    const uint32_t ae = a & 0x00ff00ffu, be = b & 0x00ff00ffu, ao = (a >> 8) & 0x00ff00ffu, bo = (b >> 8) & 0x00ff00ffu;
-    const uint32_t e = ((ae & 0xffff) > (be & 0xffff) ? (ae & 0xffff) : (be & 0xffff)) |
-                       ((ae >> 16) > (be >> 16) ? (ae & 0xffff0000u) : (be & 0xffff0000u));
-    const uint32_t o = ((ao & 0xffff) > (bo & 0xffff) ? (ao & 0xffff) : (bo & 0xffff)) |
-                       ((ao >> 16) > (bo >> 16) ? (ao & 0xffff0000u) : (bo & 0xffff0000u));
-    return e | (o << 8);
+    return pk_max_u16(a & 0x00ff00ffu, b & 0x00ff00ffu) | pk_max_u16(a & 0xff00ff00u, b & 0xff00ff00u);
+}
+// per-byte clamp of packed unsigned bytes to [lo, hi] (0 <= lo <= hi <= 255)
+__device__ __forceinline__ uint32_t clamp_u8x4(uint32_t a, uint32_t lo, uint32_t hi) {
+    const uint32_t le = lo * 0x00010001u, he = hi * 0x00010001u;
+    const uint32_t e = pk_min_u16(pk_max_u16(a & 0x00ff00ffu, le), he);
+    const uint32_t o = pk_min_u16(pk_max_u16(a & 0xff00ff00u, le << 8), he << 8);
+    return e | o;
 }
 
 // XCD-aware remap of a linear workgroup id.  Workgroups are dealt round-robin to the 8 XCDs

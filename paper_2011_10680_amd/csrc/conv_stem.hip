@@ -145,7 +145,7 @@ constexpr int FUSE_NPX = FUSE_CR * FUSE_CC;        // 255 conv pixels
 
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
 conv_stem_pool_kernel(const ConvArgs a, const int pool_P, const int pool_Q, const int pool_y_dt, const int pool_lo,
-                      const int pool_hi, uint8_t *__restrict__ pool_y, const int tiles_q, const int tiles_p) {
+                      const int pool_hi, uint8_t *__restrict__ pool_y, const int tiles_q, const int tiles_p, const int n_tiles) {
     __shared__ __attribute__((aligned(16))) uint8_t lw[STEM_W_BYTES];
     __shared__ __attribute__((aligned(16))) uint32_t lx[FUSE_ROWS * FUSE_COLS];
     __shared__ __attribute__((aligned(16))) uint8_t lc[256 * 64];   // requantised conv1 tile [pixel][channel]
@@ -153,140 +153,169 @@ conv_stem_pool_kernel(const ConvArgs a, const int pool_P, const int pool_Q, cons
     __shared__ ChanRes par_r[64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int bid = blockIdx.x;
-    const int tq = bid % tiles_q; bid /= tiles_q;
-    const int tp_ = bid % tiles_p;
-    const int n = bid / tiles_p;
-    const int pp0 = tp_ * FUSE_PR, pq0 = tq * FUSE_PC;       // pooled tile origin
-    const int cp0 = 2 * pp0 - 1, cq0 = 2 * pq0 - 1;          // conv tile origin (may be -1)
-
+    // The workgroup is persistent: weights and parameters are staged once, then it walks over tiles
+    // blockIdx.x, + gridDim.x, ...; the raw input bytes of the next tile are fetched into registers while the
+    // current tile is multiplied, requantised and pooled.
     for (int i = tid; i < STEM_W_BYTES / 16; i += 256) {
         const int row = i >> 4, ch = i & 15;
         *(v4i *)(lw + row * 256 + ((ch ^ (row & 15)) << 4)) = *(const v4i *)(a.w + i * 16);
     }
-    // input patch: row rl <-> image row 2*cp0 - 3 + rl, column col <-> image column 2*cq0 - 3 + col;
-    // groups of 4 pixels start at image column 4*pq0 - 8 + 4g, i.e. patch column 4g - 3
-    const uint8_t *img = a.x + (int64_t)n * a.H * a.W * 3;
-    for (int i = tid; i < FUSE_ROWS * 12; i += 256) {
-        const int rl = i / 12, g = i - rl * 12;
-        const int ih = 2 * cp0 - 3 + rl;
-        const int iw = 4 * pq0 - 8 + 4 * g;
-        uint32_t px[4] = {0, 0, 0, 0};
-        if ((unsigned)ih < (unsigned)a.H && iw >= 0 && iw + 3 < a.W) {
-            const uint32_t *src = (const uint32_t *)(img + ((int64_t)ih * a.W + iw) * 3);
-            const uint32_t d0 = src[0], d1 = src[1], d2 = src[2];
-            px[0] = d0 & 0x00ffffffu;
-            px[1] = ((d0 >> 24) | (d1 << 8)) & 0x00ffffffu;
-            px[2] = ((d1 >> 16) | (d2 << 16)) & 0x00ffffffu;
-            px[3] = d2 >> 8;
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int col = 4 * g - 3 + k;
-            if (col >= 0 && col < FUSE_COLS) lx[rl * FUSE_COLS + col] = px[k] ^ 0x00808080u;
-        }
-    }
     int wide = stage_params(a, 0, 64, par_m, par_r);
     wide = __syncthreads_or(wide);
 
-    // ---- conv1 on the 255 pixels of the tile: wave w takes MFMA pixel tiles 2w and 2w+1 ----
+    // input patch of a tile: row rl <-> image row 2*cp0 - 3 + rl, column col <-> image column 2*cq0 - 3 + col;
+    // groups of 4 pixels (12 bytes) start at image column 4*pq0 - 8 + 4g, i.e. patch column 4g - 3.  A thread
+    // owns work items tid and tid + 256 of the FUSE_ROWS * 12 groups.
+    constexpr int NITEM = (FUSE_ROWS * 12 + 255) / 256;
+    uint32_t raw[NITEM][3];
+    auto fetch = [&](int tile) {
+        int t = tile;
+        const int tq = t % tiles_q; t /= tiles_q;
+        const int tp_ = t % tiles_p;
+        const int n = t / tiles_p;
+        const int cp0 = 2 * tp_ * FUSE_PR - 1, pq0 = tq * FUSE_PC;       // conv row origin, pooled column origin
+        const uint8_t *img = a.x + (int64_t)n * a.H * a.W * 3;
+#pragma unroll
+        for (int it = 0; it < NITEM; ++it) {
+            const int i = tid + it * 256;
+            const int rl = i / 12, g = i - rl * 12;
+            const int ih = 2 * cp0 - 3 + rl;
+            const int iw = 4 * pq0 - 8 + 4 * g;
+            raw[it][0] = raw[it][1] = raw[it][2] = 0;
+            if (tile < n_tiles && i < FUSE_ROWS * 12 && (unsigned)ih < (unsigned)a.H && iw >= 0 && iw + 3 < a.W) {
+                const uint32_t *src = (const uint32_t *)(img + ((int64_t)ih * a.W + iw) * 3);
+                raw[it][0] = src[0]; raw[it][1] = src[1]; raw[it][2] = src[2];
+            }
+        }
+    };
+    // widen the fetched RGB triples to RGB0 dwords, offset by -128 (XOR 0x80 per byte), into the LDS patch;
+    // out-of-image positions are raw zeros and get the same offset (the bias correction assumes it everywhere)
+    auto stage = [&]() {
+#pragma unroll
+        for (int it = 0; it < NITEM; ++it) {
+            const int i = tid + it * 256;
+            const int rl = i / 12, g = i - rl * 12;
+            const uint32_t d0 = raw[it][0], d1 = raw[it][1], d2 = raw[it][2];
+            const uint32_t p0 = d0 & 0x00ffffffu;
+            const uint32_t p1 = ((d0 >> 24) | (d1 << 8)) & 0x00ffffffu;
+            const uint32_t p2 = ((d1 >> 16) | (d2 << 16)) & 0x00ffffffu;
+            const uint32_t p3 = d2 >> 8;
+            const int col = 4 * g - 3;          // -3, 1, 5, ... 41: patch columns col .. col + 3
+            if (i < FUSE_ROWS * 12) {
+                uint32_t *dst = lx + rl * FUSE_COLS + col;
+                if (col >= 0) { dst[0] = p0 ^ 0x00808080u; dst[1] = p1 ^ 0x00808080u; dst[2] = p2 ^ 0x00808080u; }
+                if (col + 3 < FUSE_COLS) dst[3] = p3 ^ 0x00808080u;
+            }
+        }
+    };
     const int rho = lane & 31, khalf = lane >> 5;
     const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
     int a_row[2];
 #pragma unroll
     for (int tc = 0; tc < 2; ++tc) a_row[tc] = hsel * 32 + tc * 16 + isel;
-    int b_base[2], ci[2];
-#pragma unroll
-    for (int tp = 0; tp < 2; ++tp) {
-        ci[tp] = (2 * wave + tp) * 32 + rho;                       // 0..255; 255 is the one padding slot
-        const int cix = ci[tp] < FUSE_NPX ? ci[tp] : 0;
-        const int cr = cix / FUSE_CC, cc = cix - cr * FUSE_CC;
-        b_base[tp] = (2 * cr) * FUSE_COLS + 2 * cc + 4 * khalf;
-    }
-    v16i acc[2][2];
-#pragma unroll
-    for (int tp = 0; tp < 2; ++tp)
-#pragma unroll
-        for (int tc = 0; tc < 2; ++tc)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
-#pragma unroll
-    for (int r = 0; r < 7; ++r) {
-        v4i af[2], bf[2];
-#pragma unroll
-        for (int tc = 0; tc < 2; ++tc) {
-            const int row = a_row[tc];
-            af[tc] = *(const v4i *)(lw + row * 256 + (((2 * r + khalf) ^ (row & 15)) << 4));
-        }
-#pragma unroll
+    ConvArgs lds_out = a;             // the epilogue stores into the LDS conv tile: [pixel][64 channels]
+    lds_out.y = lc;
+    lds_out.K = 64;
+    const int pg = tid & 3, pj = (tid >> 2) & 7, pi = tid >> 5;   // pool phase: 16 channels of one pooled pixel
+
+    int tile = blockIdx.x;            // < n_tiles by construction of the grid
+    fetch(tile);
+    for (; tile < n_tiles; tile += gridDim.x) {
+        int t = tile;
+        const int tq = t % tiles_q; t /= tiles_q;
+        const int tp_ = t % tiles_p;
+        const int n = t / tiles_p;
+        const int pp0 = tp_ * FUSE_PR, pq0 = tq * FUSE_PC;       // pooled tile origin
+        const int cp0 = 2 * pp0 - 1, cq0 = 2 * pq0 - 1;          // conv tile origin (may be -1)
+        stage();
+        fetch(tile + gridDim.x);
+        __syncthreads();              // patch complete; the previous tile's pool reads are done
+
+        // ---- conv1 on the 255 pixels of the tile: wave w takes MFMA pixel tiles 2w and 2w+1, one after the
+        // other (kept as a rolled loop: both at once would need twice the accumulators and spill) ----
+#pragma nounroll
         for (int tp = 0; tp < 2; ++tp) {
-            const uint2 lo = *(const uint2 *)(lx + b_base[tp] + r * FUSE_COLS);
-            const uint2 hi = *(const uint2 *)(lx + b_base[tp] + r * FUSE_COLS + 2);
-            bf[tp] = (v4i){(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
-        }
-#pragma unroll
-        for (int tp = 0; tp < 2; ++tp)
+            const int cidx = (2 * wave + tp) * 32 + rho;               // 0..255; 255 is the one padding slot
+            const int cix = cidx < FUSE_NPX ? cidx : 0;
+            const int cr = cix / FUSE_CC, cc = cix - cr * FUSE_CC;
+            const int bb = (2 * cr) * FUSE_COLS + 2 * cc + 4 * khalf;
+            v16i acc[1][2];
 #pragma unroll
             for (int tc = 0; tc < 2; ++tc)
-                acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[tc], bf[tp], acc[tp][tc], 0, 0, 0);
-    }
-    {
-        ConvArgs lds_out = a;             // the epilogue stores into the LDS conv tile: [pixel][64 channels]
-        lds_out.y = lc;
-        lds_out.K = 64;
-        const int64_t mm[2] = {ci[0], ci[1]};
-        const bool valid[2] = {true, true};   // every slot is inside lc; out-of-image pixels are skipped when pooling
-        const uint32_t none[2][2][4] = {};
-        epilogue_tile<2, 2, false, true>(lds_out, par_m, par_r, mm, valid, 0, khalf * 32, acc, wide, none);
-    }
-    __syncthreads();
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[0][tc][i] = 0;
+#pragma unroll
+            for (int r = 0; r < 7; ++r) {
+                v4i af[2];
+#pragma unroll
+                for (int tc = 0; tc < 2; ++tc) {
+                    const int row = a_row[tc];
+                    af[tc] = *(const v4i *)(lw + row * 256 + (((2 * r + khalf) ^ (row & 15)) << 4));
+                }
+                const uint2 lo = *(const uint2 *)(lx + bb + r * FUSE_COLS);
+                const uint2 hi = *(const uint2 *)(lx + bb + r * FUSE_COLS + 2);
+                const v4i bf = (v4i){(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+#pragma unroll
+                for (int tc = 0; tc < 2; ++tc)
+                    acc[0][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[tc], bf, acc[0][tc], 0, 0, 0);
+            }
+            const int64_t mm[1] = {cidx};
+            const bool valid[1] = {true};   // every slot is inside lc; out-of-image pixels are skipped when pooling
+            const uint32_t none[1][2][4] = {};
+            epilogue_tile<2, 1, false, 1>(lds_out, par_m, par_r, mm, valid, 0, khalf * 32, acc, wide, none);
+        }
+        __syncthreads();              // conv tile complete; patch reads are done
 
-    // ---- 3x3/2 max pool out of LDS: thread = 16 channels of one pooled pixel ----
-    const int g = tid & 3, j = (tid >> 2) & 7, i = tid >> 5;
-    const int pp = pp0 + i, pq = pq0 + j;
-    if (i >= FUSE_PR || pp >= pool_P || pq >= pool_Q) return;
-    uint4 best = make_uint4(0, 0, 0, 0);   // unsigned data: zero is the identity of the maximum
+        // ---- 3x3/2 max pool out of LDS ----
+        const int pp = pp0 + pi, pq = pq0 + pj;
+        if (pi < FUSE_PR && pp < pool_P && pq < pool_Q) {
+            // running per-byte maxima, even and odd bytes kept apart (two 16-bit lanes each); unsigned data:
+            // zero is the identity of the maximum
+            uint32_t be[4] = {0, 0, 0, 0}, bo[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int dr = 0; dr < 3; ++dr) {
-        const int cp = cp0 + 2 * i + dr;
-        if ((unsigned)cp >= (unsigned)a.P) continue;
+            for (int dr = 0; dr < 3; ++dr) {
+                const int cp = cp0 + 2 * pi + dr;
+                if ((unsigned)cp >= (unsigned)a.P) continue;
 #pragma unroll
-        for (int dc = 0; dc < 3; ++dc) {
-            const int cq = cq0 + 2 * j + dc;
-            if ((unsigned)cq >= (unsigned)a.Q) continue;
-            const uint4 v = *(const uint4 *)(lc + ((2 * i + dr) * FUSE_CC + 2 * j + dc) * 64 + g * 16);
-            best.x = max_u8x4(best.x, v.x); best.y = max_u8x4(best.y, v.y);
-            best.z = max_u8x4(best.z, v.z); best.w = max_u8x4(best.w, v.w);
+                for (int dc = 0; dc < 3; ++dc) {
+                    const int cq = cq0 + 2 * pj + dc;
+                    if ((unsigned)cq >= (unsigned)a.Q) continue;
+                    const uint4 v = *(const uint4 *)(lc + ((2 * pi + dr) * FUSE_CC + 2 * pj + dc) * 64 + pg * 16);
+                    const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        be[d] = pk_max_u16(be[d], vv[d] & 0x00ff00ffu);
+                        bo[d] = pk_max_u16(bo[d], vv[d] & 0xff00ff00u);
+                    }
+                }
+            }
+            uint32_t ov[4], nib[2] = {0, 0};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                ov[d] = clamp_u8x4(be[d] | bo[d], (uint32_t)pool_lo, (uint32_t)pool_hi);
+                // low nibbles of the four bytes -> 16 bits (only used for a packed 4-bit output, values <= 15)
+                const uint32_t h = (ov[d] & 0xf) | ((ov[d] >> 4) & 0xf0) | ((ov[d] >> 8) & 0xf00) | ((ov[d] >> 12) & 0xf000);
+                nib[d >> 1] |= h << (16 * (d & 1));
+            }
+            const int64_t oe = (((int64_t)n * pool_P + pp) * pool_Q + pq) * 64 + pg * 16;
+            if (is4(pool_y_dt)) *(uint2 *)(pool_y + (oe >> 1)) = make_uint2(nib[0], nib[1]);
+            else *(uint4 *)(pool_y + oe) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
         }
     }
-    const uint32_t wv[4] = {best.x, best.y, best.z, best.w};
-    uint32_t ov[4], nib[2] = {0, 0};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        uint32_t o = 0, h = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            int32_t v = (int32_t)((wv[d] >> (8 * e)) & 0xff);
-            v = v < pool_lo ? pool_lo : (v > pool_hi ? pool_hi : v);
-            o |= (uint32_t)(v & 0xff) << (8 * e);
-            h |= (uint32_t)(v & 0xf) << (4 * e);
-        }
-        ov[d] = o;
-        nib[d >> 1] |= h << (16 * (d & 1));
-    }
-    const int64_t oe = (((int64_t)n * pool_P + pp) * pool_Q + pq) * 64 + g * 16;
-    if (is4(pool_y_dt)) *(uint2 *)(pool_y + (oe >> 1)) = make_uint2(nib[0], nib[1]);
-    else *(uint4 *)(pool_y + oe) = make_uint4(ov[0], ov[1], ov[2], ov[3]);
 }
 
 hawq_status launch_conv_stem_pool(const ConvArgs &a, int pool_y_dt, int pool_lo, int pool_hi, void *pool_y, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     const int pool_P = (a.P - 1) / 2 + 1, pool_Q = (a.Q - 1) / 2 + 1;
     const int tiles_p = (pool_P + FUSE_PR - 1) / FUSE_PR, tiles_q = (pool_Q + FUSE_PC - 1) / FUSE_PC;
-    const int64_t blocks = (int64_t)a.N * tiles_p * tiles_q;
-    if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
-    conv_stem_pool_kernel<<<(uint32_t)blocks, 256, 0, s>>>(a, pool_P, pool_Q, pool_y_dt, pool_lo, pool_hi, (uint8_t *)pool_y,
-                                                           tiles_q, tiles_p);
+    const int64_t n_tiles = (int64_t)a.N * tiles_p * tiles_q;
+    if (n_tiles > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+    const int64_t grid = n_tiles < 3 * 256 ? n_tiles : 3 * 256;    // persistent: three workgroups per CU
+    // the pooled bytes are unsigned: bounds outside 0..255 never bind
+    pool_lo = pool_lo < 0 ? 0 : pool_lo;
+    pool_hi = pool_hi > 255 ? 255 : pool_hi;
+    conv_stem_pool_kernel<<<(uint32_t)grid, 256, 0, s>>>(a, pool_P, pool_Q, pool_y_dt, pool_lo, pool_hi, (uint8_t *)pool_y,
+                                                          tiles_q, tiles_p, (int)n_tiles);
     return check_launch();
 }
 
