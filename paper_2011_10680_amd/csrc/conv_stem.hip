@@ -280,7 +280,10 @@ conv_stem_pool_kernel(const ConvArgs a, const int pool_P, const int pool_Q, cons
                 for (int dc = 0; dc < 3; ++dc) {
                     const int cq = cq0 + 2 * pj + dc;
                     if ((unsigned)cq >= (unsigned)a.Q) continue;
-                    const uint4 v = *(const uint4 *)(lc + ((2 * pi + dr) * FUSE_CC + 2 * pj + dc) * 64 + pg * 16);
+                    const int pix = (2 * pi + dr) * FUSE_CC + 2 * pj + dc;
+                    // chunk swizzle of the tile (the exact general epilogue writes the plain layout)
+                    const int chunk = wide ? pg : ((pg ^ (pix >> 2)) & 3);
+                    const uint4 v = *(const uint4 *)(lc + pix * 64 + (chunk << 4));
                     const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {

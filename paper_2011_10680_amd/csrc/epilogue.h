@@ -258,7 +258,7 @@ __device__ __forceinline__ void epilogue_tile_general(const ConvArgs &a, const C
 //   3. clamp, pack 4 (or 8) outputs per dword, 16-byte (8-byte) store per 16 channels
 // `wide` (a channel outside the narrow range) or a signed 4-bit tensor take the general form.
 // YMODE 0: plain global stores of the valid pixels.  1: a.y points into LDS (a kernel that keeps the requantised
-// tile on chip); stores use LDS instructions.  2: every lane issues its store as a buffer store, invalid pixels
+// tile on chip, 64 channels per pixel, chunk-swizzled -- see the store below); stores use LDS instructions.  2: every lane issues its store as a buffer store, invalid pixels
 // with an out-of-range offset that the hardware drops -- the number of memory instructions is then the same
 // for every wave, which lets a caller count outstanding operations exactly.
 template <int TC, int TP, bool PRE, int YMODE = 0>
@@ -370,8 +370,12 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                     __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, yrs, (int)off, 0, 0);
                 } else if (valid[tp]) {
                     if (YMODE == 1) {
+                        // LDS tile of 64-byte pixels: the four 16-byte chunks of a pixel are XOR-swizzled with
+                        // (pixel >> 2) & 3, so that the sixteen lanes of a store phase (consecutive pixels, one
+                        // chunk) fall into different banks
                         typedef __attribute__((address_space(3))) v4i lds_v4i;
-                        *(lds_v4i *)(a.y + (m[tp] * (int64_t)a.K + chg)) = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                        const int pix = (int)m[tp];
+                        *(lds_v4i *)(a.y + (pix * 64 + ((((chg >> 4) ^ (pix >> 2)) & 3) << 4))) = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
                     } else {
                         *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
                     }

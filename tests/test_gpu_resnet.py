@@ -64,6 +64,24 @@ def test_layerwise_and_logits(hawq, arch, mixed, N):
     assert np.array_equal(got2, want)
 
 
+@pytest.mark.parametrize("image_hw,N", [(64, 3), (100, 2), (224, 1)])
+def test_fused_stem_with_wide_parameters_and_odd_sizes(hawq, image_hw, N):
+    """conv1 fused with the max pool (no kept activations): multipliers of conv1 outside the narrow epilogue's range
+    take the exact 64-bit path inside the fused kernel; image sizes whose pooled size is not a multiple of the
+    pooled tile (7 x 8) exercise the ragged tiles.  Scaling numerator and shift together must not change a bit."""
+    net = wl.make_resnet(18, seed=77, image_hw=image_hw)
+    x = wl.make_image_batch(9, N, image_hw=image_hw)
+    want = onet.forward(net, x)
+    got, _ = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got, want)
+    conv1 = net["layers"][0]
+    conv1["b"] = (conv1["b"].astype(np.int64) << 14).astype(np.int32)
+    conv1["c"] = (conv1["c"].astype(np.int32) + 14).astype(np.uint8)
+    assert np.array_equal(onet.forward(net, x), want)
+    got, _ = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("arch,batch,mixed,seed", [(18, 64, False, 1002), (50, 128, False, 1003), (50, 256, True, 1004)])
 def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed):
     """The network configurations at their full batch, in the launch configuration the benchmark times
