@@ -17,13 +17,19 @@
 
 namespace hawq {
 
-template <bool RES>   // a shortcut is added
+// RES: a shortcut is added.  INT4: packed 4-bit operands -- the weights are expanded to INT8 once, while they are
+// staged into LDS; the pixels stay packed in the patch (32-byte rows) and are split into nibbles when a fragment
+// is read: the low nibbles of a lane's 16 bytes form the first-half MFMA operand, the high nibbles the second
+// half, and the weight staging applies the same split, which leaves every dot product unchanged.
+template <bool RES, bool INT4>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
     constexpr int BP = 128;                     // pixels per tile
     constexpr int PROWS = 256;                  // patch rows (input pixels) a patch buffer holds
-    constexpr int NPW = PROWS / 16 / 4;         // patch fetch instructions per wave (16 rows = 1 KB each)
-    constexpr int PB = PROWS * 64;
+    constexpr int ROWB = INT4 ? 32 : 64;        // bytes of a pixel (64 channels) in memory and in the patch
+    constexpr int RPI = 1024 / ROWB;            // patch rows one fetch instruction (1 KB) fills
+    constexpr int NPW = PROWS / RPI / 4;        // patch fetch instructions per wave
+    constexpr int PB = PROWS * ROWB;
     constexpr int TC = 2, TP = 1;
     constexpr int R = RES ? TC * TP : 0, S = TC * TP;   // shortcut loads / stores per lane and tile (16 bytes each)
     constexpr uint32_t kInvalid = 0x80000000u;
@@ -40,8 +46,8 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
     const int n_in = a.N * HW;                  // input pixels = output pixels
     const int prows = BP + 2 * W + 2;           // rows in use (<= PROWS - 1, checked by the host)
 
-    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, 64 * 576, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, n_in * 64, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, 64 * 9 * ROWB, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, n_in * ROWB, 0x00020000);
     constexpr bool has_res = RES;
     const bool r4 = is4(a.res_dt);
     const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc(
@@ -49,7 +55,7 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
 
     // ---- weights -> LDS, once: instruction j of wave w fills 1 KB = 16 channels of one tap; lane i writes chunk
     // i of that KB and therefore fetches the chunk the XOR swizzle places there ----
-    {
+    if constexpr (!INT4) {
         const int row16 = lane >> 2;
 #pragma unroll
         for (int j = 0; j < 9; ++j) {
@@ -59,23 +65,44 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc_w, (__attribute__((address_space(3))) void *)(wl + inst * 1024), 16, k * 576 + tap * 64 + ch * 16, 0, 0, 0);
         }
+    } else {
+        // packed weights: a thread takes 16 packed bytes (half a tap row of one channel: the bytes a lane half
+        // `kh` multiplies), expands them to the two 16-byte INT8 chunks (kk = 0: low nibbles, kk = 1: high nibbles,
+        // sign-extended) and writes them where the INT8 layout keeps chunk 2 kk + kh
+        for (int i = tid; i < 9 * 64 * 2; i += 256) {
+            const int kh = i & 1, k = (i >> 1) & 63, tap = i >> 7;
+            const v4i v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, k * 288 + tap * 32 + kh * 16, 0, 0);
+            v4i lo, hi;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t u = (uint32_t)v[e];
+                uint32_t l = u & 0x0F0F0F0Fu, h = (u >> 4) & 0x0F0F0F0Fu;
+                l |= (l & 0x08080808u) * 0x1Eu;
+                h |= (h & 0x08080808u) * 0x1Eu;
+                lo[e] = (int)l; hi[e] = (int)h;
+            }
+            const int sw = (k >> 2) & 3;
+            *(v4i *)(wl + tap * 4096 + k * 64 + ((kh ^ sw) << 4)) = lo;
+            *(v4i *)(wl + tap * 4096 + k * 64 + (((2 + kh) ^ sw) << 4)) = hi;
+        }
     }
     int wide = stage_params(a, 0, 64, par_m, par_r);
 
     // ---- patch fetch: patch row j of tile t is flat input pixel  t*BP - W - 1 + j ----
-    const int p_row0 = lane >> 2;
+    // (INT8: 64-byte rows, four lanes per row, chunks XOR-swizzled; INT4: 32-byte rows, two lanes per row, plain)
+    const int p_row0 = INT4 ? lane >> 1 : lane >> 2;
     auto fetch_patch = [&](int tile, uint8_t *buf) {
         const int f0 = tile * BP - W - 1;
 #pragma unroll
         for (int jj = 0; jj < NPW; ++jj) {
             const int inst = wave + 4 * jj;
-            const int row = inst * 16 + p_row0;
-            const int ch = (lane & 3) ^ ((row >> 2) & 3);
+            const int row = inst * RPI + p_row0;
+            const int ch = INT4 ? (lane & 1) : ((lane & 3) ^ ((row >> 2) & 3));
             const int f = f0 + row;
             const bool ok = tile < n_tiles && row < prows && f >= 0 && f < n_in;   // other rows are filled with zeros
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rsrc_x, (__attribute__((address_space(3))) void *)(buf + inst * 1024), 16,
-                ok ? f * 64 + ch * 16 : (int)kInvalid, 0, 0, 0);
+                ok ? f * ROWB + ch * 16 : (int)kInvalid, 0, 0, 0);
         }
     };
     // shortcut bytes of the lane's outputs of a tile (16 channels per load; 4-bit data uses the first 8 bytes)
@@ -102,7 +129,7 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) a_fo[tc][kk] = row * 64 + (((kk * 2 + khalf) ^ ((row >> 2) & 3)) << 4);
     }
-    const int ml64 = (wave * 32 + rho) * 64;    // byte offset of the lane's pixel in the tap-(0,0) window
+    const int ml64 = (wave * 32 + rho) * ROWB;  // byte offset of the lane's pixel in the tap-(0,0) window
 
     // One tile: wait for its patch, start the next patch and shortcut fetch, multiply, requantise, store.
     // Vector-memory operations a wave issues per tile, in program order: NPW patch loads and R shortcut loads
@@ -139,15 +166,27 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
             constexpr int r = t / 3, s = t % 3;
             // bits 8-9 of the window row's byte offset are (row >> 2) & 3, its swizzle; the second-half chunk
             // index is the first-half one XOR 2
-            const int v = ml64 + (r * W + s) * 64;
-            const int c0 = (((v >> 8) & 3) ^ khalf) << 4;
+            const int v = ml64 + (r * W + s) * ROWB;
             const bool in = (mask >> t) & 1u;
             // a tap outside the image reads row PROWS-1 of the same buffer, which is beyond the rows in use and
             // therefore zero-filled by the fetch (plain offsets into the one buffer: the compiler then knows these
             // reads cannot touch the other patch buffer, whose asynchronous fill is in flight)
-            const int off0 = in ? v + c0 : (PROWS - 1) * 64 + khalf * 16;
-            const v4i b0 = *(const v4i *)(cur + off0);
-            const v4i b1 = *(const v4i *)(cur + (off0 ^ 32));
+            v4i b0, b1;
+            if constexpr (INT4) {
+                const int off = in ? v + khalf * 16 : (PROWS - 1) * ROWB + khalf * 16;
+                const v4i raw = *(const v4i *)(cur + off);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t u = (uint32_t)raw[e];
+                    b0[e] = (int)(u & 0x0F0F0F0Fu);
+                    b1[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
+                }
+            } else {
+                const int c0 = (((v >> 8) & 3) ^ khalf) << 4;
+                const int off0 = in ? v + c0 : (PROWS - 1) * 64 + khalf * 16;
+                b0 = *(const v4i *)(cur + off0);
+                b1 = *(const v4i *)(cur + (off0 ^ 32));
+            }
 #pragma unroll
             for (int tc = 0; tc < TC; ++tc) {
                 const v4i a0 = *(const v4i *)(wl + t * 4096 + a_fo[tc][0]);
@@ -183,7 +222,6 @@ conv3x3_c64_kernel(const ConvArgs a, const int n_tiles) {
 
 bool conv3x3_c64_eligible(const ConvArgs &a, int x_hi) {
     if (!conv_mfma_eligible(a, x_hi)) return false;
-    if (is4(a.x_dt)) return false;
     if (a.R != 3 || a.S != 3 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 1 || a.pad_w != 1) return false;
     if (a.C != 64 || a.K != 64) return false;
     if (128 + 2 * a.W + 2 > 255) return false;      // the patch of a tile has to fit its LDS buffer
@@ -194,6 +232,7 @@ bool conv3x3_c64_eligible(const ConvArgs &a, int x_hi) {
     al |= ((uintptr_t)a.c | (uintptr_t)a.res_c) & 3;
     if ((al & 15) != 0) return false;
     if ((int64_t)a.N * a.H * a.W * 64 >= ((int64_t)1 << 31)) return false;
+    if (is4(a.x_dt) && (((uintptr_t)a.x | (uintptr_t)a.w) & 15)) return false;
     return true;
 }
 
@@ -201,8 +240,14 @@ hawq_status launch_conv3x3_c64(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     const int n_tiles = (a.M + 127) / 128;
     const int grid = n_tiles < 512 ? n_tiles : 512;   // two workgroups per CU
-    if (a.res != nullptr) conv3x3_c64_kernel<true><<<grid, 256, 0, s>>>(a, n_tiles);
-    else conv3x3_c64_kernel<false><<<grid, 256, 0, s>>>(a, n_tiles);
+    const bool four = is4(a.x_dt);
+    if (a.res != nullptr) {
+        if (four) conv3x3_c64_kernel<true, true><<<grid, 256, 0, s>>>(a, n_tiles);
+        else conv3x3_c64_kernel<true, false><<<grid, 256, 0, s>>>(a, n_tiles);
+    } else {
+        if (four) conv3x3_c64_kernel<false, true><<<grid, 256, 0, s>>>(a, n_tiles);
+        else conv3x3_c64_kernel<false, false><<<grid, 256, 0, s>>>(a, n_tiles);
+    }
     return check_launch();
 }
 

@@ -188,6 +188,18 @@ def test_conv3x3_64_channels_resident_weights(hawq, N, H, W, res, res_signed, y_
     assert 0.05 < (v != 0).mean() and (v == y_hi).mean() < 0.5
 
 
+@pytest.mark.parametrize("N,H,W,res", [(11, 56, 56, False), (12, 55, 53, True), (40, 30, 29, True)])
+def test_conv3x3_64_channels_packed_int4(hawq, N, H, W, res):
+    """Packed 4-bit activations, weights, shortcut and output through the persistent 3x3 kernel."""
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=N + H + W + 4, N=N, H=H, W=W, C=64, K=64, R=3, S=3, stride=1, pad=1, bits=4,
+                                 with_residual=res), 4)
+    got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, res_dt=hawq.U4, y_hi=15)
+    assert_same(got, want, str((N, H, W)))
+    v = oracle.unpack(want, oracle.U4)
+    assert 0.05 < (v > 0).mean() < 0.999
+
+
 def test_conv3x3_64_channels_wide_parameters(hawq):
     """Multipliers outside the narrow epilogue's range take the exact 64-bit path inside the persistent kernel."""
     from gpu_util import run_conv_gpu, assert_same
