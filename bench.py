@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50_int8_b128", choices=sorted(WORKLOADS))
-    ap.add_argument("--cpu-images", type=int, default=48, help="images in the CPU-oracle baseline sample (0: skip)")
+    ap.add_argument("--cpu-images", type=int, default=256, help="images in the CPU-oracle baseline sample (0: skip)")
     ap.add_argument("--report", default=None, help="optional file for the per-layer table (JSON)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
@@ -155,7 +155,7 @@ def main():
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
     roof.update(traffic=profiled_traffic(args.workload),
-                kernel="one forward = %d launches (conv_stem_pool, conv_mfma, conv_pw, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
+                kernel="one forward = %d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
                 # the matrix-core convolutions alone, from per-launch events (each interval also holds a few
