@@ -86,6 +86,9 @@ typedef struct {
  * bias, b, res_b: int32 [K]; c, res_c: uint8 [K].  b == c == NULL is allowed only with
  * y_dtype == HAWQ_S32 and no residual: y = t (raw accumulator + bias).
  * The INT32 accumulator never goes to memory; x and y must not overlap.
+ * Every valid request is served; the matrix-core kernels need C a multiple of 64, 16-byte aligned x and w,
+ * at most 308 reduction steps (R*S*C/64) and, for their vector epilogue, K a multiple of 16 with 16-byte aligned
+ * y / residual / bias / b arrays -- anything else runs on a slower exact kernel with the same results.
  */
 hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias,
                             const int32_t *b, const uint8_t *c, const void *residual, const int32_t *res_b,
