@@ -49,6 +49,8 @@ def lib():
         _lib.oracle_unpack.argtypes = [vp, ctypes.c_int, i64, vp]
         _lib.oracle_conv2d_int.restype = ctypes.c_int
         _lib.oracle_conv2d_int.argtypes = [i32] * 11 + [ctypes.c_int] * 4 + [vp] * 8 + [i32, i64, i64, vp]
+        _lib.oracle_conv2d_dual_int.restype = ctypes.c_int
+        _lib.oracle_conv2d_dual_int.argtypes = [vp, vp, i32] + [ctypes.c_int] * 5 + [vp] * 10 + [i32, i64, i64, vp]
         _lib.oracle_gemm_int.restype = ctypes.c_int
         _lib.oracle_gemm_int.argtypes = [i32] * 3 + [ctypes.c_int] * 3 + [vp] * 5 + [i32, i64, i64, vp]
         _lib.oracle_residual_add_dyadic.restype = ctypes.c_int
@@ -128,6 +130,32 @@ def conv2d_int(x, w, bias, b, c, *, N, H, W, C, K, R, S, stride, pad, x_dt, w_dt
                                  _ptr(residual), _ptr(res_b), _ptr(res_c), int(relu), int(y_lo), int(y_hi), _ptr(y))
     if st != OK:
         raise OracleError(st, "oracle_conv2d_int")
+    return y
+
+
+def conv2d_dual_int(x, w, bias, b, c, xs, ws, bias_s, b_s, c_s, *, N, K, H, W, C, R, S, stride, pad, x_dt, w_dt,
+                    Hs, Ws, Cs, Rs, Ss, stride_s, pad_s, xs_dt, ws_dt, y_dt, relu, y_lo, y_hi):
+    """Block output with a convolution on both branches (main: x, w, ...; shortcut: xs, ws, ...), both INT32
+    accumulators rescaled by their own dyadic number and added; see ``oracle_conv2d_dual_int``."""
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    x = _c(x, _NP[x_dt]); w = _c(w, np.int8 if w_dt == S8 else _NP[w_dt])
+    xs = _c(xs, _NP[xs_dt]); ws = _c(ws, np.int8 if ws_dt == S8 else _NP[ws_dt])
+    bias = _c(bias, np.int32); b = _c(b, np.int32); c = _c(c, np.uint8)
+    bias_s = _c(bias_s, np.int32); b_s = _c(b_s, np.int32); c_s = _c(c_s, np.uint8)
+    assert x.size == nelems_to_bytes(N * H * W * C, x_dt) and w.size == nelems_to_bytes(K * R * S * C, w_dt)
+    assert xs.size == nelems_to_bytes(N * Hs * Ws * Cs, xs_dt) and ws.size == nelems_to_bytes(K * Rs * Ss * Cs, ws_dt)
+    for a in (bias, b, c, bias_s, b_s, c_s):
+        assert a.size == K
+    dims = np.array([N, H, W, C, R, S, stride, stride, pad, pad], dtype=np.int32)
+    dimss = np.array([Hs, Ws, Cs, Rs, Ss, stride_s, stride_s, pad_s, pad_s], dtype=np.int32)
+    y = _out(N * P * Q * K, y_dt, (N, P, Q, K))
+    st = lib().oracle_conv2d_dual_int(_ptr(dims), _ptr(dimss), K, x_dt, w_dt, xs_dt, ws_dt, y_dt,
+                                      _ptr(x), _ptr(w), _ptr(bias), _ptr(b), _ptr(c),
+                                      _ptr(xs), _ptr(ws), _ptr(bias_s), _ptr(b_s), _ptr(c_s),
+                                      int(relu), int(y_lo), int(y_hi), _ptr(y))
+    if st != OK:
+        raise OracleError(st, "oracle_conv2d_dual_int")
     return y
 
 

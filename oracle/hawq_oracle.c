@@ -16,7 +16,8 @@
  * max-pool (exact at these magnitudes), the paper's printed residual rounding
  * example (Appendix G), the batch-norm folding identity (Appendix D), the
  * packed/unpacked encoding invariant, and the paper's Table 1 BOPS totals for
- * the network topology.  Parity unpinned (paper silent; fixed by the readings
+ * the network topology; the two-convolution block output additionally against
+ * its composition from the single-convolution and residual-addition routines.  Parity unpinned (paper silent; fixed by the readings
  * stated in the design notes): tie-breaking direction of the rounding shift,
  * nibble order of packed 4-bit data, storage precision of the shortcut
  * tensor, the max-pool after the first convolution, the form of the global
@@ -200,6 +201,84 @@ int oracle_conv2d_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t K, int
                 }
     free(xw);
     free(ww);
+    return overflow ? OR_ERR_OVERFLOW : OR_OK;
+}
+
+/* ---- block output with a convolution on both branches ------------------------
+ * Section 3.3, the residual equation as Figure 2 (right) draws it for a block that
+ * changes shape: the main branch ends in a convolution and the shortcut is a
+ * convolution too, both accumulators stay INT32, each is rescaled by its own dyadic
+ * number (rounded separately -- Appendix G's worked example) and the integers are added:
+ *
+ *   t_m = sum x[n, p*s_h - pad_h + r, q*s_w - pad_w + s, c] * w[k,r,s,c] + bias[k]
+ *   t_s = sum xs[n, p*ss_h - pads_h + r, q*ss_w - pads_w + s, c] * ws[k,r,s,c] + bias_s[k]
+ *   y   = clamp( relu?( rq(t_m, b[k], c[k]) + rq(t_s, b_s[k], c_s[k]) ) )
+ *
+ * dims  = { N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w }   (main branch)
+ * dimss = {    Hs, Ws, Cs, Rs, Ss, stride_h, stride_w, pad_h, pad_w } (shortcut, same N)
+ * Both convolutions must produce the same P x Q x K output.                      */
+static int64_t conv_acc_one(const int32_t *xw, const int32_t *ww, int32_t n, int32_t p, int32_t q, int32_t k,
+                            int32_t H, int32_t W, int32_t C, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
+                            int32_t pad_h, int32_t pad_w)
+{
+    int64_t acc = 0;
+    for (int32_t r = 0; r < R; ++r) {
+        const int32_t ih = p * stride_h - pad_h + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int32_t s = 0; s < S; ++s) {
+            const int32_t iw = q * stride_w - pad_w + s;
+            if (iw < 0 || iw >= W) continue;
+            const int32_t *xp = xw + (((int64_t)n * H + ih) * W + iw) * C;
+            const int32_t *wp = ww + (((int64_t)k * R + r) * S + s) * C;
+            for (int32_t ci = 0; ci < C; ++ci) acc += (int64_t)xp[ci] * (int64_t)wp[ci];
+        }
+    }
+    return acc;
+}
+
+int oracle_conv2d_dual_int(const int32_t *dims, const int32_t *dimss, int32_t K,
+                           int x_dt, int w_dt, int xs_dt, int ws_dt, int y_dt,
+                           const void *x, const void *w, const int32_t *bias, const int32_t *b, const uint8_t *c,
+                           const void *xs, const void *ws, const int32_t *bias_s, const int32_t *b_s, const uint8_t *c_s,
+                           int32_t relu, int64_t y_lo, int64_t y_hi, void *y)
+{
+    if (!dims || !dimss || !x || !w || !bias || !b || !c || !xs || !ws || !bias_s || !b_s || !c_s || !y) return OR_ERR_ARG;
+    const int32_t N = dims[0], H = dims[1], W = dims[2], C = dims[3], R = dims[4], S = dims[5];
+    const int32_t sh = dims[6], sw = dims[7], ph = dims[8], pw = dims[9];
+    const int32_t Hs = dimss[0], Ws = dimss[1], Cs = dimss[2], Rs = dimss[3], Ss = dimss[4];
+    const int32_t ssh = dimss[5], ssw = dimss[6], psh = dimss[7], psw = dimss[8];
+    if (N < 0 || K <= 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return OR_ERR_ARG;
+    if (Hs <= 0 || Ws <= 0 || Cs <= 0 || Rs <= 0 || Ss <= 0 || ssh <= 0 || ssw <= 0 || psh < 0 || psw < 0) return OR_ERR_ARG;
+    if (H + 2 * ph < R || W + 2 * pw < S || Hs + 2 * psh < Rs || Ws + 2 * psw < Ss) return OR_ERR_ARG;
+    const int32_t P = (H + 2 * ph - R) / sh + 1, Q = (W + 2 * pw - S) / sw + 1;
+    if (P != (Hs + 2 * psh - Rs) / ssh + 1 || Q != (Ws + 2 * psw - Ss) / ssw + 1) return OR_ERR_ARG;
+    if (!type_range_ok(y_dt, y_lo, y_hi)) return OR_ERR_ARG;
+    if ((is4(x_dt) || is4(w_dt)) && (C % 2)) return OR_ERR_ARG;
+    if ((is4(xs_dt) || is4(ws_dt)) && (Cs % 2)) return OR_ERR_ARG;
+    if (is4(y_dt) && (K % 2)) return OR_ERR_ARG;
+
+    int32_t *xw = widen(x, x_dt, (int64_t)N * H * W * C);
+    int32_t *ww = widen(w, w_dt, (int64_t)K * R * S * C);
+    int32_t *xsw = widen(xs, xs_dt, (int64_t)N * Hs * Ws * Cs);
+    int32_t *wsw = widen(ws, ws_dt, (int64_t)K * Rs * Ss * Cs);
+    if (!xw || !ww || !xsw || !wsw) { free(xw); free(ww); free(xsw); free(wsw); return OR_ERR_ALLOC; }
+    if (is4(y_dt)) memset(y, 0, (size_t)(((int64_t)N * P * Q * K) / 2));
+    int overflow = 0;
+#pragma omp parallel for collapse(3) schedule(static) reduction(| : overflow)
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t p = 0; p < P; ++p)
+            for (int32_t q = 0; q < Q; ++q)
+                for (int32_t k = 0; k < K; ++k) {
+                    const int64_t t_m = conv_acc_one(xw, ww, n, p, q, k, H, W, C, R, S, sh, sw, ph, pw) + (int64_t)bias[k];
+                    const int64_t t_s = conv_acc_one(xsw, wsw, n, p, q, k, Hs, Ws, Cs, Rs, Ss, ssh, ssw, psh, psw) + (int64_t)bias_s[k];
+                    if (t_m > INT32_MAX || t_m < INT32_MIN || t_s > INT32_MAX || t_s < INT32_MIN) overflow |= 1;
+                    int64_t yv = oracle_rq(t_m, b[k], c[k]) + oracle_rq(t_s, b_s[k], c_s[k]);
+                    if (relu && yv < 0) yv = 0;
+                    if (yv < y_lo) yv = y_lo;
+                    if (yv > y_hi) yv = y_hi;
+                    store_elem(y, y_dt, (((int64_t)n * P + p) * Q + q) * K + k, yv);
+                }
+    free(xw); free(ww); free(xsw); free(wsw);
     return overflow ? OR_ERR_OVERFLOW : OR_OK;
 }
 

@@ -13,7 +13,10 @@ operation count reproduces Table 1's BOPS).  The shortcut is the block input, or
 1x1/s transition convolution (no ReLU, signed output) when the shape changes.
 The residual addition rescales both branches with their own dyadic numbers
 (Section 3.3); a block with a transition layer feeds the same stored block input to
-both 1x1 convolutions (Figure 2).
+both 1x1 convolutions (Figure 2).  A transition layer flagged ``int32_shortcut``
+is not stored at all: the block's output is formed from the two INT32 accumulators,
+each rescaled by its own dyadic number (the transition layer's (b, c) then map its
+accumulator to the block's output scale).
 
 Mixed precision (Section 3.4: weights and activations of a layer share one bit
 width): a tensor is stored at the width of the convolution that reads it, the
@@ -26,7 +29,7 @@ is checked against it layer by layer.
 """
 import numpy as np
 
-from . import (U8, S8, U4, S4, S32, conv2d_int, gemm_int, avgpool_int, maxpool_int)
+from . import (U8, S8, U4, S4, S32, conv2d_int, conv2d_dual_int, gemm_int, avgpool_int, maxpool_int)
 
 _WIDTHS = (64, 128, 256, 512)
 _DEPTHS = {18: (2, 2, 2, 2), 50: (3, 4, 6, 3)}
@@ -172,6 +175,16 @@ def forward(net, x, keep=None):
                 note(lj["name"], u)
                 u_dt, u_h = _act_dt(ob), _conv_out(u_h, lj["R"], lj["stride"], lj["pad"])
             # shortcut
+            if lds is not None and lds.get("int32_shortcut"):
+                t = conv2d_dual_int(u, last["w"], last["bias"], last["b"], last["c"],
+                                    block_in, lds["w"], lds["bias"], lds["b"], lds["c"],
+                                    N=N, K=cout, H=u_h, W=u_h, C=last["C"], R=last["R"], S=last["S"], stride=last["stride"],
+                                    pad=last["pad"], x_dt=u_dt, w_dt=_w_dt(last["bits"]),
+                                    Hs=h, Ws=h, Cs=cin, Rs=1, Ss=1, stride_s=s, pad_s=0, xs_dt=block_in_dt, ws_dt=_w_dt(lds["bits"]),
+                                    y_dt=_act_dt(out_bits), relu=1, y_lo=0, y_hi=_ACT_HI[out_bits])
+                note(last["name"], t)
+                cin, h, in_bits = cout, ho, out_bits
+                continue
             if lds is not None:
                 sc = run_conv(lds, block_in, h, block_in_dt, 8, relu=0, signed_out=True)
                 note(lds["name"], sc)

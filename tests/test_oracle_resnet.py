@@ -51,10 +51,15 @@ def _torch_forward(net, x):
         cc = c.astype(np.int64).reshape(1, -1, 1, 1)
         return (ti * bb + (np.int64(1) << (cc - 1))) // (np.int64(1) << cc)
 
-    def conv(l, inp, res=None):
-        t = F.conv2d(inp, vals(l), stride=l["stride"], padding=l["pad"]) + torch.from_numpy(l["bias"].astype(np.float64)).reshape(1, -1, 1, 1)
+    def acc(l, inp):
+        return F.conv2d(inp, vals(l), stride=l["stride"], padding=l["pad"]) + torch.from_numpy(l["bias"].astype(np.float64)).reshape(1, -1, 1, 1)
+
+    def conv(l, inp, res=None, sc_acc=None):
+        t = acc(l, inp)
         y = requant(t, l["b"], l["c"])
-        if res is not None:
+        if sc_acc is not None:          # the shortcut convolution's INT32 accumulator, rescaled by that layer's own (b, c)
+            y = y + requant(sc_acc[1], sc_acc[0]["b"], sc_acc[0]["c"])
+        elif res is not None:
             y = y + requant(res, l["res_b"], l["res_c"])
         if l["relu"]:
             y = np.maximum(y, 0)
@@ -70,13 +75,15 @@ def _torch_forward(net, x):
             blocks.append(pre)
     for pre in blocks:
         inp = t
-        sc = conv(L[pre + ".ds"], inp) if (pre + ".ds") in L else inp
+        ds = L.get(pre + ".ds")
+        sc_acc = (ds, acc(ds, inp)) if (ds is not None and ds["int32_shortcut"]) else None
+        sc = None if sc_acc is not None else (conv(ds, inp) if ds is not None else inp)
         u = conv(L[pre + ".c1"], inp)
         if (pre + ".c3") in L:
             u = conv(L[pre + ".c2"], u)
-            t = conv(L[pre + ".c3"], u, res=sc)
+            t = conv(L[pre + ".c3"], u, res=sc, sc_acc=sc_acc)
         else:
-            t = conv(L[pre + ".c2"], u, res=sc)
+            t = conv(L[pre + ".c2"], u, res=sc, sc_acc=sc_acc)
     s = t.sum(dim=(2, 3)).numpy().astype(np.int64)
     pb, pc = net["pool_b"].astype(np.int64), net["pool_c"].astype(np.int64)
     pooled = np.clip((s * pb + (1 << (pc - 1))) // (1 << pc), 0, 127)
@@ -84,10 +91,12 @@ def _torch_forward(net, x):
     return pooled @ fc["w_vals"].reshape(fc["K"], -1).astype(np.int64).T + fc["bias"].astype(np.int64)
 
 
-@pytest.mark.parametrize("arch,mixed", [(18, False), (50, False), (18, True), (50, True)])
-def test_forward_equals_independent_float64_composition(arch, mixed):
+@pytest.mark.parametrize("arch,mixed,int32_sc", [(18, False, False), (50, False, False), (18, True, False), (50, True, False),
+                                                 (18, False, True), (50, True, True)])
+def test_forward_equals_independent_float64_composition(arch, mixed, int32_sc):
     bits = wl.draw_bits(arch, 77 + arch) if mixed else None
-    net = wl.make_resnet(arch, seed=500 + arch, bits=bits, image_hw=64, num_classes=40)
+    net = wl.make_resnet(arch, seed=500 + arch, bits=bits, image_hw=64, num_classes=40, int32_shortcut=int32_sc)
+    assert sum(l["int32_shortcut"] and l["kind"] == "ds" for l in net["layers"]) == ((3 if arch == 18 else 4) if int32_sc else 0)
     if mixed:
         assert 0 < sum(l["bits"] == 4 for l in net["layers"]) < len(net["layers"])
     x = wl.make_image_batch(3, 2, image_hw=64)
@@ -98,12 +107,12 @@ def test_forward_equals_independent_float64_composition(arch, mixed):
     assert np.abs(got[0] - got[1]).max() > 0
 
 
-@pytest.mark.parametrize("arch,mixed", [(18, False), (50, True)])
-def test_synthetic_network_is_not_degenerate(arch, mixed):
+@pytest.mark.parametrize("arch,mixed,int32_sc", [(18, False, False), (50, True, False), (50, False, True)])
+def test_synthetic_network_is_not_degenerate(arch, mixed, int32_sc):
     """Random weights with arbitrary scales would saturate within a few layers and make bit-exactness
     vacuous; the generator centres every layer's scale analytically.  Check it worked."""
     bits = wl.draw_bits(arch, 4000 + arch) if mixed else None
-    net = wl.make_resnet(arch, seed=1000 + arch, bits=bits)
+    net = wl.make_resnet(arch, seed=1000 + arch, bits=bits, int32_shortcut=int32_sc)
     x = wl.make_image_batch(7, 1)
     keep = {}
     logits = onet.forward(net, x, keep)

@@ -122,8 +122,13 @@ def _shift_for(scale):
     return int(math.floor(math.log2(1.5 * (1 << 14) / scale)))
 
 
-def make_resnet(arch, seed, bits=None, image_hw=224, num_classes=1000):
+def make_resnet(arch, seed, bits=None, image_hw=224, num_classes=1000, int32_shortcut=False):
     """Random integer parameters for a whole integer-only ResNet.
+
+    int32_shortcut: every block with a transition convolution adds that convolution's INT32 accumulator
+    directly (both branches rescaled from INT32); the same draws are made, and the transition layer's shift
+    is then raised by the shortcut shift of the block's last convolution minus 15, so that its multiplier
+    maps the accumulator to the block's output scale instead of to a stored signed 8-bit tensor.
 
     `bits` maps group name -> 4 | 8 (default: all 8).  Per layer the draw order
     is w, bias, b, c, [res_b, res_c]; after the last layer: pool_b, pool_c.
@@ -230,6 +235,15 @@ def make_resnet(arch, seed, bits=None, image_hw=224, num_classes=1000):
         else:
             d["res_b"] = d["res_c"] = None
         layers.append(d)
+
+    for i, d in enumerate(layers):
+        d["int32_shortcut"] = False
+        if int32_shortcut and d["kind"] == "ds":
+            last = layers[i - 1]
+            assert last["has_residual"]
+            d["c"] = (d["c"].astype(np.int32) + last["res_c"].astype(np.int32) - 15).astype(np.uint8)
+            d["int32_shortcut"] = True
+            last["int32_shortcut"] = True
 
     c_last = shapes[-1]["C"]
     hw_pool = shapes[-2]["P"] * shapes[-2]["Q"]
