@@ -87,12 +87,32 @@ typedef struct {
  * y_dtype == HAWQ_S32 and no residual: y = t (raw accumulator + bias).
  * The INT32 accumulator never goes to memory; x and y must not overlap.
  * Every valid request is served; the matrix-core kernels need C a multiple of 64, 16-byte aligned x and w,
- * at most 308 reduction steps (R*S*C/64) and, for their vector epilogue, K a multiple of 16 with 16-byte aligned
+ * at most 304 reduction steps (R*S*C/64) and, for their vector epilogue, K a multiple of 16 with 16-byte aligned
  * y / residual / bias / b arrays -- anything else runs on a slower exact kernel with the same results.
  */
 hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias,
                             const int32_t *b, const uint8_t *c, const void *residual, const int32_t *res_b,
                             const uint8_t *res_c, void *y, void *stream);
+
+/*
+ * Block output with a convolution on both branches -- Section 3.3's residual equation in the form Figure 2 draws
+ * for a block that changes shape: the main branch ends in a convolution, the shortcut is a convolution too, both
+ * accumulators stay INT32 (neither is written to memory), each is rescaled by its own dyadic number, rounded
+ * separately (Appendix G's example) and the integers are added:
+ *   t_m = conv(x, w) + bias          t_s = conv(xs, ws) + bias_s
+ *   y   = clamp( relu?( rq(t_m, b[k], c[k]) + rq(t_s, b_s[k], c_s[k]) ), y_lo, y_hi )
+ * desc describes the main convolution and the output (y_dtype, relu, y_lo, y_hi; res_dtype is ignored); desc_s the
+ * shortcut convolution, which must be 1x1 without padding and give the same N, P, Q, K (its y_dtype, relu and
+ * clamp are ignored; its operand types follow the rule of hawq_conv2d_int on their own and may differ from the main
+ * branch's).  All twelve pointers are device memory and required.  Errors as hawq_conv2d_int; a shortcut that is not
+ * 1x1 / unpadded or whose output shape differs -> HAWQ_ERR_SHAPE.
+ * 8-bit operands on both branches with C and Cs multiples of 64, K a multiple of 16 and 16-byte aligned arrays run
+ * on the matrix cores in one launch; anything else runs on a slower exact kernel with the same results.
+ */
+hawq_status hawq_conv2d_dual_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias,
+                                 const int32_t *b, const uint8_t *c, const hawq_conv_desc *desc_s, const void *xs,
+                                 const void *ws, const int32_t *bias_s, const int32_t *b_s, const uint8_t *c_s, void *y,
+                                 void *stream);
 
 /*
  * Quantised fully connected layer / GEMM -- the matrix-multiply form of Section 3.1:
@@ -153,8 +173,15 @@ typedef struct {
     const int32_t *res_b;   /* [K] for the last conv of a block (it adds the shortcut), else NULL */
     const uint8_t *res_c;   /* [K] likewise                                                 */
     int32_t bits;           /* 4 or 8; conv1 and fc must be 8; ds must equal its block's c1 */
-    int32_t reserved;
+    int32_t flags;          /* HAWQ_LAYER_* bits, 0 for the default behaviour                */
 } hawq_layer_params;
+
+/* On a ds layer: the transition convolution's INT32 accumulator is not stored as a signed 8-bit tensor but added
+ * directly to the block's last convolution (hawq_conv2d_dual_int: Figure 2, both branches INT32).  The ds layer's
+ * (b, c) then map its accumulator to the block's OUTPUT scale, and the last convolution's res_b / res_c are unused
+ * (may be NULL).  One launch replaces two wherever the matrix-core form applies; otherwise the two raw INT32
+ * accumulators pass through the workspace and a residual-addition launch. */
+#define HAWQ_LAYER_INT32_SHORTCUT 1
 
 /* Shape of layer `index` of the canonical order, for a square image of side image_hw. */
 typedef struct {

@@ -28,7 +28,10 @@ class ConvDesc(ctypes.Structure):
 
 class LayerParams(ctypes.Structure):
     _fields_ = [("w", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("b", ctypes.c_void_p), ("c", ctypes.c_void_p),
-                ("res_b", ctypes.c_void_p), ("res_c", ctypes.c_void_p), ("bits", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("res_b", ctypes.c_void_p), ("res_c", ctypes.c_void_p), ("bits", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+LAYER_INT32_SHORTCUT = 1
 
 
 class LayerInfo(ctypes.Structure):
@@ -51,6 +54,8 @@ def load_library():
     i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
     lib.hawq_conv2d_int.restype = ctypes.c_int
     lib.hawq_conv2d_int.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 10
+    lib.hawq_conv2d_dual_int.restype = ctypes.c_int
+    lib.hawq_conv2d_dual_int.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 5 + [ctypes.POINTER(ConvDesc)] + [vp] * 7
     lib.hawq_gemm_int.restype = ctypes.c_int
     lib.hawq_gemm_int.argtypes = [i32] * 6 + [vp] * 5 + [i32] * 3 + [vp, vp]
     lib.hawq_residual_add_dyadic.restype = ctypes.c_int
@@ -117,6 +122,12 @@ def hawq_conv2d_int(desc, x, w, bias, b, c, residual, res_b, res_c, y, stream=No
                                            _p(res_b), _p(res_c), _p(y), _stream(stream)), "hawq_conv2d_int")
 
 
+def hawq_conv2d_dual_int(desc, x, w, bias, b, c, desc_s, xs, ws, bias_s, b_s, c_s, y, stream=None):
+    _check(load_library().hawq_conv2d_dual_int(ctypes.byref(desc), _p(x), _p(w), _p(bias), _p(b), _p(c), ctypes.byref(desc_s),
+                                                _p(xs), _p(ws), _p(bias_s), _p(b_s), _p(c_s), _p(y), _stream(stream)),
+           "hawq_conv2d_dual_int")
+
+
 def hawq_gemm_int(M, N, Kdim, x_dt, w_dt, y_dt, x, w, bias, b, c, relu, y_lo, y_hi, y, stream=None):
     _check(load_library().hawq_gemm_int(M, N, Kdim, x_dt, w_dt, y_dt, _p(x), _p(w), _p(bias), _p(b), _p(c), relu, y_lo,
                                          y_hi, _p(y), _stream(stream)), "hawq_gemm_int")
@@ -156,7 +167,8 @@ def hawq_net_layer_info(arch, image_hw, num_classes, index):
 
 class HawqNet:
     """Owner of a ``hawq_net*``.  ``layers`` is the list of per-layer dicts of host numpy arrays in
-    canonical order (keys w, bias, b, c, res_b, res_c, bits), as made by the workload generator."""
+    canonical order (keys w, bias, b, c, res_b, res_c, bits and optionally int32_shortcut on a transition layer),
+    as made by the workload generator or the converter."""
 
     def __init__(self, arch, layers, pool_b, pool_c, image_hw=224, num_classes=1000, keep_activations=False):
         import numpy as np
@@ -179,6 +191,7 @@ class HawqNet:
             arr[i].res_b = hp(l.get("res_b"), np.int32)
             arr[i].res_c = hp(l.get("res_c"), np.uint8)
             arr[i].bits = int(l["bits"])
+            arr[i].flags = LAYER_INT32_SHORTCUT if (l.get("int32_shortcut") and l["name"].endswith(".ds")) else 0
         handle = ctypes.c_void_p()
         _check(lib.hawq_net_create(arch, image_hw, num_classes, arr, len(layers), hp(pool_b, np.int32), hp(pool_c, np.uint8),
                                    1 if keep_activations else 0, ctypes.byref(handle)), "hawq_net_create")

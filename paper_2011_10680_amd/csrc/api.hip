@@ -85,6 +85,8 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     a.x = (const uint8_t *)x; a.w = (const uint8_t *)w; a.bias = bias; a.b = b; a.c = c;
     a.res = (const uint8_t *)residual; a.res_b = residual ? res_b : nullptr; a.res_c = residual ? res_c : nullptr;
     a.y = (uint8_t *)y;
+    a.xs = nullptr; a.ws = nullptr; a.bias_s = nullptr; a.b_s = nullptr; a.c_s = nullptr;
+    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.P = (int32_t)P; a.Q = (int32_t)Q; a.M = (int32_t)M;
@@ -107,6 +109,36 @@ hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     return launch_conv_direct(a, s);
 }
 
+// Validate a two-convolution block output and fill the kernel argument block (main branch as make_conv_args; the
+// shortcut convolution's fields from its own descriptor).
+hawq_status make_dual_args(const hawq_conv_desc *d, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                           const uint8_t *c, const hawq_conv_desc *ds, const void *xs, const void *ws, const int32_t *bias_s,
+                           const int32_t *b_s, const uint8_t *c_s, void *y, bool check_pointers, ConvArgs &a, int &x_hi, int &xs_hi) {
+    if (!d || !ds) return HAWQ_ERR_NULL;
+    hawq_conv_desc dm = *d;
+    dm.res_dtype = HAWQ_U8;
+    hawq_status st = make_conv_args(&dm, x, w, bias, b, c, nullptr, nullptr, nullptr, y, check_pointers, a, x_hi);
+    if (st != HAWQ_OK) return st;
+    if (d->y_dtype == HAWQ_S32) return HAWQ_ERR_DTYPE;   // the block output is a requantised tensor
+    // the shortcut convolution on its own terms: operand types, overflow bound, sizes (its output fields are the block's)
+    hawq_conv_desc dsc = *ds;
+    dsc.y_dtype = d->y_dtype; dsc.relu = d->relu; dsc.y_lo = d->y_lo; dsc.y_hi = d->y_hi; dsc.res_dtype = HAWQ_U8;
+    ConvArgs t;
+    st = make_conv_args(&dsc, xs, ws, bias_s, b_s, c_s, nullptr, nullptr, nullptr, y, check_pointers, t, xs_hi);
+    if (st != HAWQ_OK) return st;
+    if (t.R != 1 || t.S != 1 || t.pad_h != 0 || t.pad_w != 0) return HAWQ_ERR_SHAPE;
+    if (t.N != a.N || t.P != a.P || t.Q != a.Q || t.K != a.K) return HAWQ_ERR_SHAPE;
+    a.xs = t.x; a.ws = t.w; a.bias_s = t.bias; a.b_s = t.b; a.c_s = t.c;
+    a.Hs = t.H; a.Ws = t.W; a.Cs = t.C; a.stride_sh = t.stride_h; a.stride_sw = t.stride_w; a.xs_dt = t.x_dt; a.ws_dt = t.w_dt;
+    return HAWQ_OK;
+}
+
+hawq_status dispatch_conv_dual(const ConvArgs &a, int x_hi, int xs_hi, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    if (conv_mfma_dual_eligible(a, x_hi, xs_hi)) return launch_conv_mfma_dual(a, s);
+    return launch_conv_direct(a, s);
+}
+
 }  // namespace hawq
 
 extern "C" {
@@ -119,6 +151,17 @@ hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const voi
     hawq_status st = make_conv_args(desc, x, w, bias, b, c, residual, res_b, res_c, y, true, a, x_hi);
     if (st != HAWQ_OK) return st;
     return dispatch_conv(a, x_hi, (hipStream_t)stream);
+}
+
+hawq_status hawq_conv2d_dual_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                                 const uint8_t *c, const hawq_conv_desc *desc_s, const void *xs, const void *ws,
+                                 const int32_t *bias_s, const int32_t *b_s, const uint8_t *c_s, void *y, void *stream) {
+    if (!desc || !desc_s || !b || !c || !b_s || !c_s) return HAWQ_ERR_NULL;
+    ConvArgs a;
+    int x_hi, xs_hi;
+    hawq_status st = make_dual_args(desc, x, w, bias, b, c, desc_s, xs, ws, bias_s, b_s, c_s, y, true, a, x_hi, xs_hi);
+    if (st != HAWQ_OK) return st;
+    return dispatch_conv_dual(a, x_hi, xs_hi, (hipStream_t)stream);
 }
 
 hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int32_t w_dt, int32_t y_dt, const void *x,

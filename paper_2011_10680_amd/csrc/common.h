@@ -28,6 +28,13 @@ struct ConvArgs {
     int32_t M;               // N*P*Q output pixels
     int32_t x_dt, w_dt, y_dt, res_dt;
     int32_t lo, hi;          // clamp with ReLU already folded in (lo = max(lo,0))
+    // Optional second convolution on the shortcut branch (xs != nullptr; 1x1, unpadded, same N, P, Q, K): its INT32
+    // accumulator plus bias_s is rescaled by (b_s, c_s) and added to the rescaled main branch.  res is null then.
+    const uint8_t *xs;       // shortcut activations [N][Hs][Ws][Cs]
+    const uint8_t *ws;       // shortcut weights [K][Cs]
+    const int32_t *bias_s, *b_s;
+    const uint8_t *c_s;
+    int32_t Hs, Ws, Cs, stride_sh, stride_sw, xs_dt, ws_dt;
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }
@@ -112,7 +119,10 @@ int tile_override();
 // 3x3 / stride 1 / pad 1, 64 -> 64 channels, INT8: weights resident in LDS, pixel operand kept across the taps
 bool conv3x3_c64_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv3x3_c64(const ConvArgs &a, hipStream_t s);
-hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape
+hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid shape (also with a shortcut convolution)
+// matrix-core kernel for a block output with a convolution on both branches (ConvArgs::xs set)
+bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi);
+hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s);
 // persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);

@@ -1,8 +1,8 @@
 // Direct quantised convolution: one thread per output element (per pair of channels for 4-bit
 // outputs), scalar integer multiply-accumulate.  Serves every shape and type combination the
 // interface accepts that the matrix-core kernel does not (channel counts that are not a
-// multiple of 64, unsigned 8-bit inputs above 127, unaligned buffers).  Same arithmetic,
-// same epilogue order as the fast kernel.
+// multiple of 64, unsigned 8-bit inputs above 127, unaligned buffers), with or without a second
+// convolution on the shortcut branch.  Same arithmetic, same epilogue order as the fast kernels.
 #include "common.h"
 
 namespace hawq {
@@ -39,6 +39,13 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(const ConvArgs a, cons
         } else {
             int64_t v = rq64(t, a.b[k], a.c[k]);
             if (has_res) v += rq64(load_elem(a.res, a.res_dt, m * a.K + k), a.res_b[k], a.res_c[k]);
+            if (a.xs != nullptr) {   // shortcut convolution (1x1, unpadded): its own accumulator, bias and dyadic number
+                int32_t acc_s = 0;
+                const int64_t xo = (((int64_t)n * a.Hs + p * a.stride_sh) * a.Ws + q * a.stride_sw) * a.Cs;
+                const int64_t wo = (int64_t)k * a.Cs;
+                for (int c = 0; c < a.Cs; ++c) acc_s += load_elem(a.xs, a.xs_dt, xo + c) * load_elem(a.ws, a.ws_dt, wo + c);
+                v += rq64(acc_s + a.bias_s[k], a.b_s[k], a.c_s[k]);
+            }
             out[e] = clamp64(v, a.lo, a.hi);
         }
     }

@@ -31,7 +31,10 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
 // shapes live on occupancy).
 // NBUF: LDS buffers in the operand ring (4, or 8 for the LDS-DMA path when one workgroup has a CU to itself)
-template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4>
+// DUAL: block output with a convolution on both branches (Section 3.3's residual equation with two INT32 accumulators,
+// Figure 2): after the main convolution's K-steps the same pipeline runs on through the K-steps of the 1x1 shortcut
+// convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds both.
+template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, bool DUAL = false>
 __global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr int T = WC * WP * 64;
@@ -53,6 +56,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     __shared__ __attribute__((aligned(1024))) uint8_t lds2[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds3[kBufBytes];
     static_assert(NBUF == 4 || (NBUF == 8 && !INT4), "ring depth");
+    static_assert(!DUAL || !INT4, "the two-convolution form takes 8-bit operands");
     __shared__ __attribute__((aligned(1024))) uint8_t lds4[NBUF == 8 ? kBufBytes : 16];
     __shared__ __attribute__((aligned(1024))) uint8_t lds5[NBUF == 8 ? kBufBytes : 16];
     __shared__ __attribute__((aligned(1024))) uint8_t lds6[NBUF == 8 ? kBufBytes : 16];
@@ -69,7 +73,8 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         else return lds7;
     };
     __shared__ ChanMain par_m[BC];
-    __shared__ ChanRes par_r[BC];
+    __shared__ ChanRes par_r[DUAL ? 1 : BC];
+    __shared__ ChanMain par_s[DUAL ? BC : 1];   // the shortcut convolution's staged parameters
     // Per K-step addressing, tabulated once per workgroup: {weight offset, activation tap offset, r | s << 16}.
     // Deriving these in the loop costs each wave some twenty scalar instructions per step, and the one scalar
     // unit of a CU serves all its waves: with sixteen waves resident that alone approaches the duration of
@@ -86,15 +91,21 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
 
     const int Cb = INT4 ? a.C / 2 : a.C;          // bytes per pixel
     const int cchunks = a.C / 64;                 // K-steps per tap
-    const int steps = a.R * a.S * cchunks;
+    const int steps1 = a.R * a.S * cchunks;             // K-steps of the (main) convolution
+    const int steps = steps1 + (DUAL ? a.Cs / 64 : 0);  // ... followed by those of the shortcut convolution
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
-    for (int i = tid; i < steps + NBUF + 4; i += T) {
+    // (the rounded-up loop fetches at most 2*NBUF - 2 entries past the last step)
+    for (int i = tid; i < steps + 2 * NBUF; i += T) {
         const int st = i < steps ? i : steps - 1;      // past the last step the activation address stays put ...
-        const int cc = st % cchunks, t = st / cchunks;
-        const int s_ = t % a.S, r_ = t / a.S;
         // ... and the weight offset leaves the buffer: the weights read as zeros, padded iterations add nothing
-        steptab[i] = make_int4(i < steps ? i * (INT4 ? 32 : 64) : 0x40000000, (r_ * a.W + s_) * Cb + cc * (INT4 ? 32 : 64),
-                               r_ | (s_ << 16), 0);
+        if (DUAL && st >= steps1) {
+            steptab[i] = make_int4(i < steps ? (st - steps1) * 64 : 0x40000000, (st - steps1) * 64, 0, 0);
+        } else {
+            const int cc = st % cchunks, t = st / cchunks;
+            const int s_ = t % a.S, r_ = t / a.S;
+            steptab[i] = make_int4(i < steps ? i * (INT4 ? 32 : 64) : 0x40000000, (r_ * a.W + s_) * Cb + cc * (INT4 ? 32 : 64),
+                                   r_ | (s_ << 16), 0);
+        }
     }
     __syncthreads();
 
@@ -103,9 +114,10 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // filter tap falls into the zero padding, presents an offset beyond num_records and the
     // hardware returns zeros -- no branch, no select, and the address is one 32-bit add.
     constexpr uint32_t kInvalid = 0x80000000u;     // >= any tensor size the interface accepts
-    const __amdgpu_buffer_rsrc_t rsrc_w =
+    // (not const: the two-convolution form switches descriptors and offsets to the shortcut's tensors once)
+    __amdgpu_buffer_rsrc_t rsrc_w =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * wrow_bytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_x =
+    __amdgpu_buffer_rsrc_t rsrc_x =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.N * a.H * a.W * Cb), 0x00020000);
     int a_row[NA], a_ch[NA];
     uint32_t a_voff[NA];
@@ -124,7 +136,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     uint32_t b_voff[NB];   // offset of tap (0,0), channel chunk 0 (may be "negative" inside the padding)
     bool b_ok[NB];
     const int PQ = a.P * a.Q;
-    const bool padded = (a.pad_h | a.pad_w) != 0;
+    bool padded = (a.pad_h | a.pad_w) != 0;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int i = tid + j * T;
@@ -139,6 +151,33 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         b_iw0[j] = q * a.stride_w - a.pad_w;
         b_voff[j] = (uint32_t)(((n * a.H + b_ih0[j]) * a.W + b_iw0[j]) * Cb + b_ch[j] * 16);
         if (!b_ok[j] && !padded) b_voff[j] = kInvalid;   // unpadded: validity never changes with the tap
+    }
+
+    v16i acc[TP][TC];
+    v16i accm[DUAL ? TP : 1][DUAL ? TC : 1];   // two-convolution form: the finished main-branch accumulators
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
+    if constexpr (DUAL) {
+        // The same rows' offsets into the shortcut convolution's weights and (strided, unpadded) activations.  They are
+        // needed once, when the fetches switch over, which is always before the main accumulators are parked in accm:
+        // until then they live in accm's registers instead of adding to the loop's register pressure.
+        static_assert(NA + NB <= 16, "parking space");
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            const int k = k0 + a_row[j];
+            accm[0][0][j] = (int)(k < a.K ? (uint32_t)(k * a.Cs + a_ch[j] * 16) : kInvalid);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int mm = b_ok[j] ? m0 + b_row[j] : 0;
+            const int n = mm / PQ, pq = mm - n * PQ;
+            const int p = pq / a.Q, q = pq - p * a.Q;
+            accm[0][0][NA + j] = (int)(b_ok[j] ? (uint32_t)(((n * a.Hs + p * a.stride_sh) * a.Ws + q * a.stride_sw) * a.Cs + b_ch[j] * 16) : kInvalid);
+        }
     }
 
     // Two register sets: while K-step t is multiplied out of LDS, step t+1 sits in one set (issued one
@@ -157,6 +196,18 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     auto gload = [&](int step, auto setc) {
         constexpr int set = decltype(setc)::value;
         (void)step;
+        if constexpr (DUAL) {
+            if (tab_i == steps1) {   // first K-step of the shortcut convolution: from here on its tensors are fetched
+                rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws, 0, (int)((int64_t)a.K * a.Cs), 0x00020000);
+                rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.xs, 0, (int)((int64_t)a.N * a.Hs * a.Ws * a.Cs), 0x00020000);
+                // the shortcut's offsets were parked in the not yet used second accumulator set (see below)
+#pragma unroll
+                for (int j = 0; j < NA; ++j) a_voff[j] = (uint32_t)accm[0][0][j];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) b_voff[j] = (uint32_t)accm[0][0][NA + j];
+                padded = false;
+            }
+        }
         const uint32_t a_off = (uint32_t)ent.x, tapoff = (uint32_t)ent.y;
         const int r = ent.z & 0xffff, s = ent.z >> 16;
 #pragma unroll
@@ -257,14 +308,6 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         for (int kk = 0; kk < 2; ++kk) b_fo[tp][kk] = BC * 64 + row * 64 + (((kk * 2 + khalf) ^ swz(row)) << 4);
     }
 
-    v16i acc[TP][TC];
-#pragma unroll
-    for (int tp = 0; tp < TP; ++tp)
-#pragma unroll
-        for (int tc = 0; tc < TC; ++tc)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
-
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, 1>;
     using S2 = std::integral_constant<int, 2>;
@@ -278,7 +321,8 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
-    if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
+    if constexpr (DUAL) wide = stage_params_dual(a, k0, BC, par_m, par_s);
+    else if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
     // the lane's shortcut bytes are fetched now, a whole K loop ahead of their use in the epilogue
     uint32_t resw[TP][TC][4] = {};
     const bool has_res = tile_epi && a.res != nullptr;
@@ -339,6 +383,18 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         using Wr = std::integral_constant<int, (phase + 2) % 4>;
         using Dma = std::integral_constant<int, (phase + NBUF - 1) % NBUF>;
         using Set = std::integral_constant<int, phase % 2>;
+        if constexpr (DUAL) {
+            if (step == steps1) {   // the main convolution is complete: park its accumulators, start the shortcut's at zero
+#pragma unroll
+                for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+                    for (int tc = 0; tc < TC; ++tc) {
+                        accm[tp][tc] = acc[tp][tc];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
+                    }
+            }
+        }
         v4i af1[TC], bf1[TP];
 #pragma unroll
         for (int tc = 0; tc < TC; ++tc) af1[tc] = *(const v4i *)(ldsbuf(Cur{}) + a_fo[tc][1]);
@@ -389,6 +445,16 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int chl = wc * (BC / WC) + khalf * 16 * TC;
     const int ch0 = k0 + chl;
     if (ch0 >= a.K) return;
+    if constexpr (DUAL) {
+        int64_t mm[TP];
+        bool valid[TP];
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            mm[tp] = m0 + wp * (BP / WP) + tp * 32 + rho;
+            valid[tp] = mm[tp] < a.M;
+        }
+        epilogue_tile_dual<TC, TP>(a, par_m, par_s, mm, valid, k0, chl, accm, acc, wide);
+    } else {
     if (tile_epi) {
         int64_t mm[TP];
         bool valid[TP];
@@ -407,6 +473,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         if (vec_epilogue) epilogue_pixel<TC, true>(a, m, ch0, acc[tp]);
         else epilogue_pixel<TC, false>(a, m, ch0, acc[tp]);
     });
+    }
 }
 
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
@@ -421,8 +488,28 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
         if (a.x_dt != HAWQ_U8 && a.x_dt != HAWQ_S8) return false;
     }
     if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
-    if ((int64_t)a.R * a.S * (a.C / 64) + 12 > kMaxSteps) return false;   // the per-step address table is in LDS
+    if ((int64_t)a.R * a.S * (a.C / 64) + 16 > kMaxSteps) return false;   // the per-step address table is in LDS
     return true;
+}
+
+bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi) {
+    if (a.xs == nullptr || a.res != nullptr || a.b == nullptr) return false;
+    if (!conv_mfma_eligible(a, x_hi) || is4(a.x_dt)) return false;
+    if (a.Cs % 64 != 0 || a.ws_dt != HAWQ_S8) return false;
+    if (a.xs_dt == HAWQ_U8 ? xs_hi > 127 : a.xs_dt != HAWQ_S8) return false;
+    if ((int64_t)a.R * a.S * (a.C / 64) + a.Cs / 64 + 16 > kMaxSteps) return false;
+    // every array 16-byte aligned, whole 16-channel groups (the epilogue's vector form), 8-bit or unsigned 4-bit output
+    uintptr_t al = (uintptr_t)a.xs | (uintptr_t)a.ws | (uintptr_t)a.y | (uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.bias_s |
+                   (uintptr_t)a.b_s | (uintptr_t)a.c | (uintptr_t)a.c_s;
+    if ((al & 15) || a.K % 16 != 0 || a.y_dt == HAWQ_S32) return false;
+    return true;
+}
+
+hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    const uint32_t n_ctiles = (a.K + 127) / 128, n_mtiles = (a.M + 127) / 128;
+    conv_mfma_kernel<128, 128, 4, 2, false, 4, true><<<n_ctiles * n_mtiles, 512, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
+    return check_launch();
 }
 
 template <int BC, int BP, int WC, int WP>

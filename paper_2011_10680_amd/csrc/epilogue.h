@@ -183,6 +183,35 @@ __device__ __forceinline__ int stage_channel(const ConvArgs &a, int k, ChanMain 
     return wide;
 }
 
+// One branch of a two-convolution block output: { bias, b, c } of channel k in ChanMain form.
+__device__ __forceinline__ int stage_branch(const int32_t *bias, const int32_t *b, const uint8_t *c, int k, int K, ChanMain &m) {
+    int wide = 0;
+    m = ChanMain{0, 1, 0, 0, 0, 0};
+    if (k < K) {
+        m.b = b[k]; m.c = c[k];
+        m.R = (int64_t)bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
+        if (m.c > 32 || ((int64_t)m.b >> (m.c - 1)) != 0) {
+            wide = 1;
+        } else {
+            m.bs = (int32_t)((uint32_t)m.b << (32 - m.c));
+            m.Rs = (int64_t)((uint64_t)m.R << (32 - m.c));
+        }
+    }
+    return wide;
+}
+
+__device__ __forceinline__ int stage_params_dual(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanMain *ps) {
+    int wide = 0;
+    const int i = threadIdx.x;
+    if (i < n_ch) {
+        ChanMain m, r;
+        wide = stage_branch(a.bias, a.b, a.c, k0 + i, a.K, m) | stage_branch(a.bias_s, a.b_s, a.c_s, k0 + i, a.K, r);
+        pm[i] = m;
+        ps[i] = r;
+    }
+    return wide;
+}
+
 __device__ __forceinline__ int stage_params(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanRes *pr) {
     int wide = 0;
     const int i = threadIdx.x;
@@ -380,6 +409,88 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
                         *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
                     }
                 }
+            }
+        }
+    });
+}
+
+// Epilogue of a block output with a convolution on both branches (Section 3.3's residual equation with two INT32
+// accumulators): y = clamp( rq(accm + bias, b, c) + rq(accs + bias_s, b_s, c_s) ), same lane layout and stores as
+// epilogue_tile (plain global stores of the valid pixels; K % 16 == 0).  pm / ps: the two branches' staged parameters.
+template <int TC, int TP>
+__device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const ChanMain *pm, const ChanMain *ps, const int64_t (&m)[TP],
+                                                   const bool (&valid)[TP], int k0, int chl, const v16i (&accm)[TP][TC],
+                                                   const v16i (&accs)[TP][TC], int wide) {
+    const int y_dt = a.y_dt;
+    const bool y4 = is4(y_dt);
+    int32_t lo = a.lo, hi = a.hi;
+    if (wide || y_dt == HAWQ_S4) {
+        // exact general form: 64-bit products, shifts and clamp
+        static_for<0, TC>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            const int chg = k0 + chl + 16 * g;
+            if (chg >= a.K) return;
+            static_for<0, TP>([&](auto tpc) {
+                constexpr int tp = decltype(tpc)::value;
+                if (!valid[tp]) return;
+                const int64_t o = m[tp] * (int64_t)a.K + chg;
+                uint32_t ow[4] = {0, 0, 0, 0};
+                static_for<0, 16>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    const ChanMain p1 = pm[chl + 16 * g + i], p2 = ps[chl + 16 * g + i];
+                    int32_t av = accm[tp][g][i], sv = accs[tp][g][i];
+                    asm volatile("" : "+v"(av), "+v"(sv));   // keeps this cold path's products apart from the narrow path's
+                    const int64_t w64 = (((int64_t)av * (int64_t)p1.b + p1.R) >> p1.c) + (((int64_t)sv * (int64_t)p2.b + p2.R) >> p2.c);
+                    const int32_t y = clamp64(w64, lo, hi);
+                    if (y4) ow[i >> 3] |= (uint32_t)(y & 0xf) << (4 * (i & 7));
+                    else ow[i >> 2] |= (uint32_t)(y & 0xff) << (8 * (i & 3));
+                });
+                if (y4) *(uint2 *)(a.y + (o >> 1)) = make_uint2(ow[0], ow[1]);
+                else *(uint4 *)(a.y + o) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+            });
+        });
+        return;
+    }
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    static_for<0, TC>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        const int chg = k0 + chl + 16 * g;
+        if (chg >= a.K) return;
+        int32_t y[TP][16];
+        static_for<0, 16>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const ChanMain &p1 = pm[chl + 16 * g + i];
+            const ChanMain &p2 = ps[chl + 16 * g + i];
+            const int32_t bs1 = p1.bs, bs2 = p2.bs;
+            const int64_t Rs1 = p1.Rs, Rs2 = p2.Rs;
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
+                const int32_t v = (int32_t)(((int64_t)accm[tp][g][i] * (int64_t)bs1 + Rs1) >> 32) +
+                                  (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                int32_t t;
+                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(v), "v"(lo), "v"(hi));
+                y[tp][i] = t;
+            }
+        });
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            if (y4) {
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    w0 |= (uint32_t)y[tp][i] << (4 * i);
+                    w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
+                }
+                if (valid[tp]) *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+            } else {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 1], (uint32_t)y[tp][4 * q], 0x0c0c0400u);
+                    const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
+                    w[q] = t0 | t1;
+                }
+                if (valid[tp]) *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
     });

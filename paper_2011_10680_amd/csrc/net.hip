@@ -13,6 +13,10 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
                            const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,
                            bool check_pointers, ConvArgs &a, int &x_hi_out);
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s);
+hawq_status make_dual_args(const hawq_conv_desc *d, const void *x, const void *w, const int32_t *bias, const int32_t *b,
+                           const uint8_t *c, const hawq_conv_desc *ds, const void *xs, const void *ws, const int32_t *bias_s,
+                           const int32_t *b_s, const uint8_t *c_s, void *y, bool check_pointers, ConvArgs &a, int &x_hi, int &xs_hi);
+hawq_status dispatch_conv_dual(const ConvArgs &a, int x_hi, int xs_hi, hipStream_t s);
 void stem_pack_weights(const int8_t *w, int8_t *out);
 bool conv_stem_eligible(const ConvArgs &a);
 }  // namespace hawq
@@ -66,7 +70,9 @@ bool build_topology(int arch, int hw, int classes, std::vector<LayerShape> &out)
     return true;
 }
 
-enum StepKind { STEP_STEM, STEP_MAXPOOL, STEP_CONV, STEP_AVGPOOL, STEP_FC };
+// STEP_CONV_DUAL: a block's last convolution and its transition convolution in one launch (both INT32 accumulators
+// rescaled and added); STEP_RESADD: the same sum formed from two raw INT32 tensors in the workspace.
+enum StepKind { STEP_STEM, STEP_MAXPOOL, STEP_CONV, STEP_AVGPOOL, STEP_FC, STEP_CONV_DUAL, STEP_RESADD };
 
 struct Tensor {           // a stored activation
     int64_t elems_per_image;
@@ -82,6 +88,11 @@ struct Step {
     int layer = -1;               // index into the canonical layer list
     int in = -1, res = -1, out = -1;  // tensor ids (-1: external image / logits)
     hawq_conv_desc desc{};        // N filled per call
+    hawq_conv_desc desc_s{};      // STEP_CONV_DUAL: the transition convolution (reads tensor `res`)
+    const uint8_t *w_s = nullptr;             // ... its parameters
+    const int32_t *bias_s = nullptr, *b_s = nullptr;
+    const uint8_t *c_s = nullptr;
+    bool raw = false;             // STEP_CONV: store the INT32 accumulator + bias, no requantisation
     const uint8_t *w = nullptr;   // device parameter pointers
     const uint8_t *w_stem = nullptr;      // conv1 only: weights re-tiled for the stem kernel
     const int32_t *bias_stem = nullptr;   //             bias + 128 * sum(w) (input offset correction)
@@ -192,7 +203,11 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         const hawq_layer_params &p = lp[i];
         if (!p.w || !p.bias) return fail(HAWQ_ERR_NULL);
         if (!L[i].is_fc && (!p.b || !p.c)) return fail(HAWQ_ERR_NULL);
-        if (L[i].has_residual && (!p.res_b || !p.res_c)) return fail(HAWQ_ERR_NULL);
+        if (p.flags & ~HAWQ_LAYER_INT32_SHORTCUT) return fail(HAWQ_ERR_UNSUPPORTED);
+        if ((p.flags & HAWQ_LAYER_INT32_SHORTCUT) && !L[i].is_ds) return fail(HAWQ_ERR_UNSUPPORTED);
+        // the shortcut multiplier of a block's last convolution is unused when its transition layer keeps INT32
+        const bool i32sc = L[i].has_residual && i + 1 < nl && L[i + 1].is_ds && (lp[i + 1].flags & HAWQ_LAYER_INT32_SHORTCUT);
+        if (L[i].has_residual && !i32sc && (!p.res_b || !p.res_c)) return fail(HAWQ_ERR_NULL);
         if (p.bits != 4 && p.bits != 8) return fail(HAWQ_ERR_DTYPE);
         if ((L[i].is_stem || L[i].is_fc) && p.bits != 8) return fail(HAWQ_ERR_DTYPE);
         if (L[i].is_ds) {
@@ -203,7 +218,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         if (!L[i].is_fc)
             for (int k = 0; k < L[i].K; ++k) {
                 if (p.b[k] < 0 || p.c[k] < 1 || p.c[k] > 62) return fail(HAWQ_ERR_RANGE);
-                if (L[i].has_residual && (p.res_b[k] < 0 || p.res_c[k] < 1 || p.res_c[k] > 62)) return fail(HAWQ_ERR_RANGE);
+                if (L[i].has_residual && !i32sc && (p.res_b[k] < 0 || p.res_c[k] < 1 || p.res_c[k] > 62)) return fail(HAWQ_ERR_RANGE);
             }
     }
     const int c_last = L[nl - 1].C;
@@ -235,7 +250,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             memcpy(&host[off[i].b], lp[i].b, 4 * (size_t)L[i].K);
             memcpy(&host[off[i].c], lp[i].c, (size_t)L[i].K);
         }
-        if (L[i].has_residual) {
+        if (L[i].has_residual && lp[i].res_b && lp[i].res_c) {
             memcpy(&host[off[i].rb], lp[i].res_b, 4 * (size_t)L[i].K);
             memcpy(&host[off[i].rc], lp[i].res_c, (size_t)L[i].K);
         }
@@ -273,8 +288,9 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         return (j >= nl || L[j].is_fc) ? 8 : lp[j].bits;
     };
     auto conv_step = [&](int i, int in_t, int in_dt, int in_hi, int res_t, int res_dt, int out_bits, bool signed_out,
-                         bool relu) {
+                         bool relu, bool raw = false) {
         Step st;
+        st.raw = raw;
         st.kind = L[i].is_stem ? STEP_STEM : STEP_CONV;
         st.name = L[i].name; st.layer = i; st.in = in_t; st.res = res_t;
         hawq_conv_desc &d = st.desc;
@@ -283,6 +299,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         d.x_dtype = in_dt; d.w_dtype = lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8;
         d.y_dtype = signed_out ? HAWQ_S8 : (L[i].is_stem ? HAWQ_U8 : act_dt(out_bits));
         d.res_dtype = res_dt; d.relu = relu; d.y_lo = signed_out ? -128 : 0; d.y_hi = signed_out ? 127 : act_hi(out_bits);
+        if (raw) { d.y_dtype = HAWQ_S32; d.relu = 0; d.y_lo = INT32_MIN; d.y_hi = INT32_MAX; }
         d.x_hi = in_hi;
         st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
         st.b = (const int32_t *)(A + off[i].b); st.c = A + off[i].c;
@@ -351,6 +368,44 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             u_dt = act_dt(ob); u_bits = ob;
         }
         int sc = block_in, sc_dt = block_in_dt;
+        if (ds >= 0 && (lp[ds].flags & HAWQ_LAYER_INT32_SHORTCUT)) {
+            // Both branches INT32 (Figure 2).  8-bit operands on both: one launch computes both convolutions and the sum.
+            // Otherwise the raw accumulators go through the workspace and a residual-addition launch.
+            if (lp[last].bits == 8 && lp[ds].bits == 8) {
+                t = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, out_bits, false, true);
+                Step &st = net->steps.back();
+                st.kind = STEP_CONV_DUAL;
+                st.res = block_in;
+                hawq_conv_desc &d = st.desc_s;
+                d = st.desc;
+                d.H = L[ds].H; d.W = L[ds].W; d.C = L[ds].C; d.R = d.S = 1; d.stride_h = d.stride_w = L[ds].stride; d.pad_h = d.pad_w = 0;
+                d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);
+                st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
+                st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
+                st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
+                st.bytes_per_image += (double)L[ds].P * L[ds].Q * L[ds].C;   // a strided 1x1 touches only the sampled pixels
+                st.bytes_fixed += (double)L[ds].K * L[ds].C + 9.0 * L[ds].K;
+            } else {
+                const int r_raw = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, false, false, true);
+                const int m_raw = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, 8, false, false, true);
+                net->steps.back().name += ".acc";
+                Step st;
+                st.kind = STEP_RESADD; st.name = L[last].name; st.layer = last; st.in = m_raw; st.res = r_raw;
+                st.desc.H = L[last].P; st.desc.W = L[last].Q; st.desc.K = L[last].K;
+                st.desc.y_dtype = act_dt(out_bits); st.desc.y_lo = 0; st.desc.y_hi = act_hi(out_bits);
+                st.b = (const int32_t *)(A + off[last].b); st.c = A + off[last].c;
+                st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
+                st.out = new_tensor(L[last].P, L[last].Q, L[last].K, st.desc.y_dtype);
+                st.bytes_per_image = 8.0 * L[last].P * L[last].Q * L[last].K +
+                                     (double)tensor_bytes((int64_t)L[last].P * L[last].Q * L[last].K, st.desc.y_dtype);
+                st.bytes_fixed = 10.0 * L[last].K;
+                net->steps.push_back(st);
+                t = st.out;
+            }
+            in_bits = out_bits;
+            li = j;
+            continue;
+        }
         if (ds >= 0) {
             sc = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, true, false);
             sc_dt = HAWQ_S8;
@@ -455,7 +510,7 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
             ConvArgs a;
             int x_hi;
             const uint8_t *res = st.res >= 0 ? tptr(st.res) : nullptr;
-            const bool raw = st.kind == STEP_FC;
+            const bool raw = st.kind == STEP_FC || st.raw;
             rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
                                 outp, true, a, x_hi);
             if (rc == HAWQ_OK) {
@@ -476,6 +531,20 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
             }
             break;
         }
+        case STEP_CONV_DUAL: {
+            hawq_conv_desc d = st.desc, dsc = st.desc_s;
+            d.N = N; dsc.N = N;
+            ConvArgs a;
+            int x_hi, xs_hi;
+            rc = make_dual_args(&d, in, st.w, st.bias, st.b, st.c, &dsc, tptr(st.res), st.w_s, st.bias_s, st.b_s, st.c_s, outp,
+                                true, a, x_hi, xs_hi);
+            if (rc == HAWQ_OK) rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
+            break;
+        }
+        case STEP_RESADD:
+            rc = launch_residual_add((int64_t)N * st.desc.H * st.desc.W, st.desc.K, HAWQ_S32, HAWQ_S32, st.desc.y_dtype, in, st.b,
+                                     st.c, tptr(st.res), st.b_s, st.c_s, st.desc.y_lo, st.desc.y_hi, outp, stream);
+            break;
         case STEP_MAXPOOL:
             if (st.skip && net->steps[s - 1].fused_pool) break;   // done inside conv1's kernel
             rc = launch_maxpool(N, st.desc.H, st.desc.W, st.desc.C, st.desc.x_dtype, st.desc.y_dtype, in, st.desc.y_lo,

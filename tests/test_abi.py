@@ -86,6 +86,29 @@ def test_conv_argument_validation_on_host(lib):
     assert lib.hawq_status_string(5).decode().lower().startswith("int32")
 
 
+def test_dual_conv_argument_validation_on_host(lib):
+    import paper_2011_10680_amd as hawq
+    P = ctypes.c_void_p(4096)
+    main = dict(N=2, H=8, W=8, C=64, K=128, R=3, S=3)
+    short = dict(N=2, H=15, W=15, C=128, K=128, R=1, S=1, stride_h=2, stride_w=2, pad_h=0, pad_w=0)
+
+    def call(dm, dsc, **ptrs):
+        a = dict(x=P, w=P, bias=P, b=P, c=P, xs=P, ws=P, bias_s=P, b_s=P, c_s=P, y=P)
+        a.update(ptrs)
+        return lib.hawq_conv2d_dual_int(ctypes.byref(dm), a["x"], a["w"], a["bias"], a["b"], a["c"], ctypes.byref(dsc), a["xs"],
+                                        a["ws"], a["bias_s"], a["b_s"], a["c_s"], a["y"], None)
+    assert call(_desc(**main), _desc(**short), xs=None) == 1                      # HAWQ_ERR_NULL
+    assert call(_desc(**main), _desc(**short), b_s=None) == 1                     # both branches are requantised
+    assert call(_desc(**main), _desc(**dict(short, H=17, W=17))) == 2             # output sizes differ -> HAWQ_ERR_SHAPE
+    assert call(_desc(**main), _desc(**dict(short, K=64))) == 2
+    assert call(_desc(**main), _desc(**dict(short, R=3, S=3, H=17, W=17))) == 2   # shortcut must be 1x1
+    assert call(_desc(**main), _desc(**dict(short, w_dtype=hawq.S4))) == 3        # operand widths of one branch must agree
+    assert call(_desc(**dict(main, y_dtype=hawq.S32, y_lo=-5, y_hi=5)), _desc(**short)) == 3
+    assert call(_desc(**dict(main, y_hi=300)), _desc(**short)) == 4
+    assert call(_desc(**main), _desc(**dict(short, C=65536 * 2, x_hi=255))) == 5   # the shortcut's own overflow bound
+    assert call(_desc(**dict(main, N=0)), _desc(**dict(short, N=0))) == 0
+
+
 def test_other_entry_points_validate_on_host(lib):
     P = ctypes.c_void_p(4096)
     assert lib.hawq_gemm_int(4, 0, 64, 0, 1, 4, P, P, P, None, None, 0, 0, 0, P, None) == 2
@@ -115,6 +138,14 @@ def test_net_create_rejects_bad_parameters_before_touching_the_gpu(lib):
     with pytest.raises(hawq.HawqError) as e:
         hawq.HawqNet(18, bad, net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
     assert e.value.status == 3
+    arr_flag = [dict(l) for l in net["layers"]]
+    idx = {l["name"]: i for i, l in enumerate(arr_flag)}
+    arr_flag[idx["layer2.0.ds"]]["int32_shortcut"] = True
+    arr_flag[idx["layer2.0.c2"]]["res_b"] = arr_flag[idx["layer2.0.c2"]]["res_c"] = None   # unused in that form: may be absent ...
+    arr_flag[idx["layer2.1.c2"]]["res_b"] = None                  # ... but not on a block with an identity shortcut
+    with pytest.raises(hawq.HawqError) as e:
+        hawq.HawqNet(18, arr_flag, net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
+    assert e.value.status == 1
     with pytest.raises(hawq.HawqError) as e:                      # wrong layer count
         hawq.HawqNet(18, net["layers"][:-1], net["pool_b"], net["pool_c"], image_hw=64, num_classes=10)
     assert e.value.status == 2
