@@ -21,11 +21,17 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_TOPS = 5033.0     # MI355X dense INT8 MFMA, published (5.0 POP/s)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
+# Transition blocks (the first block of every stage) of the all-INT8 workloads run in the form of the paper's Figure 2: the
+# block's last convolution and the transition convolution both stay INT32 and are rescaled and added in one launch.  The
+# "_stored" variants keep the transition convolution's output as a signed 8-bit tensor value first (same launches wherever
+# the pair can be fused, one more rounding); the networks with 4-bit layers use that form throughout.
 WORKLOADS = {
-    "resnet50_int8_b128": dict(arch=50, batch=128, mixed=False, seed=1003),
-    "resnet18_int8_b64": dict(arch=18, batch=64, mixed=False, seed=1002),
+    "resnet50_int8_b128": dict(arch=50, batch=128, mixed=False, seed=1003, int32_shortcut=True),
+    "resnet18_int8_b64": dict(arch=18, batch=64, mixed=False, seed=1002, int32_shortcut=True),
     "resnet50_mixed_b256": dict(arch=50, batch=256, mixed=True, seed=1004),
     "resnet50_int4_b128": dict(arch=50, batch=128, mixed="all4", seed=1005),
+    "resnet50_int8_b128_stored": dict(arch=50, batch=128, mixed=False, seed=1003),
+    "resnet18_int8_b64_stored": dict(arch=18, batch=64, mixed=False, seed=1002),
 }
 
 
@@ -100,7 +106,7 @@ def main():
         bits = wl.draw_bits(arch, 4000 + arch)
     else:
         bits = None
-    net = wl.make_resnet(arch, seed=wk["seed"], bits=bits)
+    net = wl.make_resnet(arch, seed=wk["seed"], bits=bits, int32_shortcut=wk.get("int32_shortcut", False))
     x = torch.from_numpy(wl.make_image_batch(wk["seed"] + 1, N)).cuda()
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
     ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
@@ -155,7 +161,7 @@ def main():
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
     roof.update(traffic=profiled_traffic(args.workload),
-                kernel="one forward = %d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
+                kernel="one forward = %d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
                 # the matrix-core convolutions alone, from per-launch events (each interval also holds a few
@@ -169,7 +175,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8" if not wk["mixed"] else "int4/int8", "data": "synthetic",
         "config": {"workload": args.workload, "batch": N, "image": "3x224x224 uint8",
-                   "layers_int4": sum(l["bits"] == 4 for l in net["layers"])},
+                   "layers_int4": sum(l["bits"] == 4 for l in net["layers"]),
+                   "transition_blocks": "int32 both branches" if wk.get("int32_shortcut") else "stored int8 shortcut"},
         "tops": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
         "frac_int8_mfma_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / PEAK_INT8_TOPS,
         "sum_kernel_ms": float(step_ms.sum()),

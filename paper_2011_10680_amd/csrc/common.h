@@ -35,6 +35,10 @@ struct ConvArgs {
     const int32_t *bias_s, *b_s;
     const uint8_t *c_s;
     int32_t Hs, Ws, Cs, stride_sh, stride_sw, xs_dt, ws_dt;
+    // mid_s8: the shortcut accumulator is first requantised by (b_s, c_s) and clamped to the signed 8-bit tensor a separate
+    // transition layer would store, and that value enters the sum rescaled by (res_b, res_c) -- the two-launch result
+    // without the tensor's round trip through memory
+    int32_t mid_s8;
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }
@@ -123,6 +127,10 @@ hawq_status launch_conv_direct(const ConvArgs &a, hipStream_t s);   // any valid
 // matrix-core kernel for a block output with a convolution on both branches (ConvArgs::xs set)
 bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi);
 hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s);
+// persistent streaming form of the same for 1x1 main branches: (C, Cs) = (64, 64) or (128, 256), many pixels
+bool conv_pws_dual_shape_ok(int C, int Cs, int K, int64_t M);
+bool conv_pws_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi);
+hawq_status launch_conv_pws_dual(const ConvArgs &a, hipStream_t s);
 // persistent streaming kernel for 1x1 convolutions with C = 64 / 128 (/ 256 with few output channels) and many pixels
 bool conv_pw_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);

@@ -44,7 +44,9 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(const ConvArgs a, cons
                 const int64_t xo = (((int64_t)n * a.Hs + p * a.stride_sh) * a.Ws + q * a.stride_sw) * a.Cs;
                 const int64_t wo = (int64_t)k * a.Cs;
                 for (int c = 0; c < a.Cs; ++c) acc_s += load_elem(a.xs, a.xs_dt, xo + c) * load_elem(a.ws, a.ws_dt, wo + c);
-                v += rq64(acc_s + a.bias_s[k], a.b_s[k], a.c_s[k]);
+                int64_t sc = rq64(acc_s + a.bias_s[k], a.b_s[k], a.c_s[k]);
+                if (a.mid_s8) sc = rq64(clamp64(sc, -128, 127), a.res_b[k], a.res_c[k]);
+                v += sc;
             }
             out[e] = clamp64(v, a.lo, a.hi);
         }

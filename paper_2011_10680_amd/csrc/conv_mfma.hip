@@ -34,9 +34,12 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // DUAL: block output with a convolution on both branches (Section 3.3's residual equation with two INT32 accumulators,
 // Figure 2): after the main convolution's K-steps the same pipeline runs on through the K-steps of the 1x1 shortcut
 // convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds both.
-template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, bool DUAL = false>
+// (DUALM = 1), or with the shortcut accumulator first rounded to the signed 8-bit value a separate transition layer would
+// have stored (DUALM = 2: the bits of the two-launch form without the tensor's round trip; see epilogue_tile_dual).
+template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, int DUALM = 0>
 __global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
+    constexpr bool DUAL = DUALM != 0;
     constexpr int T = WC * WP * 64;
     constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
     constexpr int BKB = INT4 ? 32 : 64;         // bytes of one K-step in memory
@@ -73,7 +76,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         else return lds7;
     };
     __shared__ ChanMain par_m[BC];
-    __shared__ ChanRes par_r[DUAL ? 1 : BC];
+    __shared__ ChanRes par_r[DUALM == 1 ? 1 : BC];
     __shared__ ChanMain par_s[DUAL ? BC : 1];   // the shortcut convolution's staged parameters
     // Per K-step addressing, tabulated once per workgroup: {weight offset, activation tap offset, r | s << 16}.
     // Deriving these in the loop costs each wave some twenty scalar instructions per step, and the one scalar
@@ -321,7 +324,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
-    if constexpr (DUAL) wide = stage_params_dual(a, k0, BC, par_m, par_s);
+    if constexpr (DUAL) wide = stage_params_dual(a, k0, BC, par_m, par_s, DUALM == 2 ? par_r : nullptr);
     else if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
     // the lane's shortcut bytes are fetched now, a whole K loop ahead of their use in the epilogue
     uint32_t resw[TP][TC][4] = {};
@@ -453,7 +456,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             mm[tp] = m0 + wp * (BP / WP) + tp * 32 + rho;
             valid[tp] = mm[tp] < a.M;
         }
-        epilogue_tile_dual<TC, TP>(a, par_m, par_s, mm, valid, k0, chl, accm, acc, wide);
+        epilogue_tile_dual<TC, TP, 0, DUALM == 2>(a, par_m, par_s, par_r, mm, valid, k0, chl, accm, acc, wide);
     } else {
     if (tile_epi) {
         int64_t mm[TP];
@@ -494,6 +497,7 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
 
 bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi) {
     if (a.xs == nullptr || a.res != nullptr || a.b == nullptr) return false;
+    if (a.mid_s8 && (a.res_b == nullptr || a.res_c == nullptr)) return false;
     if (!conv_mfma_eligible(a, x_hi) || is4(a.x_dt)) return false;
     if (a.Cs % 64 != 0 || a.ws_dt != HAWQ_S8) return false;
     if (a.xs_dt == HAWQ_U8 ? xs_hi > 127 : a.xs_dt != HAWQ_S8) return false;
@@ -508,7 +512,10 @@ bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi) {
 hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     const uint32_t n_ctiles = (a.K + 127) / 128, n_mtiles = (a.M + 127) / 128;
-    conv_mfma_kernel<128, 128, 4, 2, false, 4, true><<<n_ctiles * n_mtiles, 512, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
+    // four waves of 64 channels x 64 pixels: two accumulator sets of that size need the register budget of two waves per
+    // SIMD (the eight-wave form would spill inside the K loop, and a reload there waits for every operand in flight)
+    if (a.mid_s8) conv_mfma_kernel<128, 128, 2, 2, false, 4, 2><<<n_ctiles * n_mtiles, 256, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
+    else conv_mfma_kernel<128, 128, 2, 2, false, 4, 1><<<n_ctiles * n_mtiles, 256, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
     return check_launch();
 }
 

@@ -406,6 +406,162 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
 #undef HAWQ_PWS_STEP
 }
 
+// Block output with a convolution on both branches, streaming form: the shared-stage kernel above with the pixels of
+// BOTH 1x1 convolutions in a stage -- KC1 sub-tiles of the main branch's input followed by KC2 of the shortcut's
+// (strided) input -- two weight sets in registers and two accumulators per wave.  MID: the shortcut accumulator is first
+// rounded to the signed 8-bit value a separate transition layer would store (see epilogue_tile_dual).  The transition
+// tensor is never written or read, and one launch replaces two.
+template <int KC1, int KC2, int WPE, bool MID>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE)))
+conv_pws_dual_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
+    constexpr int NS = 4;
+    constexpr int KC = KC1 + KC2;
+    constexpr int STAGE = KC * 2048;                // 32 pixels x (C + Cs) bytes
+    constexpr int DW = KC * 2 / 4;                  // LDS-DMA instructions (1 KB) per wave and stage
+    static_assert(KC % 2 == 0, "stage split");
+    constexpr int S = 1;                            // stores per wave and group
+    constexpr uint32_t kInvalid = 0x80000000u;
+    __shared__ ChanMain par_m[4][32];
+    __shared__ ChanMain par_s[4][32];
+    __shared__ ChanRes par_r[4][32];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs0[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs1[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs2[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t xs3[STAGE];
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = (int)xcd_remap(blockIdx.x, gridDim.x) * 4 + wave;
+    const int ct = g % n_ct, seq = g / n_ct;        // the four waves of a workgroup share `seq` (n_ct is a multiple of 4)
+    const int rho = lane & 31, khalf = lane >> 5;
+    const int k0 = ct * 32;
+
+    int wide = 0;
+    if (khalf == 0) {
+        ChanMain m, r;
+        wide = stage_branch(a.bias, a.b, a.c, k0 + rho, a.K, m) | stage_branch(a.bias_s, a.b_s, a.c_s, k0 + rho, a.K, r);
+        par_m[wave][rho] = m;
+        par_s[wave][rho] = r;
+        ChanRes q = ChanRes{0, 1, 1, 0};
+        if (MID) wide |= stage_res(a.res_b, a.res_c, k0 + rho, a.K, q);
+        par_r[wave][rho] = q;
+    }
+    wide = __any(wide);
+    const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * a.C), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_ws = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws, 0, (int)((int64_t)a.K * a.Cs), 0x00020000);
+    // both weight sets (32 rows x (C + Cs) bytes: exactly one stage) reach the registers through LDS, coalesced
+    v4i A[KC][2];
+    {
+        uint8_t *wst = wave == 0 ? xs0 : (wave == 1 ? xs1 : (wave == 2 ? xs2 : xs3));
+        const int w_row = lane >> 2;
+        const int w_chunk = (lane & 3) ^ ((w_row >> 2) & 3);
+#pragma unroll
+        for (int inst = 0; inst < 2 * KC; ++inst) {
+            const int kc = inst >> 1, h = inst & 1;
+            const int k = k0 + h * 16 + w_row;
+            if (kc < KC1) {
+                const uint32_t off = k < a.K ? (uint32_t)(k * a.C + kc * 64 + w_chunk * 16) : kInvalid;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, (__attribute__((address_space(3))) void *)(wst + inst * 1024), 16,
+                                                         (int)off, 0, 0, 0);
+            } else {
+                const uint32_t off = k < a.K ? (uint32_t)(k * a.Cs + (kc - KC1) * 64 + w_chunk * 16) : kInvalid;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_ws, (__attribute__((address_space(3))) void *)(wst + inst * 1024), 16,
+                                                         (int)off, 0, 0, 0);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int row = hsel * 16 + isel;
+        const int sw = (row >> 2) & 3;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+                A[kc][kk] = *(const v4i *)(wst + kc * 2048 + row * 64 + (((kk * 2 + khalf) ^ sw) << 4));
+        __syncthreads();    // every wave has its weights (and parameters) before the stage buffers are reused
+    }
+    // A wave's fetch instructions of a stage: sub-tile (wave + 4 j) / 2, row half (wave + 4 j) % 2 -- which tensor an
+    // instruction reads is fixed per wave and j, so its descriptor and per-pixel stride are chosen once, here.
+    const int PQ = a.P * a.Q;
+    const int d_row = lane >> 2;
+    const int d_chunk = (lane & 3) ^ ((d_row >> 2) & 3);
+    auto issue = [&](int grp, uint8_t *xs) {
+        const int64_t mbase = (int64_t)grp * 32;
+#pragma unroll
+        for (int j = 0; j < DW; ++j) {
+            const int inst = wave + 4 * j;
+            const int kc = inst >> 1, h = inst & 1;
+            const bool main_branch = kc < KC1;      // wave-uniform
+            const int64_t m = mbase + h * 16 + d_row;
+            uint32_t off = kInvalid;
+            if (grp < n_groups && m < a.M) {
+                if (main_branch) {
+                    off = (uint32_t)m * (uint32_t)a.C + kc * 64 + d_chunk * 16;
+                } else {
+                    const int mi = (int)m;
+                    const int n = mi / PQ, pq = mi - n * PQ;
+                    const int p = pq / a.Q, q = pq - p * a.Q;
+                    off = (uint32_t)(((n * a.Hs + p * a.stride_sh) * a.Ws + q * a.stride_sw) * a.Cs) + (kc - KC1) * 64 + d_chunk * 16;
+                }
+            }
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(main_branch ? a.x : a.xs), 0,
+                main_branch ? (int)((int64_t)a.N * a.H * a.W * a.C) : (int)((int64_t)a.N * a.Hs * a.Ws * a.Cs), 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(xs + inst * 1024), 16, (int)off, 0, 0, 0);
+        }
+    };
+    const bool slow_epilogue = wide || a.y_dt == HAWQ_S4;
+    const int swz = (rho >> 2) & 3;
+    auto compute = [&](int grp, const uint8_t *xs) {
+        v16i acc[1][1], acc2[1][1];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { acc[0][0][i] = 0; acc2[0][0][i] = 0; }
+        const int64_t mm[1] = {(int64_t)grp * 32 + rho};
+        const bool valid[1] = {mm[0] < a.M};
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const uint8_t *sub = xs + kc * 2048 + rho * 64;
+            const v4i b0 = *(const v4i *)(sub + ((khalf ^ swz) << 4));
+            const v4i b1 = *(const v4i *)(sub + (((2 + khalf) ^ swz) << 4));
+            if (kc < KC1) {
+                acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc[0][0], 0, 0, 0);
+                acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[0][0], 0, 0, 0);
+            } else {
+                acc2[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc2[0][0], 0, 0, 0);
+                acc2[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc2[0][0], 0, 0, 0);
+            }
+        }
+        epilogue_tile_dual<1, 1, 2, MID>(a, par_m[wave], par_s[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, acc2, wide);
+        if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    // outstanding-operation counts as in the kernel above, without shortcut loads
+    auto arrive = [&](int it) {
+        constexpr int L = (NS - 2) * DW;
+        if (it == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L) : "memory");
+        else if (it == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + S) : "memory");
+        else if (it == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + 2 * S) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + 3 * S) : "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+    int grp = seq, it = 0;
+    issue(grp, xs0);
+    issue(grp + n_seq, xs1);
+    issue(grp + 2 * n_seq, xs2);
+#define HAWQ_PWSD_STEP(curx, nxtx)                   \
+    arrive(it);                                      \
+    issue(grp + 3 * n_seq, nxtx);                    \
+    compute(grp, curx);                              \
+    grp += n_seq;                                    \
+    ++it;                                            \
+    if (grp >= n_groups) break;
+    while (grp < n_groups) {
+        HAWQ_PWSD_STEP(xs0, xs3)
+        HAWQ_PWSD_STEP(xs1, xs0)
+        HAWQ_PWSD_STEP(xs2, xs1)
+        HAWQ_PWSD_STEP(xs3, xs2)
+    }
+#undef HAWQ_PWSD_STEP
+}
+
 bool conv_pw_eligible(const ConvArgs &a, int x_hi) {
     if (!conv_mfma_eligible(a, x_hi)) return false;
     if (a.R != 1 || a.S != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
@@ -463,6 +619,45 @@ static hawq_status launch_pws(const ConvArgs &a, hipStream_t s) {
     if (a.res != nullptr) conv_pws_kernel<KC, WPE, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
     else conv_pws_kernel<KC, WPE, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
     return check_launch();
+}
+
+bool conv_pws_dual_shape_ok(int C, int Cs, int K, int64_t M) {
+    // (at (256, 512) the stage ring and the weight registers leave one workgroup per CU: the separate launches win)
+    const bool pair = (C == 64 && Cs == 64) || (C == 128 && Cs == 256);
+    return pair && K % 128 == 0 && K >= 256 && M >= 8192;
+}
+
+bool conv_pws_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi) {
+    if (a.xs == nullptr || a.res != nullptr || a.b == nullptr) return false;
+    if (!conv_mfma_eligible(a, x_hi) || is4(a.x_dt)) return false;
+    if (a.R != 1 || a.S != 1 || a.pad_h != 0 || a.pad_w != 0 || a.stride_h != 1 || a.stride_w != 1) return false;
+    if (a.ws_dt != HAWQ_S8 || (a.xs_dt == HAWQ_U8 ? xs_hi > 127 : a.xs_dt != HAWQ_S8)) return false;
+    if (!conv_pws_dual_shape_ok(a.C, a.Cs, a.K, a.M)) return false;
+    if (a.y_dt == HAWQ_S32) return false;
+    if (a.mid_s8 && (a.res_b == nullptr || a.res_c == nullptr)) return false;
+    uintptr_t al = (uintptr_t)a.y | (uintptr_t)a.xs | (uintptr_t)a.ws;
+    if (al & 15) return false;
+    if (((uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.bias_s | (uintptr_t)a.b_s | (uintptr_t)a.res_b) & 3) return false;
+    return true;
+}
+
+template <int KC1, int KC2, int WPE>
+static hawq_status launch_pws_dual(const ConvArgs &a, hipStream_t s) {
+    const int n_ct = a.K / 32;                           // a multiple of 4
+    const int n_groups = (a.M + 31) / 32;
+    int n_seq = (WPE * 4 * 256) / n_ct;
+    if (n_seq < 1) n_seq = 1;
+    if (n_seq > n_groups) n_seq = n_groups;
+    const uint32_t blocks = (uint32_t)(n_seq * (n_ct / 4));
+    if (a.mid_s8) conv_pws_dual_kernel<KC1, KC2, WPE, true><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    else conv_pws_dual_kernel<KC1, KC2, WPE, false><<<blocks, 256, 0, s>>>(a, n_ct, n_seq, n_groups);
+    return check_launch();
+}
+
+hawq_status launch_conv_pws_dual(const ConvArgs &a, hipStream_t s) {
+    if (a.M == 0) return HAWQ_OK;
+    if (a.C == 64) return launch_pws_dual<1, 1, 4>(a, s);
+    return launch_pws_dual<2, 4, 2>(a, s);
 }
 
 hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s) {

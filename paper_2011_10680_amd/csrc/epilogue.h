@@ -200,7 +200,20 @@ __device__ __forceinline__ int stage_branch(const int32_t *bias, const int32_t *
     return wide;
 }
 
-__device__ __forceinline__ int stage_params_dual(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanMain *ps) {
+// The stored-shortcut form's second rescaling { res_b, res_c } of channel k; wide if outside the narrow evaluation's range.
+__device__ __forceinline__ int stage_res(const int32_t *res_b, const uint8_t *res_c, int k, int K, ChanRes &r) {
+    int wide = 0;
+    r = ChanRes{0, 1, 1, 0};
+    if (k < K) {
+        r.rb = res_b[k]; r.rc = res_c[k];
+        if (r.rc > 31 || r.rb >= (1 << 22)) wide = 1;
+        r.rround = (int32_t)(1u << ((r.rc - 1) & 31));
+    }
+    return wide;
+}
+
+// pr != nullptr: also stage res_b / res_c (the shortcut passes through a signed 8-bit value)
+__device__ __forceinline__ int stage_params_dual(const ConvArgs &a, int k0, int n_ch, ChanMain *pm, ChanMain *ps, ChanRes *pr) {
     int wide = 0;
     const int i = threadIdx.x;
     if (i < n_ch) {
@@ -208,6 +221,11 @@ __device__ __forceinline__ int stage_params_dual(const ConvArgs &a, int k0, int 
         wide = stage_branch(a.bias, a.b, a.c, k0 + i, a.K, m) | stage_branch(a.bias_s, a.b_s, a.c_s, k0 + i, a.K, r);
         pm[i] = m;
         ps[i] = r;
+        if (pr != nullptr) {
+            ChanRes q;
+            wide |= stage_res(a.res_b, a.res_c, k0 + i, a.K, q);
+            pr[i] = q;
+        }
     }
     return wide;
 }
@@ -415,15 +433,21 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
 }
 
 // Epilogue of a block output with a convolution on both branches (Section 3.3's residual equation with two INT32
-// accumulators): y = clamp( rq(accm + bias, b, c) + rq(accs + bias_s, b_s, c_s) ), same lane layout and stores as
-// epilogue_tile (plain global stores of the valid pixels; K % 16 == 0).  pm / ps: the two branches' staged parameters.
-template <int TC, int TP>
-__device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const ChanMain *pm, const ChanMain *ps, const int64_t (&m)[TP],
-                                                   const bool (&valid)[TP], int k0, int chl, const v16i (&accm)[TP][TC],
-                                                   const v16i (&accs)[TP][TC], int wide) {
+// accumulators), same lane layout as epilogue_tile, K % 16 == 0.  pm / ps: the two branches' staged parameters.
+//   MID == false:  y = clamp( rq(accm + bias, b, c) + rq(accs + bias_s, b_s, c_s) )
+//   MID == true :  the shortcut accumulator first becomes the signed 8-bit tensor a separate transition layer would have
+//                  stored, sc = clamp(rq(accs + bias_s, b_s, c_s), -128, 127), and enters the sum as rq(sc, res_b, res_c)
+//                  (pr: staged res_b / res_c) -- bit for bit the result of the two-launch form, without the round trip.
+// YMODE 0: plain global stores of the valid pixels; 2: every lane issues a buffer store (invalid pixels out of range).
+template <int TC, int TP, int YMODE = 0, bool MID = false>
+__device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const ChanMain *pm, const ChanMain *ps, const ChanRes *pr,
+                                                   const int64_t (&m)[TP], const bool (&valid)[TP], int k0, int chl,
+                                                   const v16i (&accm)[TP][TC], const v16i (&accs)[TP][TC], int wide) {
     const int y_dt = a.y_dt;
     const bool y4 = is4(y_dt);
     int32_t lo = a.lo, hi = a.hi;
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.y, 0, YMODE == 2 ? (int)tensor_bytes((int64_t)a.M * a.K, y_dt) : 0, 0x00020000);
     if (wide || y_dt == HAWQ_S4) {
         // exact general form: 64-bit products, shifts and clamp
         static_for<0, TC>([&](auto gc) {
@@ -440,7 +464,12 @@ __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const Chan
                     const ChanMain p1 = pm[chl + 16 * g + i], p2 = ps[chl + 16 * g + i];
                     int32_t av = accm[tp][g][i], sv = accs[tp][g][i];
                     asm volatile("" : "+v"(av), "+v"(sv));   // keeps this cold path's products apart from the narrow path's
-                    const int64_t w64 = (((int64_t)av * (int64_t)p1.b + p1.R) >> p1.c) + (((int64_t)sv * (int64_t)p2.b + p2.R) >> p2.c);
+                    int64_t sc = ((int64_t)sv * (int64_t)p2.b + p2.R) >> p2.c;
+                    if (MID) {
+                        const ChanRes p3 = pr[chl + 16 * g + i];
+                        sc = rq64(clamp64(sc, -128, 127), p3.rb, p3.rc);
+                    }
+                    const int64_t w64 = (((int64_t)av * (int64_t)p1.b + p1.R) >> p1.c) + sc;
                     const int32_t y = clamp64(w64, lo, hi);
                     if (y4) ow[i >> 3] |= (uint32_t)(y & 0xf) << (4 * (i & 7));
                     else ow[i >> 2] |= (uint32_t)(y & 0xff) << (8 * (i & 3));
@@ -451,7 +480,8 @@ __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const Chan
         });
         return;
     }
-    asm volatile("" : "+v"(lo), "+v"(hi));
+    int32_t m128 = -128, p127 = 127;
+    asm volatile("" : "+v"(lo), "+v"(hi), "+v"(m128), "+v"(p127));
     static_for<0, TC>([&](auto gc) {
         constexpr int g = decltype(gc)::value;
         const int chg = k0 + chl + 16 * g;
@@ -463,10 +493,17 @@ __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const Chan
             const ChanMain &p2 = ps[chl + 16 * g + i];
             const int32_t bs1 = p1.bs, bs2 = p2.bs;
             const int64_t Rs1 = p1.Rs, Rs2 = p2.Rs;
+            ChanRes p3 = ChanRes{0, 1, 1, 0};
+            if (MID) p3 = pr[chl + 16 * g + i];
 #pragma unroll
             for (int tp = 0; tp < TP; ++tp) {
-                const int32_t v = (int32_t)(((int64_t)accm[tp][g][i] * (int64_t)bs1 + Rs1) >> 32) +
-                                  (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                int32_t sc = (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                if (MID) {
+                    int32_t s8;
+                    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(s8) : "v"(sc), "v"(m128), "v"(p127));
+                    sc = (__mul24(s8, p3.rb) + p3.rround) >> p3.rc;
+                }
+                const int32_t v = (int32_t)(((int64_t)accm[tp][g][i] * (int64_t)bs1 + Rs1) >> 32) + sc;
                 int32_t t;
                 asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(v), "v"(lo), "v"(hi));
                 y[tp][i] = t;
@@ -481,7 +518,12 @@ __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const Chan
                     w0 |= (uint32_t)y[tp][i] << (4 * i);
                     w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
                 }
-                if (valid[tp]) *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+                if (YMODE == 2) {
+                    const uint32_t off = valid[tp] ? (uint32_t)((m[tp] * (int64_t)a.K + chg) >> 1) : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, make_uint2(w0, w1)), yrs, (int)off, 0, 0);
+                } else if (valid[tp]) {
+                    *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+                }
             } else {
                 uint32_t w[4];
 #pragma unroll
@@ -490,7 +532,12 @@ __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const Chan
                     const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
                     w[q] = t0 | t1;
                 }
-                if (valid[tp]) *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+                if (YMODE == 2) {
+                    const uint32_t off = valid[tp] ? (uint32_t)(m[tp] * (int64_t)a.K + chg) : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, yrs, (int)off, 0, 0);
+                } else if (valid[tp]) {
+                    *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+                }
             }
         }
     });

@@ -93,6 +93,11 @@ struct Step {
     const int32_t *bias_s = nullptr, *b_s = nullptr;
     const uint8_t *c_s = nullptr;
     bool raw = false;             // STEP_CONV: store the INT32 accumulator + bias, no requantisation
+    // A transition convolution and the block's last convolution that adds its output (stored-shortcut form): where the
+    // two-convolution kernels apply, the pair runs as one launch at the last convolution's step, with the
+    // transition tensor's rounding done in registers -- same bits, no round trip, and the transition step launches nothing.
+    int pair_last = -1;           // on the transition step: index of the last convolution's step
+    int pair_ds = -1;             // on the last convolution's step: index of the transition step
     const uint8_t *w = nullptr;   // device parameter pointers
     const uint8_t *w_stem = nullptr;      // conv1 only: weights re-tiled for the stem kernel
     const int32_t *bias_stem = nullptr;   //             bias + 128 * sum(w) (input offset correction)
@@ -128,6 +133,8 @@ void assign_slots(hawq_net *net) {
         const Step &st = net->steps[s];
         if (st.in >= 0) T[st.in].last_use = (int)s;
         if (st.res >= 0) T[st.res].last_use = (int)s;
+        // a transition step that is carried out at its block's last convolution reads its input there
+        if (st.pair_ds >= 0 && net->steps[st.pair_ds].in >= 0) T[net->steps[st.pair_ds].in].last_use = (int)s;
     }
     std::vector<int> owner;  // slot -> tensor currently in it (-1 free)
     auto &sb = net->slot_bytes_per_image;
@@ -155,6 +162,14 @@ void assign_slots(hawq_net *net) {
         if (sb[pick] < need) sb[pick] = need;
         t.slot = pick;
     }
+}
+
+// Does the (transition, last convolution) pair whose transition step is `ds_step` run as one launch at batch N?
+bool pair_runs_fused(const hawq_net *net, int N, int ds_step) {
+    const Step &d = net->steps[ds_step];
+    if (d.pair_last < 0 || net->keep) return false;
+    (void)N;
+    return true;   // 8-bit operands on both branches (checked when the plan was made): one of the two-convolution kernels applies
 }
 
 size_t slot_offset(const hawq_net *net, int slot, int N) {
@@ -406,11 +421,17 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             li = j;
             continue;
         }
+        int ds_step = -1;
         if (ds >= 0) {
             sc = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, true, false);
             sc_dt = HAWQ_S8;
+            ds_step = (int)net->steps.size() - 1;
         }
         t = conv_step(last, u, u_dt, act_hi(u_bits), sc, sc_dt, out_bits, false, true);
+        if (ds_step >= 0 && !net->keep && lp[last].bits == 8 && lp[ds].bits == 8) {
+            net->steps[ds_step].pair_last = (int)net->steps.size() - 1;
+            net->steps.back().pair_ds = ds_step;
+        }
         in_bits = out_bits;
         li = j;
     }
@@ -484,6 +505,16 @@ hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, dou
     const Step &st = net->steps[step];
     *macs = st.macs_per_image * N;
     *bytes = st.bytes_per_image * N + st.bytes_fixed;
+    // a transition / last convolution pair that runs as one launch: all the work and the traffic it still needs (both
+    // inputs, both parameter sets, the block output) are reported on the last convolution's step
+    if (st.pair_last >= 0 && pair_runs_fused(net, N, step)) { *macs = 0; *bytes = 0; }
+    if (st.pair_ds >= 0 && pair_runs_fused(net, N, st.pair_ds)) {
+        const Step &d = net->steps[st.pair_ds];
+        const hawq_conv_desc &c = st.desc, &e = d.desc;
+        const double px = (double)c.H * c.W;     // the last convolution has stride 1: as many input as output pixels
+        *macs += d.macs_per_image * N;
+        *bytes = (px * c.C + px * e.C + px * c.K) * N + st.bytes_fixed + d.bytes_fixed;
+    }
     return HAWQ_OK;
 }
 
@@ -495,10 +526,36 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
     if ((uintptr_t)workspace & 255) return HAWQ_ERR_UNSUPPORTED;
     uint8_t *ws = (uint8_t *)workspace;
     auto tptr = [&](int t) -> uint8_t * { return ws + slot_offset(net, net->tensors[t].slot, N); };
+    char deferred[256] = {0};   // transition steps whose work runs with their block's last convolution
+    if (net->steps.size() > sizeof deferred) return HAWQ_ERR_UNSUPPORTED;
     for (size_t s = 0; s < net->steps.size(); ++s) {
         const Step &st = net->steps[s];
         if (ev && hipEventRecord(ev[2 * s], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
         hawq_status rc = HAWQ_OK;
+        if (st.kind == STEP_CONV && (st.pair_last >= 0 || (st.pair_ds >= 0 && deferred[st.pair_ds]))) {
+            const Step &l = st.pair_last >= 0 ? net->steps[st.pair_last] : st;
+            const Step &d = st.pair_last >= 0 ? st : net->steps[st.pair_ds];
+            hawq_conv_desc dm = l.desc, dsc = d.desc;
+            dm.N = N; dsc.N = N;
+            ConvArgs a;
+            int x_hi, xs_hi;
+            rc = make_dual_args(&dm, tptr(l.in), l.w, l.bias, l.b, l.c, &dsc, tptr(d.in), d.w, d.bias, d.b, d.c, tptr(l.out), true,
+                                a, x_hi, xs_hi);
+            if (rc != HAWQ_OK) return rc;
+            a.mid_s8 = 1; a.res_b = l.res_b; a.res_c = l.res_c;
+            if (st.pair_last >= 0) {
+                if (pair_runs_fused(net, N, (int)s) && (conv_pws_dual_eligible(a, x_hi, xs_hi) || conv_mfma_dual_eligible(a, x_hi, xs_hi))) {
+                    deferred[s] = 1;
+                    if (ev && hipEventRecord(ev[2 * s + 1], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+                    continue;
+                }
+            } else {
+                rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
+                if (rc != HAWQ_OK) return rc;
+                if (ev && hipEventRecord(ev[2 * s + 1], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+                continue;
+            }
+        }
         const uint8_t *in = st.in >= 0 ? tptr(st.in) : (const uint8_t *)x;
         uint8_t *outp = st.out >= 0 ? tptr(st.out) : (uint8_t *)logits;
         switch (st.kind) {

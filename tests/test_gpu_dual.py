@@ -176,19 +176,43 @@ def test_network_with_int32_shortcuts(hawq, arch, mixed, N):
     assert np.array_equal(got2, want)
 
 
-def test_full_size_resnet50_with_int32_shortcuts_sampled(hawq):
-    import torch
-    arch, batch, seed = 50, 128, 1003
-    net = wl.make_resnet(arch, seed=seed, int32_shortcut=True)
-    x = wl.make_image_batch(seed + 1, batch)
-    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
-    ws = torch.empty(hn.workspace_bytes(batch), dtype=torch.uint8, device="cuda")
-    logits = torch.empty((batch, 1000), dtype=torch.int32, device="cuda")
-    hn.hawq_forward_resnet(torch.from_numpy(x).cuda(), batch, logits, ws)
-    torch.cuda.synchronize()
-    got = logits.cpu().numpy()
-    sample = [0, 63, 127]
-    want = onet.forward(net, x[sample])
-    for j, i in enumerate(sample):
-        assert np.array_equal(got[i], want[j]), "image %d of the full batch differs from the oracle" % i
-    hn.close()
+# shapes the persistent streaming form serves (many pixels; (C, Cs) = (64, 64) or (128, 256); K a multiple of 128)
+@pytest.mark.parametrize("shape", [(3, 56, 64, 256, 1, 64, 1), (11, 28, 128, 512, 1, 256, 2), (5, 47, 64, 384, 1, 64, 2)])
+def test_streaming_form(hawq, shape):
+    from gpu_util import assert_same
+    N, H, C, K, R, Cs, ss = shape
+    t = _case(sum(shape), N, H, C, K, R, Cs, ss)
+    got, want = _run(hawq, t, hawq.U8, 1, 0, 127)
+    assert_same(got, want, "streaming dual conv %r" % (shape,))
+    assert 0.02 < (want == 0).mean() < 0.9 and (want == 127).mean() < 0.2
+    tw = _case(sum(shape), N, H, C, K, R, Cs, ss, wide=True)
+    got, want2 = _run(hawq, tw, hawq.U8, 1, 0, 127)
+    assert_same(got, want2, "streaming dual conv, wide multipliers %r" % (shape,))
+    assert_same(want2, want, "oracle: scaling numerator and shift together changes nothing")
+    got, want = _run(hawq, t, hawq.U4, 1, 0, 15)
+    assert_same(got, want, "streaming dual conv, packed 4-bit output %r" % (shape,))
+
+
+@pytest.mark.parametrize("int32_sc", [False, True])
+def test_network_batch_that_pairs_transition_and_last_convolution(hawq, int32_sc):
+    """ResNet50 at a batch where stages 1 and 2 have enough pixels for the one-launch form of (transition, last convolution).
+    With stored shortcuts the pair must give the bits of the two separate launches (the network that keeps its activations
+    never pairs them) and of the oracle; wide multipliers on the paired layers take the exact path with the same result."""
+    N = 11
+    net = wl.make_resnet(50, seed=2024, int32_shortcut=int32_sc)
+    x = wl.make_image_batch(5, N)
+    want = onet.forward(net, x)
+    got, _, names = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got, want)
+    got_keep, _, _ = _forward_gpu(hawq, net, x, True)
+    assert np.array_equal(got_keep, want)
+    L = {l["name"]: l for l in net["layers"]}
+    for name, keys in (("layer1.0.ds", ("b", "c")), ("layer2.0.c3", ("b", "c")), ("layer1.0.c3", ("res_b", "res_c"))):
+        if int32_sc and keys[0] == "res_b":
+            continue
+        l = L[name]
+        l[keys[0]] = (l[keys[0]].astype(np.int64) << 15).astype(np.int32)
+        l[keys[1]] = (l[keys[1]].astype(np.int32) + 15).astype(np.uint8)
+    assert np.array_equal(onet.forward(net, x[:2]), want[:2])
+    got, _, _ = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got, want)

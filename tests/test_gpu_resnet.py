@@ -82,15 +82,16 @@ def test_fused_stem_with_wide_parameters_and_odd_sizes(hawq, image_hw, N):
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("arch,batch,mixed,seed", [(18, 64, False, 1002), (50, 128, False, 1003), (50, 256, True, 1004)])
-def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed):
+@pytest.mark.parametrize("arch,batch,mixed,seed,int32_sc", [(18, 64, False, 1002, True), (50, 128, False, 1003, True), (50, 256, True, 1004, False),
+                                                            (18, 64, False, 1002, False), (50, 128, False, 1003, False)])
+def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed, int32_sc):
     """The network configurations at their full batch, in the launch configuration the benchmark times
     (reused workspace slots).  The oracle computes a sample of images one by one (images are independent, so
     a row of the batched logits must equal the single-image result); on top of that: run-to-run identical
     bits, and the same image gives the same logits wherever it sits in the batch."""
     import torch
     bits = wl.draw_bits(arch, 4000 + arch) if mixed else None
-    net = wl.make_resnet(arch, seed=seed, bits=bits)
+    net = wl.make_resnet(arch, seed=seed, bits=bits, int32_shortcut=int32_sc)   # the benchmark's workloads: both transition forms
     x = wl.make_image_batch(seed + 1, batch)
     x[batch - 1] = x[0]                      # duplicate image at the other end of the batch
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
