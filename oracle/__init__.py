@@ -57,6 +57,10 @@ def lib():
         _lib.oracle_residual_add_dyadic.argtypes = [i64, i32] + [ctypes.c_int] * 3 + [vp] * 6 + [i32, i64, i64, vp]
         _lib.oracle_avgpool_int.restype = ctypes.c_int
         _lib.oracle_avgpool_int.argtypes = [i32] * 4 + [ctypes.c_int] * 2 + [vp] * 3 + [i64, i64, vp]
+        _lib.oracle_pool2d_sum_int.restype = ctypes.c_int
+        _lib.oracle_pool2d_sum_int.argtypes = [i32] * 10 + [ctypes.c_int] * 2 + [vp] * 3 + [i64, i64, vp]
+        _lib.oracle_concat_dyadic.restype = ctypes.c_int
+        _lib.oracle_concat_dyadic.argtypes = [i64, i32, vp, vp, vp, vp, vp, ctypes.c_int, i64, i64, vp]
         _lib.oracle_maxpool_int.restype = ctypes.c_int
         _lib.oracle_maxpool_int.argtypes = [i32] * 4 + [ctypes.c_int] * 2 + [vp, i64, i64, vp]
     return _lib
@@ -201,4 +205,36 @@ def maxpool_int(x, *, N, H, W, C, x_dt, y_dt, y_lo, y_hi):
     st = lib().oracle_maxpool_int(N, H, W, C, x_dt, y_dt, _ptr(x), int(y_lo), int(y_hi), _ptr(y))
     if st != OK:
         raise OracleError(st, "oracle_maxpool_int")
+    return y
+
+
+def pool2d_sum_int(x, b, c, *, N, H, W, C, R, S, stride, pad, x_dt, y_dt, y_lo=-(1 << 31), y_hi=(1 << 31) - 1):
+    """Window sum carried in INT32 (raw sums with b = c = None and y_dt = S32), optionally followed by one dyadic
+    rescale and clamp; see ``oracle_pool2d_sum_int``."""
+    x = _c(x, _NP[x_dt]); b = _c(b, np.int32); c = _c(c, np.uint8)
+    assert x.size == nelems_to_bytes(N * H * W * C, x_dt)
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    y = _out(N * P * Q * C, y_dt, (N, P, Q, C))
+    st = lib().oracle_pool2d_sum_int(N, H, W, C, R, S, stride, stride, pad, pad, x_dt, y_dt, _ptr(x), _ptr(b), _ptr(c),
+                                     int(y_lo), int(y_hi), _ptr(y))
+    if st != OK:
+        raise OracleError(st, "oracle_pool2d_sum_int")
+    return y
+
+
+def concat_dyadic(branches, *, n_pixels, y_dt, y_lo, y_hi):
+    """branches: list of (q [n_pixels, K_i], dtype, b [K_i], c [K_i]); returns [n_pixels, sum K_i] (packed for 4-bit)."""
+    n = len(branches)
+    qs = [_c(q, _NP[dt]) for q, dt, _, _ in branches]
+    bs = [_c(b, np.int32) for _, _, b, _ in branches]
+    cs = [_c(c, np.uint8) for _, _, _, c in branches]
+    K = np.array([b.size for b in bs], dtype=np.int32)
+    for q, (_, dt, _, _), k in zip(qs, branches, K):
+        assert q.size == nelems_to_bytes(n_pixels * int(k), dt)
+    dts = (ctypes.c_int * n)(*[dt for _, dt, _, _ in branches])
+    arr = lambda xs: (ctypes.c_void_p * n)(*[x.ctypes.data for x in xs])
+    y = _out(n_pixels * int(K.sum()), y_dt, (n_pixels, int(K.sum())))
+    st = lib().oracle_concat_dyadic(n_pixels, n, _ptr(K), dts, arr(qs), arr(bs), arr(cs), y_dt, int(y_lo), int(y_hi), _ptr(y))
+    if st != OK:
+        raise OracleError(st, "oracle_concat_dyadic")
     return y

@@ -17,7 +17,10 @@
  * example (Appendix G), the batch-norm folding identity (Appendix D), the
  * packed/unpacked encoding invariant, and the paper's Table 1 BOPS totals for
  * the network topology; the two-convolution block output additionally against
- * its composition from the single-convolution and residual-addition routines.  Parity unpinned (paper silent; fixed by the readings
+ * its composition from the single-convolution and residual-addition routines;
+ * the INT32 window-sum pool against the float64 library average pool and exact
+ * rationals, the per-branch concatenation against exact rationals and the
+ * real-valued module output (Appendix E).  Parity unpinned (paper silent; fixed by the readings
  * stated in the design notes): tie-breaking direction of the rounding shift,
  * nibble order of packed 4-bit data, storage precision of the shortcut
  * tensor, the max-pool after the first convolution, the form of the global
@@ -377,5 +380,84 @@ int oracle_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int x_dt, int
                     if (best > y_hi) best = y_hi;
                     store_elem(y, y_dt, (((int64_t)n * P + p) * Q + q) * C + k, best);
                 }
+    return OR_OK;
+}
+
+/* ---- pooling carried in INT32 (Appendix E: the pooling branch of an Inception module works on the INT32
+ * feature map, because pooling 4-bit data loses information).  A window SUM; the divisor of an average
+ * pool (R*S, padding counted, as in the Inception modules) is folded into the dyadic number that follows
+ * -- the one given here, or the concatenation's (no integer division anywhere).
+ *   s[n,p,q,k] = sum over the in-image taps of x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + t, k]   (INT32)
+ *   y = s                              if b == NULL (y_dt must be OR_S32)
+ *   y = clamp(rq(s, b[k], c[k]))       otherwise                                                        */
+int oracle_pool2d_sum_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
+                          int32_t pad_h, int32_t pad_w, int x_dt, int y_dt, const void *x, const int32_t *b, const uint8_t *c,
+                          int64_t y_lo, int64_t y_hi, void *y)
+{
+    if (!x || !y) return OR_ERR_ARG;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0)
+        return OR_ERR_ARG;
+    if ((b == NULL) != (c == NULL)) return OR_ERR_ARG;
+    if (b == NULL && y_dt != OR_S32) return OR_ERR_ARG;
+    if (b != NULL && !type_range_ok(y_dt, y_lo, y_hi)) return OR_ERR_ARG;
+    if ((is4(x_dt) || is4(y_dt)) && (C % 2)) return OR_ERR_ARG;
+    if (H + 2 * pad_h < R || W + 2 * pad_w < S) return OR_ERR_ARG;
+    const int32_t P = (H + 2 * pad_h - R) / stride_h + 1, Q = (W + 2 * pad_w - S) / stride_w + 1;
+    if (is4(y_dt)) memset(y, 0, (size_t)(((int64_t)N * P * Q * C) / 2));
+    int overflow = 0;
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t p = 0; p < P; ++p)
+            for (int32_t q = 0; q < Q; ++q)
+                for (int32_t k = 0; k < C; ++k) {
+                    int64_t sum = 0;
+                    for (int32_t r = 0; r < R; ++r) {
+                        const int32_t ih = p * stride_h - pad_h + r;
+                        if (ih < 0 || ih >= H) continue;
+                        for (int32_t t = 0; t < S; ++t) {
+                            const int32_t iw = q * stride_w - pad_w + t;
+                            if (iw < 0 || iw >= W) continue;
+                            sum += load_elem(x, x_dt, (((int64_t)n * H + ih) * W + iw) * C + k);
+                        }
+                    }
+                    if (sum > INT32_MAX || sum < INT32_MIN) overflow = 1;
+                    int64_t yv = sum;
+                    if (b != NULL) {
+                        yv = oracle_rq(sum, b[k], c[k]);
+                        if (yv < y_lo) yv = y_lo;
+                        if (yv > y_hi) yv = y_hi;
+                    }
+                    store_elem(y, y_dt, (((int64_t)n * P + p) * Q + q) * C + k, yv);
+                }
+    return overflow ? OR_ERR_OVERFLOW : OR_OK;
+}
+
+/* ---- concatenation with one dyadic number per branch (Appendix E: the branches of an Inception module end
+ * at different scales; each is brought to the output scale S_a by its own DN(S_i / S_a), then the channels are
+ * laid side by side):
+ *   y[p, off_i + k] = clamp(rq(q_i[p,k], b_i[k], c_i[k])),   off_i = K_0 + ... + K_(i-1)
+ * q_i: [n_pixels, K_i] of type dt[i] (an INT32 accumulator / pooled sum, or a stored low-bit tensor).      */
+int oracle_concat_dyadic(int64_t n_pixels, int32_t n_branches, const int32_t *K, const int *dt, const void *const *q,
+                         const int32_t *const *b, const uint8_t *const *c, int y_dt, int64_t y_lo, int64_t y_hi, void *y)
+{
+    if (!K || !dt || !q || !b || !c || !y || n_branches <= 0 || n_pixels < 0) return OR_ERR_ARG;
+    if (!type_range_ok(y_dt, y_lo, y_hi)) return OR_ERR_ARG;
+    int64_t Kt = 0;
+    for (int32_t i = 0; i < n_branches; ++i) {
+        if (K[i] <= 0 || !q[i] || !b[i] || !c[i]) return OR_ERR_ARG;
+        if ((is4(dt[i]) || is4(y_dt)) && (K[i] % 2)) return OR_ERR_ARG;
+        Kt += K[i];
+    }
+    if (is4(y_dt)) memset(y, 0, (size_t)((n_pixels * Kt) / 2));
+    int64_t off = 0;
+    for (int32_t i = 0; i < n_branches; ++i) {
+        for (int64_t p = 0; p < n_pixels; ++p)
+            for (int32_t k = 0; k < K[i]; ++k) {
+                int64_t yv = oracle_rq(load_elem(q[i], dt[i], p * K[i] + k), b[i][k], c[i][k]);
+                if (yv < y_lo) yv = y_lo;
+                if (yv > y_hi) yv = y_hi;
+                store_elem(y, y_dt, p * Kt + off + k, yv);
+            }
+        off += K[i];
+    }
     return OR_OK;
 }
