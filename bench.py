@@ -65,6 +65,38 @@ def profiled_traffic(workload):
     return (float(m.group(1)) + float(m.group(2))) * 1e6 if m else None
 
 
+def module_ops(hawq, torch, steps, warmup):
+    """Algorithmic GB/s of hawq_pool2d_sum_int and hawq_concat_dyadic at the size of an Inception 35x35 module, batch 128
+    (synthetic INT32 feature maps resident in HBM; HIP events on the launch stream)."""
+    N, H, Ks = 128, 35, (64, 64, 96, 64)
+    P, C = N * H * H, sum(Ks)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    qs = [torch.randint(-(1 << 20), 1 << 20, (P, K), dtype=torch.int32, device="cuda", generator=g) for K in Ks]
+    bs = [torch.randint(1 << 14, 1 << 15, (K,), dtype=torch.int32, device="cuda", generator=g) for K in Ks]
+    cs = [torch.full((K,), 28, dtype=torch.uint8, device="cuda") for K in Ks]
+    y = torch.empty((P, C), dtype=torch.uint8, device="cuda")
+    br = [(q, hawq.S32, b, c) for q, b, c in zip(qs, bs, cs)]
+    x = torch.randint(0, 1 << 20, (N, H, H, C), dtype=torch.int32, device="cuda", generator=g)
+    yp = torch.empty((N, H, H, C), dtype=torch.int32, device="cuda")
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+    t_cat = timed(lambda: hawq.hawq_concat_dyadic(P, br, hawq.U8, 0, 127, y))
+    t_pool = timed(lambda: hawq.hawq_pool2d_sum_int(N, H, H, C, 3, 3, 1, 1, 1, 1, hawq.S32, hawq.S32, x, None, None, 0, 0, yp))
+    return {"workload": "inception 35x35 module operators, batch 128, %d channels" % C,
+            "concat_dyadic": {"us": t_cat * 1e3, "algorithmic_bytes": P * C * 5, "GBps": P * C * 5 / t_cat / 1e6, "frac_hbm_peak": P * C * 5 / t_cat / 1e6 / PEAK_HBM_GBS},
+            "pool2d_sum_int32": {"us": t_pool * 1e3, "algorithmic_bytes": P * C * 8, "GBps": P * C * 8 / t_pool / 1e6, "frac_hbm_peak": P * C * 8 / t_pool / 1e6 / PEAK_HBM_GBS}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +108,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--module-ops", action="store_true",
+                    help="time the two memory-bound operators of an Inception-style module instead (INT32 3x3 window-sum "
+                         "pool and the concatenation with one dyadic number per branch, 128 x 35 x 35 x 288) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path shards by batch with no exchange; "
@@ -96,6 +131,9 @@ def main():
     import paper_2011_10680_amd as hawq
 
     hawq.load_library()   # fails loudly if libhawq.so is not built: there is no fallback path
+    if args.module_ops:
+        print(json.dumps(module_ops(hawq, torch, args.steps, args.warmup)))
+        return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wk = WORKLOADS[args.workload]

@@ -152,6 +152,37 @@ hawq_status hawq_avgpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t
 hawq_status hawq_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t x_dt, int32_t y_dt, const void *x,
                              int32_t y_lo, int32_t y_hi, void *y, void *stream);
 
+/*
+ * Pooling carried in INT32 -- Appendix E (the pooling branch of an Inception module works on the INT32 feature map).
+ * A window SUM: the divisor of an average pool (R*S with the padding counted, as in the Inception modules) is folded
+ * into the dyadic number that follows -- the one given here or the concatenation's -- so there is no integer division.
+ *   s[n,p,q,k] = sum over the in-image taps of x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + t, k]
+ *   y = s (b == c == NULL, y_dt must be HAWQ_S32)   or   y = clamp(rq(s, b[k], c[k]), y_lo, y_hi)
+ * x [N,H,W,C] HAWQ_S32 | U8 | S8 | U4 | S4;  y [N,P,Q,C].  The caller guarantees that a window's sum fits INT32
+ * (|x| < 2^31 / (R*S) for INT32 input).  x and y must not overlap.
+ */
+hawq_status hawq_pool2d_sum_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S, int32_t stride_h,
+                                int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t x_dt, int32_t y_dt, const void *x,
+                                const int32_t *b, const uint8_t *c, int32_t y_lo, int32_t y_hi, void *y, void *stream);
+
+/*
+ * Concatenation with one dyadic number per branch -- Appendix E: the branches of a module end at different scales
+ * S_i; each is brought to the output scale S_a by its own DN(S_i / S_a), then the channels are laid side by side:
+ *   y[p, off_i + k] = clamp( rq(q_i[p,k], b_i[k], c_i[k]), y_lo, y_hi ),   off_i = K_0 + ... + K_(i-1)
+ * `branches` is a HOST array of n_branches descriptors whose q / b / c are DEVICE pointers: q [n_pixels,K] of `dtype`
+ * (HAWQ_S32 for an accumulator or pooled sum, or a stored low-bit tensor), b int32 [K], c uint8 [K].
+ * y [n_pixels, sum K_i] of y_dt.  With a 4-bit type every K_i must be even.  One launch per branch.
+ */
+typedef struct {
+    const void *q;
+    const int32_t *b;
+    const uint8_t *c;
+    int32_t K;
+    int32_t dtype;
+} hawq_concat_branch;
+hawq_status hawq_concat_dyadic(int64_t n_pixels, int32_t n_branches, const hawq_concat_branch *branches, int32_t y_dt,
+                               int32_t y_lo, int32_t y_hi, void *y, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Whole-network forward (integer-only ResNet18 / ResNet50, Figure 2 and Section 3.3).
  *

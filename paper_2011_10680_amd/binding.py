@@ -34,6 +34,10 @@ class LayerParams(ctypes.Structure):
 LAYER_INT32_SHORTCUT = 1
 
 
+class ConcatBranch(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("b", ctypes.c_void_p), ("c", ctypes.c_void_p), ("K", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
 class LayerInfo(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 24)] + [(n, ctypes.c_int32) for n in
                 ("C", "K", "R", "S", "stride", "pad", "H", "W", "P", "Q", "has_residual", "is_ds")]
@@ -64,6 +68,10 @@ def load_library():
     lib.hawq_avgpool_int.argtypes = [i32] * 6 + [vp] * 3 + [i32, i32, vp, vp]
     lib.hawq_maxpool_int.restype = ctypes.c_int
     lib.hawq_maxpool_int.argtypes = [i32] * 6 + [vp, i32, i32, vp, vp]
+    lib.hawq_pool2d_sum_int.restype = ctypes.c_int
+    lib.hawq_pool2d_sum_int.argtypes = [i32] * 12 + [vp] * 3 + [i32, i32, vp, vp]
+    lib.hawq_concat_dyadic.restype = ctypes.c_int
+    lib.hawq_concat_dyadic.argtypes = [i64, i32, ctypes.POINTER(ConcatBranch), i32, i32, i32, vp, vp]
     lib.hawq_net_num_layers.restype = i32
     lib.hawq_net_num_layers.argtypes = [i32]
     lib.hawq_net_layer_info.restype = ctypes.c_int
@@ -147,6 +155,21 @@ def hawq_avgpool_int(N, H, W, C, x_dt, y_dt, x, b, c, y_lo, y_hi, y, stream=None
 def hawq_maxpool_int(N, H, W, C, x_dt, y_dt, x, y_lo, y_hi, y, stream=None):
     _check(load_library().hawq_maxpool_int(N, H, W, C, x_dt, y_dt, _p(x), y_lo, y_hi, _p(y), _stream(stream)),
            "hawq_maxpool_int")
+
+
+def hawq_pool2d_sum_int(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x_dt, y_dt, x, b, c, y_lo, y_hi, y, stream=None):
+    _check(load_library().hawq_pool2d_sum_int(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x_dt, y_dt, _p(x), _p(b), _p(c),
+                                               y_lo, y_hi, _p(y), _stream(stream)), "hawq_pool2d_sum_int")
+
+
+def hawq_concat_dyadic(n_pixels, branches, y_dt, y_lo, y_hi, y, stream=None):
+    """branches: list of (q, dtype, b, c) device tensors; K is taken from b."""
+    arr = (ConcatBranch * len(branches))()
+    for i, (q, dt, b, c) in enumerate(branches):
+        arr[i].q, arr[i].b, arr[i].c = q.data_ptr(), b.data_ptr(), c.data_ptr()
+        arr[i].K, arr[i].dtype = b.numel(), dt
+    _check(load_library().hawq_concat_dyadic(n_pixels, len(branches), arr, y_dt, y_lo, y_hi, _p(y), _stream(stream)),
+           "hawq_concat_dyadic")
 
 
 def hawq_tune_set_tile(tile):

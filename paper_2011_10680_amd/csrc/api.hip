@@ -224,6 +224,59 @@ hawq_status hawq_maxpool_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t
     return launch_maxpool(N, H, W, C, x_dt, y_dt, x, y_lo, y_hi, y, (hipStream_t)stream);
 }
 
+hawq_status hawq_pool2d_sum_int(int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
+                                int32_t pad_h, int32_t pad_w, int32_t x_dt, int32_t y_dt, const void *x, const int32_t *b,
+                                const uint8_t *c, int32_t y_lo, int32_t y_hi, void *y, void *stream) {
+    if (!x || !y) return HAWQ_ERR_NULL;
+    if ((b == nullptr) != (c == nullptr)) return HAWQ_ERR_NULL;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0)
+        return HAWQ_ERR_SHAPE;
+    if ((int64_t)H + 2 * (int64_t)pad_h < R || (int64_t)W + 2 * (int64_t)pad_w < S) return HAWQ_ERR_SHAPE;
+    int64_t lo, hi;
+    if (!dtype_range(x_dt, lo, hi) || !dtype_range(y_dt, lo, hi)) return HAWQ_ERR_DTYPE;
+    if (b == nullptr) {
+        if (y_dt != HAWQ_S32) return HAWQ_ERR_DTYPE;   // raw window sums are INT32
+        y_lo = INT32_MIN; y_hi = INT32_MAX;
+    } else {
+        hawq_status st = check_clamp(y_dt, y_lo, y_hi);
+        if (st != HAWQ_OK) return st;
+    }
+    if ((is4(x_dt) || is4(y_dt)) && (C & 1)) return HAWQ_ERR_SHAPE;
+    if (x_dt != HAWQ_S32 && (int64_t)R * S * 255 >= kMaxBytes) return HAWQ_ERR_OVERFLOW;
+    const int64_t P = ((int64_t)H + 2 * pad_h - R) / stride_h + 1, Q = ((int64_t)W + 2 * pad_w - S) / stride_w + 1;
+    if (tensor_bytes((int64_t)N * H * W * C, x_dt) >= kMaxBytes || tensor_bytes((int64_t)N * P * Q * C, y_dt) >= kMaxBytes)
+        return HAWQ_ERR_UNSUPPORTED;
+    return launch_pool_sum(N, H, W, C, R, S, stride_h, stride_w, pad_h, pad_w, x_dt, y_dt, x, b, c, y_lo, y_hi, y, (hipStream_t)stream);
+}
+
+hawq_status hawq_concat_dyadic(int64_t n_pixels, int32_t n_branches, const hawq_concat_branch *branches, int32_t y_dt,
+                               int32_t y_lo, int32_t y_hi, void *y, void *stream) {
+    if (!branches || !y) return HAWQ_ERR_NULL;
+    if (n_pixels < 0 || n_branches <= 0) return HAWQ_ERR_SHAPE;
+    hawq_status st = check_clamp(y_dt, y_lo, y_hi);
+    if (st != HAWQ_OK) return st;
+    int64_t Kt = 0;
+    for (int32_t i = 0; i < n_branches; ++i) {
+        const hawq_concat_branch &br = branches[i];
+        if (!br.q || !br.b || !br.c) return HAWQ_ERR_NULL;
+        if (br.K <= 0) return HAWQ_ERR_SHAPE;
+        int64_t lo, hi;
+        if (!dtype_range(br.dtype, lo, hi)) return HAWQ_ERR_DTYPE;
+        if ((is4(br.dtype) || is4(y_dt)) && (br.K & 1)) return HAWQ_ERR_SHAPE;
+        if (tensor_bytes(n_pixels * br.K, br.dtype) >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+        Kt += br.K;
+    }
+    if (Kt > INT32_MAX || tensor_bytes(n_pixels * Kt, y_dt) >= kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    int64_t off = 0;
+    for (int32_t i = 0; i < n_branches; ++i) {
+        const hawq_concat_branch &br = branches[i];
+        st = launch_concat_branch(n_pixels, br.K, (int)Kt, (int)off, br.dtype, y_dt, br.q, br.b, br.c, y_lo, y_hi, y, (hipStream_t)stream);
+        if (st != HAWQ_OK) return st;
+        off += br.K;
+    }
+    return HAWQ_OK;
+}
+
 void hawq_tune_set_tile(int32_t tile) { set_tile_override(tile); }
 
 const char *hawq_status_string(hawq_status s) {

@@ -150,6 +150,11 @@ hawq_status launch_avgpool(int N, int HW, int C, int x_dt, int y_dt, const void 
 hawq_status launch_maxpool(int N, int H, int W, int C, int x_dt, int y_dt, const void *x, int lo, int hi, void *y,
                            hipStream_t s);
 
+hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, int sw, int ph, int pw, int x_dt, int y_dt,
+                            const void *x, const int32_t *b, const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
+hawq_status launch_concat_branch(int64_t n_pixels, int K, int Kt, int off, int q_dt, int y_dt, const void *q, const int32_t *b,
+                                 const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
+
 inline hawq_status check_launch() { return hipGetLastError() == hipSuccess ? HAWQ_OK : HAWQ_ERR_DEVICE; }
 
 }  // namespace hawq

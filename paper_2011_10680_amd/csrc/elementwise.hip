@@ -1,5 +1,5 @@
 // Memory-bound integer kernels: stand-alone dyadic residual add, global average pool,
-// 3x3/2 max pool.  One thread handles 4 consecutive channels of one pixel when the channel
+// 3x3/2 max pool, INT32 window-sum pool, per-branch dyadic concatenation.  One thread handles 4 consecutive channels of one pixel when the channel
 // count allows it (dword loads/stores of packed 8-bit data), else one unit of 1 or 2 channels.
 #include "common.h"
 
@@ -225,6 +225,180 @@ hawq_status launch_maxpool(int N, int H, int W, int C, int x_dt, int y_dt, const
         if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
         maxpool_generic_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, per, H, W, C, P, Q, x_dt, y_dt, x, lo, hi, y);
     }
+    return check_launch();
+}
+
+// ---- window-sum pool carried in INT32 (Appendix E) ----
+// one thread = `per` adjacent channels of one output pixel; the in-image taps are added in INT32 (64-bit while adding,
+// the caller's contract keeps the sum inside INT32), then either stored raw or rescaled by one dyadic number and clamped
+__global__ void __launch_bounds__(256)
+pool_sum_kernel(const int64_t units, const int H, const int W, const int C, const int R, const int S, const int sh, const int sw,
+                const int ph, const int pw, const int P, const int Q, const int per, const int x_dt, const int y_dt,
+                const void *__restrict__ x, const int32_t *__restrict__ b, const uint8_t *__restrict__ c, const int lo, const int hi,
+                void *__restrict__ y) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int cg = C / per;
+    const int k0 = (int)(u % cg) * per;
+    int64_t t = u / cg;
+    const int q = (int)(t % Q); t /= Q;
+    const int p = (int)(t % P);
+    const int n = (int)(t / P);
+    int64_t sum[4] = {0, 0, 0, 0};
+    for (int r = 0; r < R; ++r) {
+        const int ih = p * sh - ph + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int s = 0; s < S; ++s) {
+            const int iw = q * sw - pw + s;
+            if (iw < 0 || iw >= W) continue;
+            const int64_t e = (((int64_t)n * H + ih) * W + iw) * C + k0;
+            if (per == 4 && x_dt == HAWQ_S32) {
+                const v4i v = *(const v4i *)((const int32_t *)x + e);
+                sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+            } else if (per == 4 && x_dt == HAWQ_U8) {
+                const uint32_t v = *(const uint32_t *)((const uint8_t *)x + e);
+                sum[0] += v & 0xff; sum[1] += (v >> 8) & 0xff; sum[2] += (v >> 16) & 0xff; sum[3] += v >> 24;
+            } else {
+                for (int j = 0; j < per; ++j) sum[j] += load_elem(x, x_dt, e + j);
+            }
+        }
+    }
+    int32_t out[4];
+    for (int j = 0; j < per; ++j)
+        out[j] = b != nullptr ? clamp64(rq64((int32_t)sum[j], b[k0 + j], c[k0 + j]), lo, hi) : (int32_t)sum[j];
+    const int64_t o = (((int64_t)n * P + p) * Q + q) * C + k0;
+    if (y_dt == HAWQ_S32) {
+        for (int j = 0; j < per; ++j) ((int32_t *)y)[o + j] = out[j];
+    } else if (is4(y_dt)) {
+        for (int j = 0; j < per; j += 2) ((uint8_t *)y)[(o + j) >> 1] = (uint8_t)((out[j] & 0xf) | ((out[j + 1] & 0xf) << 4));
+    } else if (per == 4) {
+        ((uint32_t *)y)[o >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
+    } else {
+        for (int j = 0; j < per; ++j) ((uint8_t *)y)[o + j] = (uint8_t)out[j];
+    }
+}
+
+// fast path for the Inception pooling branch: 3x3 / stride 1 / pad 1 on INT32 (or unsigned 8-bit) data, C % 4 == 0.  One
+// thread = 4 channels of 8 adjacent output pixels of a row: it adds the three in-image rows of the 10 input columns under
+// them once (column sums, 30 loads) and every output is the sum of three adjacent column sums -- 3.75 loads per output
+// instead of 9, which is what the vector-memory path, not HBM, limits in the general kernel.
+template <bool X32>
+__global__ void __launch_bounds__(256)
+pool_sum3x3_kernel(const int64_t units, const int H, const int W, const int C, const int y_dt, const void *__restrict__ x,
+                   const int32_t *__restrict__ b, const uint8_t *__restrict__ c, const int lo, const int hi, void *__restrict__ y) {
+    constexpr int QT = 8;
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int cg = C / 4, qb = (W + QT - 1) / QT;
+    const int k0 = (int)(u % cg) * 4;
+    int64_t t = u / cg;
+    const int q0 = (int)(t % qb) * QT; t /= qb;
+    const int p = (int)(t % H);
+    const int n = (int)(t / H);
+    int32_t col[QT + 2][4];
+#pragma unroll
+    for (int j = 0; j < QT + 2; ++j) col[j][0] = col[j][1] = col[j][2] = col[j][3] = 0;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int ih = p - 1 + r;
+        if (ih < 0 || ih >= H) continue;
+#pragma unroll
+        for (int j = 0; j < QT + 2; ++j) {
+            const int iw = q0 - 1 + j;
+            if (iw < 0 || iw >= W) continue;
+            const int64_t e = (((int64_t)n * H + ih) * W + iw) * C + k0;
+            if (X32) {
+                const v4i v = *(const v4i *)((const int32_t *)x + e);
+                col[j][0] += v[0]; col[j][1] += v[1]; col[j][2] += v[2]; col[j][3] += v[3];
+            } else {
+                const uint32_t v = *(const uint32_t *)((const uint8_t *)x + e);
+                col[j][0] += v & 0xff; col[j][1] += (v >> 8) & 0xff; col[j][2] += (v >> 16) & 0xff; col[j][3] += v >> 24;
+            }
+        }
+    }
+    int32_t bb[4] = {0, 0, 0, 0}, cc[4] = {1, 1, 1, 1};
+    if (b != nullptr)
+        for (int j = 0; j < 4; ++j) { bb[j] = b[k0 + j]; cc[j] = c[k0 + j]; }
+#pragma unroll
+    for (int i = 0; i < QT; ++i) {
+        if (q0 + i >= W) break;
+        int32_t out[4];
+        for (int j = 0; j < 4; ++j) {
+            const int32_t sum = col[i][j] + col[i + 1][j] + col[i + 2][j];
+            out[j] = b != nullptr ? clamp64(rq64(sum, bb[j], cc[j]), lo, hi) : sum;
+        }
+        const int64_t o = (((int64_t)n * H + p) * W + q0 + i) * C + k0;
+        if (y_dt == HAWQ_S32) *(v4i *)((int32_t *)y + o) = (v4i){out[0], out[1], out[2], out[3]};
+        else if (is4(y_dt)) *(uint16_t *)((uint8_t *)y + (o >> 1)) = (uint16_t)((out[0] & 0xf) | ((out[1] & 0xf) << 4) | ((out[2] & 0xf) << 8) | ((out[3] & 0xf) << 12));
+        else ((uint32_t *)y)[o >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
+    }
+}
+
+hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, int sw, int ph, int pw, int x_dt, int y_dt,
+                            const void *x, const int32_t *b, const uint8_t *c, int lo, int hi, void *y, hipStream_t s) {
+    const int P = (H + 2 * ph - R) / sh + 1, Q = (W + 2 * pw - S) / sw + 1;
+    const bool any4 = is4(x_dt) || is4(y_dt);
+    if (R == 3 && S == 3 && sh == 1 && sw == 1 && ph == 1 && pw == 1 && C % 4 == 0 && (x_dt == HAWQ_S32 || x_dt == HAWQ_U8) &&
+        (((uintptr_t)x | (uintptr_t)y) & 15) == 0) {
+        const int64_t units = (int64_t)N * H * ((W + 7) / 8) * (C / 4);
+        if (units == 0) return HAWQ_OK;
+        const int64_t blocks = (units + 255) / 256;
+        if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+        if (x_dt == HAWQ_S32) pool_sum3x3_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
+        else pool_sum3x3_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
+        return check_launch();
+    }
+    const int per = (C % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15) == 0) ? 4 : (any4 ? 2 : 1);
+    const int64_t units = (int64_t)N * P * Q * (C / per);
+    if (units == 0) return HAWQ_OK;
+    const int64_t blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+    pool_sum_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, R, S, sh, sw, ph, pw, P, Q, per, x_dt, y_dt, x, b, c, lo, hi, y);
+    return check_launch();
+}
+
+// ---- concatenation with one dyadic number per branch (Appendix E) ----
+// one launch per branch: branch elements [n_pixels][K] -> channels off .. off + K of the [n_pixels][Kt] output
+__global__ void __launch_bounds__(256)
+concat_branch_kernel(const int64_t units, const int K, const int Kt, const int off, const int per, const int q_dt, const int y_dt,
+                     const void *__restrict__ q, const int32_t *__restrict__ b, const uint8_t *__restrict__ c, const int lo, const int hi,
+                     void *__restrict__ y) {
+    const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    const int kg = K / per;
+    const int64_t px = u / kg;
+    const int k0 = (int)(u - px * kg) * per;
+    const int64_t e = px * K + k0;
+    int32_t out[4];
+    if (per == 4 && q_dt == HAWQ_S32) {
+        const v4i v = *(const v4i *)((const int32_t *)q + e);
+        for (int j = 0; j < 4; ++j) out[j] = clamp64(rq64(v[j], b[k0 + j], c[k0 + j]), lo, hi);
+    } else {
+        for (int j = 0; j < per; ++j) out[j] = clamp64(rq64(load_elem(q, q_dt, e + j), b[k0 + j], c[k0 + j]), lo, hi);
+    }
+    const int64_t o = px * Kt + off + k0;
+    if (y_dt == HAWQ_S32) {
+        for (int j = 0; j < per; ++j) ((int32_t *)y)[o + j] = out[j];
+    } else if (is4(y_dt)) {
+        for (int j = 0; j < per; j += 2) ((uint8_t *)y)[(o + j) >> 1] = (uint8_t)((out[j] & 0xf) | ((out[j + 1] & 0xf) << 4));
+    } else if (per == 4) {
+        ((uint32_t *)y)[o >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
+    } else {
+        for (int j = 0; j < per; ++j) ((uint8_t *)y)[o + j] = (uint8_t)out[j];
+    }
+}
+
+hawq_status launch_concat_branch(int64_t n_pixels, int K, int Kt, int off, int q_dt, int y_dt, const void *q, const int32_t *b,
+                                 const uint8_t *c, int lo, int hi, void *y, hipStream_t s) {
+    const bool any4 = is4(q_dt) || is4(y_dt);
+    // four channels per thread need dword-aligned output positions (and 16-byte aligned INT32 rows)
+    const bool vec = K % 4 == 0 && Kt % 4 == 0 && off % 4 == 0 && (((uintptr_t)q | (uintptr_t)y) & 15) == 0;
+    const int per = vec ? 4 : (any4 ? 2 : 1);
+    const int64_t units = n_pixels * (K / per);
+    if (units == 0) return HAWQ_OK;
+    const int64_t blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+    concat_branch_kernel<<<(uint32_t)blocks, 256, 0, s>>>(units, K, Kt, off, per, q_dt, y_dt, q, b, c, lo, hi, y);
     return check_launch();
 }
 

@@ -121,6 +121,29 @@ def test_other_entry_points_validate_on_host(lib):
     assert lib.hawq_avgpool_int(1, 7, 7, 64, 0, 0, P, None, P, 0, 127, P, None) == 1
     assert lib.hawq_maxpool_int(1, 8, 8, 63, 0, 2, P, 0, 15, P, None) == 2
     assert lib.hawq_forward_resnet(None, P, 1, P, P, 0, None) == 1
+    pool = lambda *a: lib.hawq_pool2d_sum_int(*a, None)
+    assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 4, None, None, None, 0, 0, P) == 1
+    assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 4, P, P, None, 0, 0, P) == 1          # b without c
+    assert pool(1, 8, 8, 4, 3, 3, 0, 1, 1, 1, 4, 4, P, None, None, 0, 0, P) == 2        # stride 0
+    assert pool(1, 2, 2, 4, 5, 5, 1, 1, 1, 1, 4, 4, P, None, None, 0, 0, P) == 2        # window larger than the padded image
+    assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 0, P, None, None, 0, 127, P) == 3      # raw sums must be INT32
+    assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 0, P, P, P, 0, 300, P) == 4
+    assert pool(1, 8, 8, 3, 3, 3, 1, 1, 1, 1, 2, 0, P, P, P, 0, 127, P) == 2            # odd packed channel count
+    assert pool(0, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 4, P, None, None, 0, 0, P) == 0
+    from paper_2011_10680_amd.binding import ConcatBranch
+    br = (ConcatBranch * 2)()
+    for i, (K, dt) in enumerate(((6, 4), (4, 0))):
+        br[i].q, br[i].b, br[i].c, br[i].K, br[i].dtype = 4096, 4096, 4096, K, dt
+    assert lib.hawq_concat_dyadic(10, 2, None, 0, 0, 127, P, None) == 1
+    assert lib.hawq_concat_dyadic(10, 0, br, 0, 0, 127, P, None) == 2
+    assert lib.hawq_concat_dyadic(0, 2, br, 0, 0, 127, P, None) == 0                     # no pixels: nothing to do
+    assert lib.hawq_concat_dyadic(10, 2, br, 0, 0, 300, P, None) == 4
+    br[1].K = 3
+    assert lib.hawq_concat_dyadic(10, 2, br, 2, 0, 15, P, None) == 2                     # odd branch width, packed output
+    br[1].K = 4; br[1].dtype = 9
+    assert lib.hawq_concat_dyadic(10, 2, br, 0, 0, 127, P, None) == 3
+    br[1].dtype = 0; br[0].b = None
+    assert lib.hawq_concat_dyadic(10, 2, br, 0, 0, 127, P, None) == 1
 
 
 def test_net_create_rejects_bad_parameters_before_touching_the_gpu(lib):
