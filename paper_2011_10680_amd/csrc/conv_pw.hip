@@ -61,6 +61,22 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
         }
         wide = __any(wide);
     }
+    // the same parameters in registers, in the form the register-resident epilogue takes (falls back to the staged ones)
+    LaneParams lp;
+    bool fast;
+    {
+        int T_lo, T_hi;
+        const int bad = lane_form_check<RES>(a, k0 + rho, T_lo, T_hi);   // lanes rho and rho + 32 look at the same channel
+#pragma unroll
+        for (int sft = 1; sft < 32; sft <<= 1) {
+            T_lo = max(T_lo, __shfl_xor(T_lo, sft));
+            T_hi = min(T_hi, __shfl_xor(T_hi, sft));
+        }
+        fast = !__any(bad) && !wide && T_lo <= T_hi && a.y_dt != HAWQ_S4 && !(RES && a.res_dt == HAWQ_S4);
+        lp.T = T_hi;
+        if (RES && fast && khalf == 0) finish_res(a, k0 + rho, T_hi, par_r[wave][rho]);
+        load_lane_params(par_m[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
+    }
 
     // ---- weights of the 32 channels, in MFMA row-operand layout, resident in registers ----
     // row rho of the tile is channel  hsel*16 + isel  (so that a lane ends up with 16 consecutive channels)
@@ -150,9 +166,10 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
 
     // the exact general epilogue issues a data-dependent number of stores; after it everything is drained,
     // which keeps the static operation counts below valid
-    const bool slow_epilogue = wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4);
+    const bool slow_epilogue = !fast && (wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4));
     const int swz = (rho >> 2) & 3;
-    auto process = [&](int grp, const uint8_t *xs, const Stage &st, auto nwaitc) {
+    auto process = [&](auto fastc, int grp, const uint8_t *xs, const Stage &st, auto nwaitc) {
+        constexpr bool FAST = decltype(fastc)::value;
         // wait until at most NWAIT vector-memory operations issued after this stage's loads are outstanding
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(nwaitc)::value) : "memory");
         v16i acc[TP][1];
@@ -161,7 +178,7 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
 #pragma unroll
         for (int tp = 0; tp < TP; ++tp) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tp][0][i] = 0;
+            for (int i = 0; i < 16; ++i) acc[tp][0][i] = FAST ? (RES ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;   // (with a shortcut the registers are short: the bias comes from the staged copy)
             mm[tp] = ((int64_t)grp * TP + tp) * 32 + rho;
             valid[tp] = mm[tp] < a.M;
         }
@@ -186,14 +203,20 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
                 acc[tp][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc[tp][0], 0, 0, 0);
                 acc[tp][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[tp][0], 0, 0, 0);
             }
-        epilogue_tile<1, TP, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
-        if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if constexpr (FAST) {
+            epilogue_lane<TP, RES>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
+        } else {
+            epilogue_tile<1, TP, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
+            if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
     };
 
     // Ring of NS stages: while group i is processed, groups i + n_seq .. i + (NS-1) n_seq are landing
     // (issue() past the last group presents out-of-range offsets and fetches nothing, but still counts).
     // Operations issued after a stage's own loads when its turn comes: the loads of the NS-1 later stages and
     // the stores of the groups processed since -- none for the first group, up to NS-1 groups' worth later.
+    // (the walk exists twice, once per epilogue form, so that neither form's registers burden the other's loop)
+    auto walk = [&](auto fastc) {
     Stage st0, st1, st2;   // separate named objects so that each stays in registers
     using W0 = std::integral_constant<int, (NS - 1) * (D + R)>;
     using W1 = std::integral_constant<int, (NS - 1) * (D + R) + S>;
@@ -202,41 +225,44 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
     if constexpr (NS == 2) {
         issue(grp, xs0, st0);
         issue(grp + n_seq, xs1, st1);
-        process(grp, xs0, st0, W0{});
+        process(fastc, grp, xs0, st0, W0{});
         grp += n_seq;
         while (grp < n_groups) {
             issue(grp + n_seq, xs0, st0);
-            process(grp, xs1, st1, WN{});
+            process(fastc, grp, xs1, st1, WN{});
             grp += n_seq;
             if (grp >= n_groups) break;
             issue(grp + n_seq, xs1, st1);
-            process(grp, xs0, st0, WN{});
+            process(fastc, grp, xs0, st0, WN{});
             grp += n_seq;
         }
     } else {
         issue(grp, xs0, st0);
         issue(grp + n_seq, xs1, st1);
         issue(grp + 2 * n_seq, xs2, st2);
-        process(grp, xs0, st0, W0{});
+        process(fastc, grp, xs0, st0, W0{});
         grp += n_seq;
         if (grp >= n_groups) return;
         issue(grp + 2 * n_seq, xs0, st0);
-        process(grp, xs1, st1, W1{});
+        process(fastc, grp, xs1, st1, W1{});
         grp += n_seq;
         while (grp < n_groups) {
             issue(grp + 2 * n_seq, xs1, st1);
-            process(grp, xs2, st2, WN{});
+            process(fastc, grp, xs2, st2, WN{});
             grp += n_seq;
             if (grp >= n_groups) break;
             issue(grp + 2 * n_seq, xs2, st2);
-            process(grp, xs0, st0, WN{});
+            process(fastc, grp, xs0, st0, WN{});
             grp += n_seq;
             if (grp >= n_groups) break;
             issue(grp + 2 * n_seq, xs0, st0);
-            process(grp, xs1, st1, WN{});
+            process(fastc, grp, xs1, st1, WN{});
             grp += n_seq;
         }
     }
+    };
+    if (fast) walk(std::true_type{});
+    else walk(std::false_type{});
 }
 
 // Variant for C = 256 with many output channels: the four waves of a workgroup work on
@@ -279,6 +305,21 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
             par_r[wave][rho] = r;
         }
         wide = __any(wide);
+    }
+    LaneParams lp;   // the same parameters in registers (see conv_pw_kernel)
+    bool fast;
+    {
+        int T_lo, T_hi;
+        const int bad = lane_form_check<RES>(a, k0 + rho, T_lo, T_hi);   // lanes rho and rho + 32 look at the same channel
+#pragma unroll
+        for (int sft = 1; sft < 32; sft <<= 1) {
+            T_lo = max(T_lo, __shfl_xor(T_lo, sft));
+            T_hi = min(T_hi, __shfl_xor(T_hi, sft));
+        }
+        fast = !__any(bad) && !wide && T_lo <= T_hi && a.y_dt != HAWQ_S4 && !(RES && a.res_dt == HAWQ_S4);
+        lp.T = T_hi;
+        if (RES && fast && khalf == 0) finish_res(a, k0 + rho, T_hi, par_r[wave][rho]);
+        load_lane_params(par_m[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
     }
     const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
     const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * Cb), 0x00020000);
@@ -354,12 +395,13 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
             st.r[0][0][0] = st.r[0][0][1] = st.r[0][0][2] = st.r[0][0][3] = 0;
         }
     };
-    const bool slow_epilogue = wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4);
+    const bool slow_epilogue = !fast && (wide || a.y_dt == HAWQ_S4 || (RES && a.res_dt == HAWQ_S4));
     const int swz = (rho >> 2) & 3;
-    auto compute = [&](int grp, const uint8_t *xs, const Stage &st) {
+    auto compute = [&](auto fastc, int grp, const uint8_t *xs, const Stage &st) {
+        constexpr bool FAST = decltype(fastc)::value;
         v16i acc[1][1];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[0][0][i] = 0;
+        for (int i = 0; i < 16; ++i) acc[0][0][i] = FAST ? (RES ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;
         const int64_t mm[1] = {(int64_t)grp * 32 + rho};
         const bool valid[1] = {mm[0] < a.M};
 #pragma unroll
@@ -370,8 +412,12 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
             acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][0], b0, acc[0][0], 0, 0, 0);
             acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[0][0], 0, 0, 0);
         }
-        epilogue_tile<1, 1, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
-        if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if constexpr (FAST) {
+            epilogue_lane<1, RES>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
+        } else {
+            epilogue_tile<1, 1, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
+            if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
     };
     // Per group and wave, in program order: [wait for the stage] [barrier] DW stage loads + R shortcut loads for
     // the group three ahead, then this group's S stores.  Operations issued after a stage's own loads when its turn
@@ -385,6 +431,7 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
         else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L + 3 * S) : "memory");
         __builtin_amdgcn_s_barrier();
     };
+    auto walk = [&](auto fastc) {   // once per epilogue form (see conv_pw_kernel)
     Stage st0, st1, st2, st3;
     int grp = seq, it = 0;
     issue(grp, xs0, st0);
@@ -393,7 +440,7 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
 #define HAWQ_PWS_STEP(curx, curs, nxtx, nxts)        \
     arrive(it);                                      \
     issue(grp + 3 * n_seq, nxtx, nxts);              \
-    compute(grp, curx, curs);                        \
+    compute(fastc, grp, curx, curs);                 \
     grp += n_seq;                                    \
     ++it;                                            \
     if (grp >= n_groups) break;
@@ -404,6 +451,9 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
         HAWQ_PWS_STEP(xs3, st3, xs2, st2)
     }
 #undef HAWQ_PWS_STEP
+    };
+    if (fast) walk(std::true_type{});
+    else walk(std::false_type{});
 }
 
 // Block output with a convolution on both branches, streaming form: the shared-stage kernel above with the pixels of

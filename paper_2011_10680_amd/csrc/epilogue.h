@@ -158,15 +158,15 @@ __device__ __forceinline__ void epilogue_pixel(const ConvArgs &a, int64_t m, int
 //     res : rc <= 31 and rb < 2^22   -> |r| <= 255 keeps r*rb + 2^(rc-1) inside int32
 // A workgroup (or wave) with any other channel takes the general path: 64-bit shift and clamp.
 // Both paths compute the same exact integer.
-struct ChanMain { int32_t b, c; int64_t R; int32_t bs, pad; int64_t Rs; };
-struct ChanRes { int32_t rb, rc, rround, pad; };
+struct ChanMain { int32_t b, c; int64_t R; int32_t bs, bias; int64_t Rs; };
+struct ChanRes { int32_t rb, rc, rround, rbs; };   // rbs: res_b << (T - res_c) for the register-resident form's wave-uniform T
 
 __device__ __forceinline__ int stage_channel(const ConvArgs &a, int k, ChanMain &m, ChanRes &r) {
     int wide = 0;
     m = ChanMain{0, 1, 0, 0, 0, 0};
     r = ChanRes{0, 1, 1, 0};
     if (k < a.K) {
-        m.b = a.b[k]; m.c = a.c[k];
+        m.b = a.b[k]; m.c = a.c[k]; m.bias = a.bias[k];
         m.R = (int64_t)a.bias[k] * (int64_t)m.b + ((int64_t)1 << (m.c - 1));
         if (m.c > 32 || ((int64_t)m.b >> (m.c - 1)) != 0) {
             wide = 1;
@@ -430,6 +430,128 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
             }
         }
     });
+}
+
+// ------------------------------------------------------------------------------------------
+// Register-resident form for the persistent kernels (a wave keeps its 32 output channels for its whole life, so the
+// parameters of a lane's 16 channels can stay in registers; read from LDS per output they cost as much LDS bandwidth as the
+// epilogue costs VALU time).  Two rewritings make three registers per channel enough:
+//   * the accumulator starts at bias[k] instead of 0, and  rq(t, b, c) = high word of  t * (b << (32-c)) + 2^31 :
+//     the per-channel 64-bit rounding term becomes one constant;
+//   * the shortcut's shifts are aligned to one wave-uniform T:  (r*rb + 2^(rc-1)) >> rc = (r*(rb << (T-rc)) + 2^(T-1)) >> T.
+// Conditions (else the caller takes the LDS-staged exact path with a zero-initialised accumulator): c <= 32,
+// b < 2^(c-1); a T with  max rc <= T <= min(rc + 22 - bits(rb)), T <= 30  exists (|r| <= 255 keeps r*rbs + 2^(T-1) in INT32).
+struct LaneParams {
+    int32_t bias[16];   // start value of the accumulator
+    int32_t bs[16];     // b << (32 - c)
+    int32_t T;          // wave-uniform shift of the shortcut term (its multipliers, shifted to match, live in ChanRes::rbs)
+};
+
+// Whether channel k allows the form, and its bounds for T (the lane that stages channel k calls this; the wave then
+// combines: any bad -> staged form; T_lo = max, T_hi = min over its channels; T_lo <= T_hi needed).
+template <bool RES>
+__device__ __forceinline__ int lane_form_check(const ConvArgs &a, int k, int &T_lo, int &T_hi) {
+    T_lo = 1; T_hi = 30;
+    if (k >= a.K) return 0;
+    const int32_t b = a.b[k], c = a.c[k];
+    const int bad = (c > 32 || ((int64_t)b >> (c - 1)) != 0) ? 1 : 0;
+    if (RES) {
+        const int32_t rb = a.res_b[k], rc = a.res_c[k];
+        const int bits = rb == 0 ? 0 : 32 - __builtin_clz((uint32_t)rb);
+        T_lo = rc;
+        T_hi = rc + 22 - bits < 30 ? rc + 22 - bits : 30;
+    }
+    return bad;
+}
+
+// The lane's 16 channels from the staged copy (pm: the lane's first entry) into registers.
+__device__ __forceinline__ void load_lane_params(const ChanMain *pm, LaneParams &p) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { p.bias[i] = pm[i].bias; p.bs[i] = pm[i].bs; }
+}
+
+// The staged shortcut entry of channel k for shift T (call for every staged channel once T is known).
+__device__ __forceinline__ void finish_res(const ConvArgs &a, int k, int T, ChanRes &r) {
+    r.rbs = k < a.K ? (int32_t)((uint32_t)a.res_b[k] << ((T - a.res_c[k]) & 31)) : 0;
+}
+
+// Epilogue of one lane with register-resident parameters: TP pixels x 16 channels starting at absolute channel chg
+// (a whole group: chg + 16 <= K is not required, chg < K is); acc already holds bias + the products.  8-bit or unsigned
+// 4-bit outputs; shortcut bytes in pre[tp][0..3] (u8 / s8 / u4).  Stores are unconditional buffer stores (invalid pixels
+// out of range), as in epilogue_tile's YMODE 2.
+// pr: the lane's 16 staged shortcut entries -- with a shortcut the shifted multipliers are read from there (one dword per
+// channel instead of the 32 bytes of the staged form) because the registers do not hold a third array.
+template <int TP, bool RES>
+__device__ __forceinline__ void epilogue_lane(const ConvArgs &a, const LaneParams &p, const ChanRes *pr, const int64_t (&m)[TP],
+                                              const bool (&valid)[TP], int chg, const v16i (&acc)[TP][1], const uint32_t (&pre)[TP][1][4]) {
+    const int y_dt = a.y_dt, res_dt = a.res_dt;
+    const bool y4 = is4(y_dt);
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)tensor_bytes((int64_t)a.M * a.K, y_dt), 0x00020000);
+    int32_t lo = a.lo, hi = a.hi;
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    const bool chan_ok = chg < a.K;   // (no early exit: every lane takes part in the same store instructions)
+    int64_t half = (int64_t)1 << 31;
+    asm volatile("" : "+v"(half));   // opaque, in vector registers: with a known addend the compiler splits the 64-bit multiply-add into three multiplies
+    int32_t y[TP][16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        // opaque copy: otherwise the sign extension of the loop-invariant multiplier is hoisted out of the caller's loop as a
+        // 64-bit value (two registers per channel) and the product becomes a 64 x 32 multiply instead of one v_mad_i64_i32
+        int32_t bsv = p.bs[i];
+        asm volatile("" : "+v"(bsv));
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) y[tp][i] = (int32_t)(((int64_t)acc[tp][0][i] * (int64_t)bsv + half) >> 32);
+    }
+    if (RES) {
+        const int32_t rround = (int32_t)(1u << ((p.T - 1) & 31));
+        auto add_res = [&](auto kindc) {
+            constexpr int kind = decltype(kindc)::value;   // 0: u8, 1: s8, 2: u4
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int32_t rbs = pr[i].rbs;
+#pragma unroll
+                for (int tp = 0; tp < TP; ++tp) {
+                    int32_t r;
+                    if (kind == 0) r = (int32_t)__builtin_amdgcn_ubfe(pre[tp][0][i >> 2], 8 * (i & 3), 8);
+                    else if (kind == 1) r = __builtin_amdgcn_sbfe((int32_t)pre[tp][0][i >> 2], 8 * (i & 3), 8);
+                    else r = (int32_t)__builtin_amdgcn_ubfe(pre[tp][0][i >> 3], 4 * (i & 7), 4);
+                    y[tp][i] += (__mul24(r, rbs) + rround) >> p.T;
+                }
+            }
+        };
+        if (res_dt == HAWQ_U8) add_res(std::integral_constant<int, 0>{});
+        else if (res_dt == HAWQ_S8) add_res(std::integral_constant<int, 1>{});
+        else add_res(std::integral_constant<int, 2>{});
+    }
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            int32_t t;
+            asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(y[tp][i]), "v"(lo), "v"(hi));
+            y[tp][i] = t;
+        }
+        if (y4) {
+            uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                w0 |= (uint32_t)y[tp][i] << (4 * i);
+                w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
+            }
+            const uint32_t off = (valid[tp] && chan_ok) ? (uint32_t)((m[tp] * (int64_t)a.K + chg) >> 1) : 0x80000000u;
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, make_uint2(w0, w1)), yrs, (int)off, 0, 0);
+        } else {
+            uint32_t w[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 1], (uint32_t)y[tp][4 * q], 0x0c0c0400u);
+                const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
+                w[q] = t0 | t1;
+            }
+            const uint32_t off = (valid[tp] && chan_ok) ? (uint32_t)(m[tp] * (int64_t)a.K + chg) : 0x80000000u;
+            __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, yrs, (int)off, 0, 0);
+        }
+    }
 }
 
 // Epilogue of a block output with a convolution on both branches (Section 3.3's residual equation with two INT32
