@@ -113,6 +113,36 @@ def test_pointwise_streaming_signed_shortcut_and_wide_parameters(hawq):
     assert_same(got, want3, "saturating parameters")
 
 
+@pytest.mark.parametrize("C,K,spread", [(64, 256, "aligned"), (64, 256, "none"), (256, 1024, "aligned"), (256, 1024, "none"), (128, 96, "edge")])
+def test_pointwise_register_form_shortcut_shift_alignment(hawq, C, K, spread):
+    """The register-resident epilogue brings every channel's shortcut shift to one wave-uniform value: per-channel shifts
+    that just admit one ("aligned": the window of valid values has width 1), that admit none ("none": the staged form
+    must take over), zero and tiny multipliers, full-range unsigned shortcut bytes (0..255)."""
+    from gpu_util import run_conv_gpu, assert_same
+    case = _scale_c(wl.conv_case(seed=C + K + len(spread), N=3, H=56, W=56, C=C, K=K, R=1, S=1, stride=1, pad=0, bits=8,
+                                 with_residual=True), 8)
+    g = np.random.default_rng(K)
+    case["residual"] = g.integers(0, 256, size=case["residual"].shape).astype(np.uint8)
+    if spread == "aligned":      # 15-bit multipliers: valid T in [max rc, min rc + 7] = [17, 17]
+        case["res_c"] = g.integers(10, 18, size=K).astype(np.uint8)
+        case["res_c"][:2] = (10, 17)
+    elif spread == "none":
+        case["res_c"] = g.integers(5, 21, size=K).astype(np.uint8)
+        case["res_c"][:2] = (5, 20)
+    else:
+        case["res_c"] = g.integers(14, 17, size=K).astype(np.uint8)
+        case["res_b"] = case["res_b"].copy()
+        case["res_b"][0] = 0
+        case["res_b"][1] = 1
+        case["res_b"][2] = (1 << 22) - 1       # the largest multiplier the form takes ...
+        case["res_c"][2] = 22
+        case["res_b"][5] = 3
+        case["res_c"][5] = 1                    # ... next to a shift of 1
+    got, want = run_conv_gpu(case, hawq.U8, hawq.S8, hawq.U8, res_dt=hawq.U8, x_hi=127)
+    assert_same(got, want, "%d -> %d, %s" % (C, K, spread))
+    assert 0.05 < (want > 0).mean() and len(np.unique(want)) > 50
+
+
 # few tiles and a long reduction: the tiled kernel's eight-buffer operand ring
 @pytest.mark.parametrize("shape", [
     (8, 14, 14, 256, 256, 3, 3, 1, 1, False),     # 36 K-steps
