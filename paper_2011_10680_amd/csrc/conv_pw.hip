@@ -24,6 +24,7 @@ template <int KC, int TP, int NS, int WPE, bool RES, bool INT4>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE)))
 conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_groups) {
     static_assert(NS == 2 || NS == 3, "ring depth");
+    constexpr bool RREG = WPE <= 3;                 // room for the shortcut multipliers (and the biases) in registers too
     constexpr int BKB = INT4 ? 32 : 64;             // bytes of 64 reduction elements in memory = LDS row length
     constexpr int SUB = 32 * BKB;                   // one 32-pixel x 64-element sub-tile
     constexpr int STAGE = TP * KC * SUB;            // LDS bytes of one group of one wave
@@ -75,7 +76,7 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
         fast = !__any(bad) && !wide && T_lo <= T_hi && a.y_dt != HAWQ_S4 && !(RES && a.res_dt == HAWQ_S4);
         lp.T = T_hi;
         if (RES && fast && khalf == 0) finish_res(a, k0 + rho, T_hi, par_r[wave][rho]);
-        load_lane_params(par_m[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
+        load_lane_params(par_m[wave] + khalf * 16, par_r[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
     }
 
     // ---- weights of the 32 channels, in MFMA row-operand layout, resident in registers ----
@@ -178,7 +179,7 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
 #pragma unroll
         for (int tp = 0; tp < TP; ++tp) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tp][0][i] = FAST ? (RES ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;   // (with a shortcut the registers are short: the bias comes from the staged copy)
+            for (int i = 0; i < 16; ++i) acc[tp][0][i] = FAST ? ((RES && !RREG) ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;   // (four waves per SIMD with a shortcut: the registers are short, the bias comes from the staged copy)
             mm[tp] = ((int64_t)grp * TP + tp) * 32 + rho;
             valid[tp] = mm[tp] < a.M;
         }
@@ -204,7 +205,7 @@ conv_pw_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_gr
                 acc[tp][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[tp][0], 0, 0, 0);
             }
         if constexpr (FAST) {
-            epilogue_lane<TP, RES>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
+            epilogue_lane<TP, RES, RREG>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
         } else {
             epilogue_tile<1, TP, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
             if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -319,7 +320,7 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
         fast = !__any(bad) && !wide && T_lo <= T_hi && a.y_dt != HAWQ_S4 && !(RES && a.res_dt == HAWQ_S4);
         lp.T = T_hi;
         if (RES && fast && khalf == 0) finish_res(a, k0 + rho, T_hi, par_r[wave][rho]);
-        load_lane_params(par_m[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
+        load_lane_params(par_m[wave] + khalf * 16, par_r[wave] + khalf * 16, lp);   // (wave-private slots, written by this wave's own lanes above)
     }
     const int hsel = (rho >> 2) & 1, isel = (rho >> 3) * 4 + (rho & 3);
     const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * Cb), 0x00020000);
@@ -401,7 +402,7 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
         constexpr bool FAST = decltype(fastc)::value;
         v16i acc[1][1];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[0][0][i] = FAST ? (RES ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;
+        for (int i = 0; i < 16; ++i) acc[0][0][i] = FAST ? ((RES && WPE > 2) ? par_m[wave][khalf * 16 + i].bias : lp.bias[i]) : 0;
         const int64_t mm[1] = {(int64_t)grp * 32 + rho};
         const bool valid[1] = {mm[0] < a.M};
 #pragma unroll
@@ -413,7 +414,7 @@ conv_pws_kernel(const ConvArgs a, const int n_ct, const int n_seq, const int n_g
             acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kc][1], b1, acc[0][0], 0, 0, 0);
         }
         if constexpr (FAST) {
-            epilogue_lane<1, RES>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
+            epilogue_lane<1, RES, (WPE <= 2)>(a, lp, par_r[wave] + khalf * 16, mm, valid, k0 + khalf * 16, acc, st.r);
         } else {
             epilogue_tile<1, 1, true, 2>(a, par_m[wave], par_r[wave], mm, valid, k0, khalf * 16, acc, wide, st.r);
             if (slow_epilogue) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -712,7 +713,9 @@ hawq_status launch_conv_pws_dual(const ConvArgs &a, hipStream_t s) {
 
 hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
-    return launch_pws<4, 3>(a, s);   // measured: three waves per SIMD (a fourth spills registers)
+    // measured: three waves per SIMD (a fourth spills registers); with a shortcut two, whose register budget holds all of a
+    // lane's epilogue parameters
+    return a.res != nullptr ? launch_pws<4, 2>(a, s) : launch_pws<4, 3>(a, s);
 }
 
 hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {
@@ -720,7 +723,9 @@ hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s) {
     // measured: at C = 64 one pixel tile per group and four waves per SIMD hide the epilogue's integer work
     // behind the memory stream best; at C = 128 two tiles per group (two waves per SIMD) are as good as any
     // deeper or wider arrangement
-    if (a.C == 64) return launch_pw<1, 1, 2, 4>(a, s);
+    // (with a shortcut: three waves per SIMD, whose register budget holds all of a lane's epilogue parameters -- 52 -> 47.5 us
+    // for 56x56x64 -> 256 at batch 128 against four waves that read bias and shortcut multiplier from LDS)
+    if (a.C == 64) return a.res != nullptr ? launch_pw<1, 1, 2, 3>(a, s) : launch_pw<1, 1, 2, 4>(a, s);
     if (a.C == 256) return launch_pw<4, 1, 2, 2>(a, s);
     return launch_pw<2, 2, 2, 2>(a, s);
 }

@@ -444,7 +444,8 @@ __device__ __forceinline__ void epilogue_tile(const ConvArgs &a, const ChanMain 
 struct LaneParams {
     int32_t bias[16];   // start value of the accumulator
     int32_t bs[16];     // b << (32 - c)
-    int32_t T;          // wave-uniform shift of the shortcut term (its multipliers, shifted to match, live in ChanRes::rbs)
+    int32_t rbs[16];    // res_b << (T - res_c), where the register budget allows (else read from ChanRes::rbs)
+    int32_t T;          // wave-uniform shift of the shortcut term
 };
 
 // Whether channel k allows the form, and its bounds for T (the lane that stages channel k calls this; the wave then
@@ -464,10 +465,10 @@ __device__ __forceinline__ int lane_form_check(const ConvArgs &a, int k, int &T_
     return bad;
 }
 
-// The lane's 16 channels from the staged copy (pm: the lane's first entry) into registers.
-__device__ __forceinline__ void load_lane_params(const ChanMain *pm, LaneParams &p) {
+// The lane's 16 channels from the staged copy (pm / pr: the lane's first entries) into registers.
+__device__ __forceinline__ void load_lane_params(const ChanMain *pm, const ChanRes *pr, LaneParams &p) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { p.bias[i] = pm[i].bias; p.bs[i] = pm[i].bs; }
+    for (int i = 0; i < 16; ++i) { p.bias[i] = pm[i].bias; p.bs[i] = pm[i].bs; p.rbs[i] = pr[i].rbs; }
 }
 
 // The staged shortcut entry of channel k for shift T (call for every staged channel once T is known).
@@ -481,7 +482,8 @@ __device__ __forceinline__ void finish_res(const ConvArgs &a, int k, int T, Chan
 // out of range), as in epilogue_tile's YMODE 2.
 // pr: the lane's 16 staged shortcut entries -- with a shortcut the shifted multipliers are read from there (one dword per
 // channel instead of the 32 bytes of the staged form) because the registers do not hold a third array.
-template <int TP, bool RES>
+// RREG: the shifted shortcut multipliers are taken from p.rbs instead.
+template <int TP, bool RES, bool RREG = false>
 __device__ __forceinline__ void epilogue_lane(const ConvArgs &a, const LaneParams &p, const ChanRes *pr, const int64_t (&m)[TP],
                                               const bool (&valid)[TP], int chg, const v16i (&acc)[TP][1], const uint32_t (&pre)[TP][1][4]) {
     const int y_dt = a.y_dt, res_dt = a.res_dt;
@@ -508,7 +510,7 @@ __device__ __forceinline__ void epilogue_lane(const ConvArgs &a, const LaneParam
             constexpr int kind = decltype(kindc)::value;   // 0: u8, 1: s8, 2: u4
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int32_t rbs = pr[i].rbs;
+                const int32_t rbs = RREG ? p.rbs[i] : pr[i].rbs;
 #pragma unroll
                 for (int tp = 0; tp < TP; ++tp) {
                     int32_t r;
