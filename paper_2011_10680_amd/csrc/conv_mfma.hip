@@ -524,7 +524,7 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s, bool de
     const uint32_t n_ctiles = (a.K + BC - 1) / BC;
     const uint32_t n_mtiles = (a.M + BP - 1) / BP;
     const uint32_t nblocks = n_ctiles * n_mtiles;
-    if constexpr (BC == 128 && BP == 128 && WC == 4) {
+    if constexpr ((BC == 128 && BP == 128 && WC == 4) || (BC == 64 && BP == 64)) {
         if (deep && !is4(a.x_dt)) {
             conv_mfma_kernel<BC, BP, WC, WP, false, 8><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
             return check_launch();
@@ -569,7 +569,9 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
         return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16);
     }
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
-    return launch_cfg<64, 64, 2, 2>(a, vec, s);
+    // a few small tiles with a long reduction (the fully connected layer: 32 tiles x 32 K-steps at batch 128) advance one
+    // memory latency per ring depth: the ring of eight there too
+    return launch_cfg<64, 64, 2, 2>(a, vec, s, (int64_t)((a.K + 63) / 64) * ((a.M + 63) / 64) <= 512 && a.R * a.S * (a.C / 64) >= 16);
 }
 
 }  // namespace hawq
