@@ -31,10 +31,10 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
 // shapes live on occupancy).
 // NBUF: LDS buffers in the operand ring (4, or 8 for the LDS-DMA path when one workgroup has a CU to itself)
-// DUAL: block output with a convolution on both branches (Section 3.3's residual equation with two INT32 accumulators,
-// Figure 2): after the main convolution's K-steps the same pipeline runs on through the K-steps of the 1x1 shortcut
-// convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds both.
-// (DUALM = 1), or with the shortcut accumulator first rounded to the signed 8-bit value a separate transition layer would
+// DUALM != 0: block output with a convolution on both branches (Section 3.3's residual equation with two INT32
+// accumulators, Figure 2): after the main convolution's K-steps the same pipeline runs on through the K-steps of the 1x1
+// shortcut convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds
+// both (DUALM = 1) -- or first rounds the shortcut accumulator to the signed 8-bit value a separate transition layer would
 // have stored (DUALM = 2: the bits of the two-launch form without the tensor's round trip; see epilogue_tile_dual).
 template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, int DUALM = 0>
 __global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))

@@ -4,8 +4,9 @@
 // convolution, the first reducing 1x1) do a handful of MFMAs per output tile and are bound by HBM
 // traffic and by the integer epilogue.  A tile-per-workgroup kernel spends its life in start-up
 // latency there.  Here a wave is persistent instead: it keeps the weights of its 32 output channels in
-// registers (they are only C/8 registers per lane) and its channels' requantisation parameters in a
-// wave-private LDS slot, then walks over pixel tiles with the next tiles' activations and shortcut
+// registers (they are only C/8 registers per lane) and its channels' requantisation parameters in
+// registers too (epilogue_lane; a wave-private LDS slot holds the staged copy for parameters outside
+// that form's range), then walks over pixel tiles with the next tiles' activations and shortcut
 // bytes already in flight while the current tile is multiplied, requantised and stored.  No
 // workgroup barrier.
 //
