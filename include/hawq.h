@@ -191,7 +191,10 @@ hawq_status hawq_concat_dyadic(int64_t n_pixels, int32_t n_branches, const hawq_
  * (Section 3.4: one bit width per layer for weights and activations): a tensor is stored at the
  * width of the convolution that reads it (8-bit: 0..127, 4-bit: 0..15, packed); ds shares c1's
  * width and reads the same stored block input; a ds output is signed 8-bit; conv1, the pooled
- * vector and fc are 8-bit (Appendix H).
+ * vector and fc are 8-bit (Appendix H).  A network that does not keep its activations may hold a
+ * 4-bit tensor in an 8-bit container (values 0..15) and the weights of the 4-bit layers that read it
+ * expanded to bytes, where the packed form would be slower (there is no 4-bit matrix instruction);
+ * the integers are the same, hawq_net_step_output reports the container type.
  * ------------------------------------------------------------------------------------------- */
 typedef struct hawq_net hawq_net;
 

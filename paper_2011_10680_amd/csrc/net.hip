@@ -123,7 +123,6 @@ struct hawq_net {
 
 namespace {
 
-int act_dt(int bits) { return bits == 8 ? HAWQ_U8 : HAWQ_U4; }
 int act_hi(int bits) { return bits == 8 ? 127 : 15; }
 
 // Assign workspace slots: a tensor's slot is free again after its last reader has run.
@@ -240,6 +239,36 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     for (int k = 0; k < c_last; ++k)
         if (pool_b[k] < 0 || pool_c[k] < 1 || pool_c[k] > 62) return fail(HAWQ_ERR_RANGE);
 
+    // ---- 4-bit layers that run in expanded form ----
+    // There is no 4-bit matrix instruction: a 4-bit layer saves bytes, not multiply-accumulates, and the streaming kernels
+    // (1x1 with few input channels, the 64-channel 3x3) are the ones that profit.  Everywhere else the network keeps a
+    // 4-bit layer's input in an 8-bit container (values 0..15, written so by the producer's epilogue) and its weights expanded
+    // to INT8 in the arena, and the layer runs on the INT8 kernels at INT8 speed -- same integers, other storage.  A block's
+    // transition layer and first convolution read the same tensor and go together; in a block with a transition layer
+    // the last convolution and the transition layer are expanded so that they can run as one launch.  With kept
+    // activations every tensor stays in the documented packed form.
+    std::vector<char> expand(nl, 0);
+    if (!net->keep) {
+        auto packed_pays = [&](const LayerShape &l) {
+            const bool pw = l.R == 1 && l.S == 1 && (l.C == 64 || l.C == 128 || (l.C == 256 && l.K <= 128));
+            const bool c64 = l.R == 3 && l.S == 3 && l.C == 64 && l.K == 64 && l.stride == 1 && l.pad == 1;
+            return pw || c64;
+        };
+        for (int i = 0; i < nl; ++i)
+            if (lp[i].bits == 4 && !L[i].is_stem && !L[i].is_fc) expand[i] = !packed_pays(L[i]);
+        for (int i = 0; i < nl; ++i) {
+            if (!L[i].is_ds || lp[i].bits != 4) continue;
+            int c1 = i, last = i;
+            while (c1 >= 0 && !(L[c1].is_c1 && L[c1].block == L[i].block)) --c1;
+            while (last >= 0 && !(L[last].has_residual && L[last].block == L[i].block)) --last;
+            expand[i] = 1;
+            if (c1 >= 0) expand[c1] = 1;                              // (same width as the transition layer: validated above)
+            if (last >= 0 && lp[last].bits == 4) expand[last] = 1;
+        }
+    }
+    auto is8 = [&](int i) { return lp[i].bits == 8 || expand[i]; };      // operands in 8-bit form
+    auto cont_dt = [&](int i) { return is8(i) ? HAWQ_U8 : HAWQ_U4; };     // container of the tensor layer i reads
+
     // ---- parameter arena layout ----
     struct Off { size_t w, bias, b, c, rb, rc; };
     std::vector<Off> off(nl);
@@ -247,7 +276,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto take = [&](size_t bytes) { size_t o = total; total = align_up(total + bytes, 256); return o; };
     for (int i = 0; i < nl; ++i) {
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
-        off[i].w = take((size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        off[i].w = take((size_t)tensor_bytes(nw, is8(i) ? HAWQ_S8 : HAWQ_S4));
         off[i].bias = take(4 * (size_t)L[i].K);
         off[i].b = take(4 * (size_t)L[i].K);
         off[i].c = take((size_t)L[i].K);
@@ -259,7 +288,16 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     std::vector<uint8_t> host(total, 0);
     for (int i = 0; i < nl; ++i) {
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
-        memcpy(&host[off[i].w], lp[i].w, (size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        if (lp[i].bits == 4 && expand[i]) {   // nibbles -> sign-extended bytes (even element in the low nibble)
+            const uint8_t *src = (const uint8_t *)lp[i].w;
+            int8_t *dst = (int8_t *)&host[off[i].w];
+            for (int64_t e = 0; e < nw; ++e) {
+                const int v = (src[e >> 1] >> (4 * (e & 1))) & 0xF;
+                dst[e] = (int8_t)(v >= 8 ? v - 16 : v);
+            }
+        } else {
+            memcpy(&host[off[i].w], lp[i].w, (size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        }
         memcpy(&host[off[i].bias], lp[i].bias, 4 * (size_t)L[i].K);
         if (!L[i].is_fc) {
             memcpy(&host[off[i].b], lp[i].b, 4 * (size_t)L[i].K);
@@ -297,12 +335,14 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         return (int)net->tensors.size() - 1;
     };
     // bit width of the conv that reads the tensor produced after layer i's block / stem
-    auto reader_bits_after = [&](int i) {
+    auto reader_after = [&](int i) {   // index of that layer, -1 for the pool / fc (8-bit)
         int j = i + 1;
         while (j < nl && L[j].is_ds) ++j;
-        return (j >= nl || L[j].is_fc) ? 8 : lp[j].bits;
+        return (j >= nl || L[j].is_fc) ? -1 : j;
     };
-    auto conv_step = [&](int i, int in_t, int in_dt, int in_hi, int res_t, int res_dt, int out_bits, bool signed_out,
+    auto reader_bits_after = [&](int i) { const int j = reader_after(i); return j < 0 ? 8 : lp[j].bits; };
+    auto reader_dt_after = [&](int i) { const int j = reader_after(i); return j < 0 ? (int)HAWQ_U8 : cont_dt(j); };
+    auto conv_step = [&](int i, int in_t, int in_dt, int in_hi, int res_t, int res_dt, int out_bits, int out_dt, bool signed_out,
                          bool relu, bool raw = false) {
         Step st;
         st.raw = raw;
@@ -311,8 +351,8 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         hawq_conv_desc &d = st.desc;
         d.N = 1; d.H = L[i].H; d.W = L[i].W; d.C = L[i].C; d.K = L[i].K; d.R = L[i].R; d.S = L[i].S;
         d.stride_h = d.stride_w = L[i].stride; d.pad_h = d.pad_w = L[i].pad;
-        d.x_dtype = in_dt; d.w_dtype = lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8;
-        d.y_dtype = signed_out ? HAWQ_S8 : (L[i].is_stem ? HAWQ_U8 : act_dt(out_bits));
+        d.x_dtype = in_dt; d.w_dtype = is8(i) ? HAWQ_S8 : HAWQ_S4;
+        d.y_dtype = signed_out ? HAWQ_S8 : (L[i].is_stem ? (int)HAWQ_U8 : out_dt);
         d.res_dtype = res_dt; d.relu = relu; d.y_lo = signed_out ? -128 : 0; d.y_hi = signed_out ? 127 : act_hi(out_bits);
         if (raw) { d.y_dtype = HAWQ_S32; d.relu = 0; d.y_lo = INT32_MIN; d.y_hi = INT32_MAX; }
         d.x_hi = in_hi;
@@ -334,17 +374,18 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
 
     int li = 0;
     int stage_bits = reader_bits_after(0);
-    int t = conv_step(0, -1, HAWQ_U8, 255, -1, HAWQ_U8, stage_bits, false, true);
+    const int stage_dt = reader_dt_after(0);
+    int t = conv_step(0, -1, HAWQ_U8, 255, -1, HAWQ_U8, stage_bits, HAWQ_U8, false, true);
     net->steps[0].w_stem = A + off_ws;
     net->steps[0].bias_stem = (const int32_t *)(A + off_bs);
     {
         Step st;
         st.kind = STEP_MAXPOOL; st.name = "pool"; st.in = t;
         const int P = conv_out(L[0].P, 3, 2, 1);
-        st.desc.H = L[0].P; st.desc.W = L[0].Q; st.desc.C = 64; st.desc.x_dtype = HAWQ_U8; st.desc.y_dtype = act_dt(stage_bits);
+        st.desc.H = L[0].P; st.desc.W = L[0].Q; st.desc.C = 64; st.desc.x_dtype = HAWQ_U8; st.desc.y_dtype = stage_dt;
         st.desc.y_lo = 0; st.desc.y_hi = act_hi(stage_bits);
-        st.out = new_tensor(P, P, 64, act_dt(stage_bits));
-        st.bytes_per_image = (double)L[0].P * L[0].Q * 64 + (double)tensor_bytes((int64_t)P * P * 64, act_dt(stage_bits));
+        st.out = new_tensor(P, P, 64, stage_dt);
+        st.bytes_per_image = (double)L[0].P * L[0].Q * 64 + (double)tensor_bytes((int64_t)P * P * 64, stage_dt);
         // Unless every activation must be kept for inspection, conv1 and the pool run as one kernel and the
         // conv1 tensor is never materialised: it needs no workspace and the pool step launches nothing.
         if (!net->keep && image_hw % 4 == 0) {
@@ -353,7 +394,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             Step &c1 = net->steps[0];
             c1.fused_pool = true;
             net->tensors[c1.out].elems_per_image = 0;
-            c1.bytes_per_image = (double)image_hw * image_hw * 3 + (double)tensor_bytes((int64_t)P * P * 64, act_dt(stage_bits));
+            c1.bytes_per_image = (double)image_hw * image_hw * 3 + (double)tensor_bytes((int64_t)P * P * 64, stage_dt);
         }
         net->steps.push_back(st);
         t = st.out;
@@ -372,42 +413,42 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             else mids.push_back(j);
         }
         if (lp[mids[0]].bits != in_bits) return fail(HAWQ_ERR_DTYPE);  // cannot happen: in_bits derives from it
-        const int out_bits = reader_bits_after(j - 1);
-        const int block_in = t, block_in_dt = act_dt(in_bits);
+        const int out_bits = reader_bits_after(j - 1), out_dt = reader_dt_after(j - 1);
+        const int block_in = t, block_in_dt = cont_dt(mids[0]);
         int u = block_in, u_dt = block_in_dt, u_bits = in_bits;
         std::vector<int> chain = mids;
         chain.push_back(last);
         for (size_t q = 0; q < mids.size(); ++q) {
             const int ob = lp[chain[q + 1]].bits;
-            u = conv_step(mids[q], u, u_dt, act_hi(u_bits), -1, HAWQ_U8, ob, false, true);
-            u_dt = act_dt(ob); u_bits = ob;
+            u = conv_step(mids[q], u, u_dt, act_hi(u_bits), -1, HAWQ_U8, ob, cont_dt(chain[q + 1]), false, true);
+            u_dt = cont_dt(chain[q + 1]); u_bits = ob;
         }
         int sc = block_in, sc_dt = block_in_dt;
         if (ds >= 0 && (lp[ds].flags & HAWQ_LAYER_INT32_SHORTCUT)) {
             // Both branches INT32 (Figure 2).  8-bit operands on both: one launch computes both convolutions and the sum.
             // Otherwise the raw accumulators go through the workspace and a residual-addition launch.
-            if (lp[last].bits == 8 && lp[ds].bits == 8) {
-                t = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, out_bits, false, true);
+            if (is8(last) && is8(ds)) {
+                t = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, out_bits, out_dt, false, true);
                 Step &st = net->steps.back();
                 st.kind = STEP_CONV_DUAL;
                 st.res = block_in;
                 hawq_conv_desc &d = st.desc_s;
                 d = st.desc;
                 d.H = L[ds].H; d.W = L[ds].W; d.C = L[ds].C; d.R = d.S = 1; d.stride_h = d.stride_w = L[ds].stride; d.pad_h = d.pad_w = 0;
-                d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);
+                d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);   // (8-bit form: block_in_dt is HAWQ_U8)
                 st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
                 st.bytes_per_image += (double)L[ds].P * L[ds].Q * L[ds].C;   // a strided 1x1 touches only the sampled pixels
                 st.bytes_fixed += (double)L[ds].K * L[ds].C + 9.0 * L[ds].K;
             } else {
-                const int r_raw = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, false, false, true);
-                const int m_raw = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, 8, false, false, true);
+                const int r_raw = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, HAWQ_U8, false, false, true);
+                const int m_raw = conv_step(last, u, u_dt, act_hi(u_bits), -1, HAWQ_U8, 8, HAWQ_U8, false, false, true);
                 net->steps.back().name += ".acc";
                 Step st;
                 st.kind = STEP_RESADD; st.name = L[last].name; st.layer = last; st.in = m_raw; st.res = r_raw;
                 st.desc.H = L[last].P; st.desc.W = L[last].Q; st.desc.K = L[last].K;
-                st.desc.y_dtype = act_dt(out_bits); st.desc.y_lo = 0; st.desc.y_hi = act_hi(out_bits);
+                st.desc.y_dtype = out_dt; st.desc.y_lo = 0; st.desc.y_hi = act_hi(out_bits);
                 st.b = (const int32_t *)(A + off[last].b); st.c = A + off[last].c;
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.out = new_tensor(L[last].P, L[last].Q, L[last].K, st.desc.y_dtype);
@@ -423,12 +464,12 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         }
         int ds_step = -1;
         if (ds >= 0) {
-            sc = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, true, false);
+            sc = conv_step(ds, block_in, block_in_dt, act_hi(in_bits), -1, HAWQ_U8, 8, HAWQ_S8, true, false);
             sc_dt = HAWQ_S8;
             ds_step = (int)net->steps.size() - 1;
         }
-        t = conv_step(last, u, u_dt, act_hi(u_bits), sc, sc_dt, out_bits, false, true);
-        if (ds_step >= 0 && !net->keep && lp[last].bits == 8 && lp[ds].bits == 8) {
+        t = conv_step(last, u, u_dt, act_hi(u_bits), sc, sc_dt, out_bits, out_dt, false, true);
+        if (ds_step >= 0 && !net->keep && is8(last) && is8(ds)) {
             net->steps[ds_step].pair_last = (int)net->steps.size() - 1;
             net->steps.back().pair_ds = ds_step;
         }
