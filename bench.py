@@ -65,6 +65,42 @@ def profiled_traffic(workload):
     return (float(m.group(1)) + float(m.group(2))) * 1e6 if m else None
 
 
+def conv_sweep(hawq, torch, wl, np):
+    """Single-layer configurations: the 56x56x64 3x3 layer (batch 1 as specified, batch 128 as a throughput companion) and
+    the ResNet18-shaped 3x3 / strided / 1x1 sweep in INT4 and in INT8 (batch 8 as specified, and batch 128), seeded inputs
+    resident in HBM, median of 20 HIP-event timed launches after 5 warm-ups.  TOPS = 2 N P Q K R S C / t (logical MACs)."""
+    def run(N, H, W, C, K, R, S, stride, pad, bits, seed):
+        case = wl.conv_case(seed=seed, N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=bits)
+        x_dt, w_dt = (hawq.U8, hawq.S8) if bits == 8 else (hawq.U4, hawq.S4)
+        P, Q = case["P"], case["Q"]
+        d = hawq.ConvDesc(N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride_h=stride, stride_w=stride, pad_h=pad, pad_w=pad, x_dtype=x_dt,
+                          w_dtype=w_dt, y_dtype=x_dt, res_dtype=hawq.U8, relu=1, y_lo=0, y_hi=127 if bits == 8 else 15,
+                          x_hi=127 if bits == 8 else 0)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        x, w, bias, b, c = dev(case["x"]), dev(case["w"]), dev(case["bias"]), dev(case["b"]), dev(case["c"])
+        y = torch.empty((N, P, Q, K if bits == 8 else K // 2), dtype=torch.uint8, device="cuda")
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for _ in range(5):
+            hawq.hawq_conv2d_int(d, x, w, bias, b, c, None, None, None, y)
+        for e0, e1 in ev:
+            e0.record()
+            hawq.hawq_conv2d_int(d, x, w, bias, b, c, None, None, None, y)
+            e1.record()
+        torch.cuda.synchronize()
+        us = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+        ops = 2.0 * N * P * Q * K * R * S * C
+        return dict(N=N, H=H, W=W, C=C, K=K, R=R, stride=stride, bits=bits, us=round(us, 2), tops=round(ops / us / 1e6, 1),
+                    frac_mfma_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
+    rows = []
+    for N in (1, 128):
+        rows.append(dict(config="single 3x3 layer", **run(N, 56, 56, 64, 64, 3, 3, 1, 1, 8, 1000)))
+    for batch in (8, 128):
+        for name, N, H, W, C, K, R, S, stride, pad in wl.int4_sweep_shapes(batch):
+            for bits in (4, 8):
+                rows.append(dict(config="sweep " + name, **run(N, H, W, C, K, R, S, stride, pad, bits, 1001)))
+    return {"workload": "single-layer configurations (event-timed launches include ~2 us of launch overhead)", "rows": rows}
+
+
 def module_ops(hawq, torch, steps, warmup):
     """Algorithmic GB/s of hawq_pool2d_sum_int and hawq_concat_dyadic at the size of an Inception 35x35 module, batch 128
     (synthetic INT32 feature maps resident in HBM; HIP events on the launch stream)."""
@@ -108,6 +144,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--conv-sweep", action="store_true",
+                    help="time the single-layer configurations (one 3x3 layer; the ResNet18-shaped INT4 / INT8 sweep) and exit")
     ap.add_argument("--module-ops", action="store_true",
                     help="time the two memory-bound operators of an Inception-style module instead (INT32 3x3 window-sum "
                          "pool and the concatenation with one dyadic number per branch, 128 x 35 x 35 x 288) and exit")
@@ -131,6 +169,9 @@ def main():
     import paper_2011_10680_amd as hawq
 
     hawq.load_library()   # fails loudly if libhawq.so is not built: there is no fallback path
+    if args.conv_sweep:
+        print(json.dumps(conv_sweep(hawq, torch, wl, np)))
+        return
     if args.module_ops:
         print(json.dumps(module_ops(hawq, torch, args.steps, args.warmup)))
         return

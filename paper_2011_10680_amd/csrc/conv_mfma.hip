@@ -11,10 +11,12 @@
 // in registers and writes 16-byte runs straight into the NHWC output.  INT32 never leaves the
 // register file.
 //
-// INT4 operands stay packed in HBM; the loader splits each 16-byte chunk into low and high
-// nibbles (weights sign-extended) and writes two INT8 chunks to LDS.  Both operands use the
-// same nibble de-interleave, i.e. the same permutation of kg, which leaves the dot product
-// unchanged.
+// INT4 operands stay packed in HBM.  With C a multiple of 128 they also stay packed in LDS (same LDS-DMA
+// pipeline as INT8, a K-step then covers 128 channels) and are split into nibbles between the fragment
+// read and the MFMA (template parameter PK).  Otherwise the loader passes them through registers, splits
+// each 16-byte chunk into low and high nibbles (weights sign-extended) and writes two INT8 chunks to LDS.
+// Both operands always use the same nibble de-interleave, i.e. the same permutation of kg, which leaves
+// the dot product unchanged.  gfx950 has no 4-bit integer MFMA: a 4-bit layer runs at the INT8 rate.
 #include "common.h"
 #include "epilogue.h"
 
@@ -36,13 +38,19 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // shortcut convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds
 // both (DUALM = 1) -- or first rounds the shortcut accumulator to the signed 8-bit value a separate transition layer would
 // have stored (DUALM = 2: the bits of the two-launch form without the tensor's round trip; see epilogue_tile_dual).
-template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, int DUALM = 0>
+// PK (4-bit operands whose channel count is a multiple of 128): the packed bytes take the LDS-DMA path unchanged -- a
+// K-step is then one tap and 128 input channels, still 64 bytes per row -- and are split into nibbles only between the
+// LDS fragment read and the MFMA (see unpack_pk below): per multiply-accumulate half the operand traffic of the INT8
+// form at every level above the register file.
+template <int BC, int BP, int WC, int WP, bool INT4, int NBUF = 4, int DUALM = 0, bool PK = false>
 __global__ void __launch_bounds__(WC *WP * 64) __attribute__((amdgpu_waves_per_eu(BC * BP / (WC * WP) >= 64 * 64 ? 2 : (BC * BP / (WC * WP) >= 64 * 32 ? (WC * WP == 8 ? 4 : 3) : 6))))
 conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nblocks, const int vec_epilogue) {
     constexpr bool DUAL = DUALM != 0;
     constexpr int T = WC * WP * 64;
-    constexpr int CPR = INT4 ? 2 : 4;           // 16-byte global chunks per tile row per K-step
-    constexpr int BKB = INT4 ? 32 : 64;         // bytes of one K-step in memory
+    static_assert(!PK || INT4, "the packed LDS-DMA form is a 4-bit form");
+    constexpr int CPR = (INT4 && !PK) ? 2 : 4;  // 16-byte global chunks per tile row per K-step
+    constexpr int BKB = (INT4 && !PK) ? 32 : 64;   // bytes of one K-step in memory
+    constexpr int CPS = PK ? 128 : 64;          // input channels of one K-step
     constexpr int NA = (BC * CPR + T - 1) / T;  // chunks per thread, weight tile
     constexpr int NB = (BP * CPR + T - 1) / T;  // chunks per thread, pixel tile
     constexpr int TC = BC / WC / 32;            // 32x32 MFMA tiles per wave along channels
@@ -53,12 +61,12 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // INT8 operands go global -> LDS directly (LDS-DMA buffer loads); packed INT4 operands pass through
     // registers to be unpacked.  The four pipeline buffers are separate objects so that the compiler's
     // wait-count tracking of the asynchronous LDS writes is per buffer.
-    constexpr bool DMA = !INT4;
+    constexpr bool DMA = !INT4 || PK;
     __shared__ __attribute__((aligned(1024))) uint8_t lds0[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds1[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds2[kBufBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t lds3[kBufBytes];
-    static_assert(NBUF == 4 || (NBUF == 8 && !INT4), "ring depth");
+    static_assert(NBUF == 4 || (NBUF == 8 && !INT4), "ring depth");   // (the deep ring measured slower with packed 4-bit operands)
     static_assert(!DUAL || !INT4, "the two-convolution form takes 8-bit operands");
     __shared__ __attribute__((aligned(1024))) uint8_t lds4[NBUF == 8 ? kBufBytes : 16];
     __shared__ __attribute__((aligned(1024))) uint8_t lds5[NBUF == 8 ? kBufBytes : 16];
@@ -93,7 +101,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int k0 = (int)(L % n_ctiles) * BC;
 
     const int Cb = INT4 ? a.C / 2 : a.C;          // bytes per pixel
-    const int cchunks = a.C / 64;                 // K-steps per tap
+    const int cchunks = a.C / CPS;                // K-steps per tap
     const int steps1 = a.R * a.S * cchunks;             // K-steps of the (main) convolution
     const int steps = steps1 + (DUAL ? a.Cs / 64 : 0);  // ... followed by those of the shortcut convolution
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
@@ -106,7 +114,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         } else {
             const int cc = st % cchunks, t = st / cchunks;
             const int s_ = t % a.S, r_ = t / a.S;
-            steptab[i] = make_int4(i < steps ? i * (INT4 ? 32 : 64) : 0x40000000, (r_ * a.W + s_) * Cb + cc * (INT4 ? 32 : 64),
+            steptab[i] = make_int4(i < steps ? i * BKB : 0x40000000, (r_ * a.W + s_) * Cb + cc * BKB,
                                    r_ | (s_ << 16), 0);
         }
     }
@@ -268,7 +276,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         v4i v;
         if constexpr (isA) { p0 = ldsbuf(bufc) + a_wo[j][0]; p1 = ldsbuf(bufc) + a_wo[j][1]; v = ra[set][j]; }
         else { p0 = ldsbuf(bufc) + b_wo[j][0]; p1 = ldsbuf(bufc) + b_wo[j][1]; v = rb[set][j]; }
-        if (INT4) {
+        if (INT4 && !PK) {
             v4i lo, hi;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -379,6 +387,39 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
 #pragma unroll
     for (int tp = 0; tp < TP; ++tp) bf0[tp] = *(const v4i *)(lds0 + b_fo[tp][0]);
 
+    // Packed 4-bit fragments: a lane's 16 bytes hold 32 channels of its row.  Low and high nibbles go to two MFMAs; both
+    // operands are split the same way, i.e. the reduction index is permuted identically on both sides.  Activations
+    // (unsigned) become bytes 0..15.  Weights (two's complement nibbles) are left in the upper half of their byte -- the
+    // byte then reads as 16 w, with the sign in place and no sign extension to compute -- so the accumulators hold
+    // 16 times the convolution and are shifted back once, after the K loop (exact; 16 * 15 * 8 * R*S*C is far inside
+    // INT32 for every reduction length the step table admits).
+    auto mfma_pk = [&](const v4i(&af)[TC], const v4i(&bf)[TP], auto between) {
+        v4i al[TC], ah[TC], bl[TP], bh[TP];
+#pragma unroll
+        for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t u = (uint32_t)af[tc][e];
+                al[tc][e] = (int)((u << 4) & 0xF0F0F0F0u);
+                ah[tc][e] = (int)(u & 0xF0F0F0F0u);
+            }
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t u = (uint32_t)bf[tp][e];
+                bl[tp][e] = (int)(u & 0x0F0F0F0Fu);
+                bh[tp][e] = (int)((u >> 4) & 0x0F0F0F0Fu);
+            }
+        static_for<0, TP * TC>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            constexpr int tp = i / TC, tc = i % TC;
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al[tc], bl[tp], acc[tp][tc], 0, 0, 0);
+            if constexpr (i == 0) between();
+            acc[tp][tc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah[tc], bh[tp], acc[tp][tc], 0, 0, 0);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
     auto iteration = [&](int step, auto phasec) {
         constexpr int phase = decltype(phasec)::value;            // step % 4
         using Cur = std::integral_constant<int, phase>;
@@ -405,6 +446,9 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         for (int tp = 0; tp < TP; ++tp) bf1[tp] = *(const v4i *)(ldsbuf(Cur{}) + b_fo[tp][1]);
         if constexpr (DMA) gload(step + NBUF - 1, Dma{});
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (PK) {
+            mfma_pk(af0, bf0, [] {});
+        } else {
         // first-half MFMAs (register path: each followed by one LDS write of step+2)
         static_for<0, TP * TC>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
@@ -413,12 +457,21 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             if constexpr (!DMA && i < NA + NB) lstore_one(Wr{}, Set{}, ic);
             __builtin_amdgcn_sched_barrier(0);
         });
+        }
         if constexpr (!DMA) {
             static_for<TP * TC, NA + NB>([&](auto ic) { lstore_one(Wr{}, Set{}, ic); });
             gload(step + 4, Set{});
             __builtin_amdgcn_sched_barrier(0);
         }
         // second-half MFMAs with the next step's first-half fragment reads in between
+        if constexpr (PK) {
+            mfma_pk(af1, bf1, [&] {
+#pragma unroll
+                for (int t2 = 0; t2 < TC; ++t2) af0[t2] = *(const v4i *)(ldsbuf(Nxt{}) + a_fo[t2][0]);
+#pragma unroll
+                for (int t2 = 0; t2 < TP; ++t2) bf0[t2] = *(const v4i *)(ldsbuf(Nxt{}) + b_fo[t2][0]);
+            });
+        } else
         static_for<0, TP * TC>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             constexpr int tp = i / TC, tc = i % TC;
@@ -444,6 +497,14 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     for (int step = 0; step < steps; step += NBUF)
         static_for<0, NBUF>([&](auto ic) { iteration(step + decltype(ic)::value, ic); });
 
+    if constexpr (PK) {
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+            for (int tc = 0; tc < TC; ++tc)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tp][tc][i] >>= 4;
+    }
     // ---- epilogue: lane owns pixel (tile tp, column rho) and channels ch0 .. ch0 + 16*TC ----
     const int chl = wc * (BC / WC) + khalf * 16 * TC;
     const int ch0 = k0 + chl;
@@ -479,6 +540,9 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     }
 }
 
+// 4-bit operands take the packed LDS-DMA form when a tap's channels fill whole 128-channel K-steps
+static bool conv_mfma_packed(const ConvArgs &a) { return is4(a.x_dt) && a.C % 128 == 0; }
+
 bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
     if (a.C % 64 != 0) return false;
     const bool four = is4(a.x_dt);
@@ -491,7 +555,7 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
         if (a.x_dt != HAWQ_U8 && a.x_dt != HAWQ_S8) return false;
     }
     if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
-    if ((int64_t)a.R * a.S * (a.C / 64) + 16 > kMaxSteps) return false;   // the per-step address table is in LDS
+    if ((int64_t)a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64)) + 16 > kMaxSteps) return false;   // the per-step address table is in LDS
     return true;
 }
 
@@ -530,7 +594,9 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s, bool de
             return check_launch();
         }
     }
-    if (is4(a.x_dt))
+    if (conv_mfma_packed(a))
+        conv_mfma_kernel<BC, BP, WC, WP, true, 4, 0, true><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
+    else if (is4(a.x_dt))
         conv_mfma_kernel<BC, BP, WC, WP, true><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
     else
         conv_mfma_kernel<BC, BP, WC, WP, false><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
@@ -565,13 +631,13 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
         // 512 -> 512 layer takes 19.9 us with weights resident in cache, 27.6 us with cold weights and the ring of
         // four, 26.2 us with the ring of eight.
         const int64_t nblocks = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
-        const int steps = a.R * a.S * (a.C / 64);
+        const int steps = a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64));
         return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16);
     }
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     // a few small tiles with a long reduction (the fully connected layer: 32 tiles x 32 K-steps at batch 128) advance one
     // memory latency per ring depth: the ring of eight there too
-    return launch_cfg<64, 64, 2, 2>(a, vec, s, (int64_t)((a.K + 63) / 64) * ((a.M + 63) / 64) <= 512 && a.R * a.S * (a.C / 64) >= 16);
+    return launch_cfg<64, 64, 2, 2>(a, vec, s, (int64_t)((a.K + 63) / 64) * ((a.M + 63) / 64) <= 512 && a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64)) >= 16);
 }
 
 }  // namespace hawq

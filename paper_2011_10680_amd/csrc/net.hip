@@ -252,7 +252,8 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         auto packed_pays = [&](const LayerShape &l) {
             const bool pw = l.R == 1 && l.S == 1 && (l.C == 64 || l.C == 128 || (l.C == 256 && l.K <= 128));
             const bool c64 = l.R == 3 && l.S == 3 && l.C == 64 && l.K == 64 && l.stride == 1 && l.pad == 1;
-            return pw || c64;
+            const bool c128 = l.R == 3 && l.S == 3 && l.C % 128 == 0;   // packed LDS-DMA form of the implicit-GEMM kernel
+            return pw || c64 || c128;
         };
         for (int i = 0; i < nl; ++i)
             if (lp[i].bits == 4 && !L[i].is_stem && !L[i].is_fc) expand[i] = !packed_pays(L[i]);

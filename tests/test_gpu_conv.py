@@ -299,6 +299,45 @@ def test_int4_conv_residual_u4_and_8bit_output(hawq):
     assert_same(got, want)
 
 
+# 4-bit layers whose channel count is a multiple of 128: the packed operands go to LDS as they are and are split into
+# nibbles at the matrix instruction.  Ragged pixel and channel tails, padding, stride, every tile shape, a shortcut,
+# both output widths, the weight extremes -8 and 7 next to activation 15, and a reduction of 4608.
+_SHAPES_PK = [
+    (3, 13, 11, 128, 128, 3, 3, 1, 1, False, 4),    # few pixels: 64x64 tile
+    (9, 29, 27, 128, 80, 3, 3, 1, 1, True, 4),      # K < 128, ragged channel tail, shortcut
+    (5, 28, 28, 256, 160, 3, 3, 2, 1, False, 4),    # strided, ragged channel tile
+    (12, 28, 28, 128, 128, 3, 3, 1, 1, True, 8),    # 128x128 tiles, 8-bit output
+    (16, 7, 7, 512, 512, 3, 3, 1, 1, False, 4),     # 36 K-steps of 128 channels
+    (7, 15, 15, 384, 64, 1, 1, 1, 0, False, 4),     # 1x1, three K-steps
+    (2, 9, 9, 128, 32, 5, 5, 1, 2, False, 4),       # 5x5 taps
+]
+
+
+@pytest.mark.parametrize("shape", _SHAPES_PK)
+def test_int4_packed_lds_form(hawq, shape):
+    from gpu_util import run_conv_gpu, assert_same
+    N, H, W, C, K, R, S, stride, pad, res, ybits = shape
+    case = _scale_c(wl.conv_case(seed=sum(shape[:9]) + 77, N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=4,
+                                 with_residual=res), 4)
+    # plant the extremes: a pixel of all 15s against a filter of all -8s and one of all 7s
+    xu = oracle.unpack(case["x"], oracle.U4).reshape(N, H, W, C)
+    wu = oracle.unpack(case["w"], oracle.S4).reshape(K, R, S, C)
+    xu[0, H // 2, W // 2, :] = 15
+    wu[0] = -8
+    wu[K - 1] = 7
+    case["x"] = wl.pack_nibbles(xu).reshape(case["x"].shape)
+    case["w"] = wl.pack_nibbles(wu).reshape(case["w"].shape)
+    if ybits == 8:
+        case["c"] = (case["c"].astype(np.int32) - 3).astype(np.uint8)
+        got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U8, res_dt=hawq.U4, y_hi=127)
+        v = want.astype(np.int32)
+    else:
+        got, want = run_conv_gpu(case, hawq.U4, hawq.S4, hawq.U4, res_dt=hawq.U4, y_hi=15)
+        v = oracle.unpack(want, oracle.U4)
+    assert_same(got, want, str(shape))
+    assert 0.03 < (v > 0).mean() < 0.999
+
+
 @pytest.mark.parametrize("shape", [(2, 20, 20, 3, 64, 7, 7, 2, 3), (1, 9, 9, 24, 10, 3, 3, 1, 1), (2, 6, 6, 64, 32, 1, 1, 1, 0)])
 def test_direct_kernel_shapes_and_full_range_u8(hawq, shape):
     """Shapes the matrix-core kernel does not take: C not a multiple of 64, and unsigned inputs up to 255."""
