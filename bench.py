@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="run the batch as one part on one stream (the library otherwise runs a batch of 96 or more as two "
+                         "halves on two streams); for per-kernel profiles, where overlapping kernels blur the durations")
     ap.add_argument("--conv-sweep", action="store_true",
                     help="time the single-layer configurations (one 3x3 layer; the ResNet18-shaped INT4 / INT8 sweep) and exit")
     ap.add_argument("--module-ops", action="store_true",
@@ -188,6 +191,9 @@ def main():
     net = wl.make_resnet(arch, seed=wk["seed"], bits=bits, int32_shortcut=wk.get("int32_shortcut", False))
     x = torch.from_numpy(wl.make_image_batch(wk["seed"] + 1, N)).cuda()
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
+    if args.single_stream:
+        hawq.hawq_tune_set_split(-1)
+    first = hn.split_first(N)
     ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
     logits = torch.empty((N, 1000), dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
@@ -240,7 +246,8 @@ def main():
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
     roof.update(traffic=profiled_traffic(args.workload),
-                kernel="one forward = %d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)" % sum(r["mbytes"] > 0 for r in rows),
+                kernel="one forward = %s%d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)"
+                       % ("2 x " if first else "", sum(r["mbytes"] > 0 for r in rows)),
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
                 # the matrix-core convolutions alone, from per-launch events (each interval also holds a few
@@ -255,7 +262,8 @@ def main():
         "dtype": "int8" if not wk["mixed"] else "int4/int8", "data": "synthetic",
         "config": {"workload": args.workload, "batch": N, "image": "3x224x224 uint8",
                    "layers_int4": sum(l["bits"] == 4 for l in net["layers"]),
-                   "transition_blocks": "int32 both branches" if wk.get("int32_shortcut") else "stored int8 shortcut"},
+                   "transition_blocks": "int32 both branches" if wk.get("int32_shortcut") else "stored int8 shortcut",
+                   "batch_parts": "%d + %d images on two streams" % (first, N - first) if first else "one"},
         "tops": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
         "frac_int8_mfma_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / PEAK_INT8_TOPS,
         "sum_kernel_ms": float(step_ms.sum()),

@@ -248,6 +248,9 @@ void hawq_net_destroy(hawq_net *net);
 /* Bytes of caller-provided device workspace hawq_forward_resnet needs for a batch of N. */
 size_t hawq_net_workspace_bytes(const hawq_net *net, int32_t N);
 
+/* Images in the first of the two parts hawq_forward_resnet runs a batch of N as (see there); 0: one part. */
+int32_t hawq_net_split_first(const hawq_net *net, int32_t N);
+
 /* Number of launches of one forward: conv1, max pool, the convolutions, average pool, fc. */
 int32_t hawq_net_num_steps(const hawq_net *net);
 
@@ -265,6 +268,12 @@ hawq_status hawq_net_step_output(const hawq_net *net, int32_t N, int32_t step, c
  * hawq_net_workspace_bytes(net, N) bytes, 256-byte aligned; x must be 16-byte aligned.  Enqueues every layer on
  * `stream`.  Unless the network keeps its activations, conv1 and the max pool run as one kernel and the conv1
  * tensor is never written to memory (its step reports an empty output).
+ * Stream semantics: as if every launch were on `stream` -- the forward starts after all work queued on `stream`
+ * before the call and work queued after the call sees the finished logits.  Inside, a batch of 96 images or more
+ * (without kept activations) runs as two halves, the second on a stream the network owns (default priority, created
+ * by hawq_net_create), forked and joined with events; images are independent, so the bits do not depend on it.
+ * Because that stream and its two events belong to the network object, calls on one hawq_net must be issued from one
+ * host thread at a time (any number may be in flight on the device).
  */
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream);

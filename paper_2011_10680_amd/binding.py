@@ -95,6 +95,10 @@ def load_library():
     lib.hawq_forward_resnet_timed.argtypes = [vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.hawq_tune_set_tile.restype = None
     lib.hawq_tune_set_tile.argtypes = [i32]
+    lib.hawq_net_split_first.restype = i32
+    lib.hawq_net_split_first.argtypes = [vp, i32]
+    lib.hawq_tune_set_split.restype = None
+    lib.hawq_tune_set_split.argtypes = [i32]
     lib.hawq_status_string.restype = ctypes.c_char_p
     lib.hawq_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -176,6 +180,11 @@ def hawq_tune_set_tile(tile):
     load_library().hawq_tune_set_tile(int(tile))
 
 
+def hawq_tune_set_split(n_first):
+    """Measurement hook: 0 = the library's batch-split rule, -1 = never split, n = first part of n images."""
+    load_library().hawq_tune_set_split(int(n_first))
+
+
 def hawq_net_num_layers(arch):
     return load_library().hawq_net_num_layers(arch)
 
@@ -248,6 +257,9 @@ class HawqNet:
         macs, nbytes = ctypes.c_double(), ctypes.c_double()
         _check(load_library().hawq_net_step_cost(self._h, N, step, ctypes.byref(macs), ctypes.byref(nbytes)), "hawq_net_step_cost")
         return macs.value, nbytes.value
+
+    def split_first(self, N):
+        return int(load_library().hawq_net_split_first(self._h, int(N)))
 
     def hawq_forward_resnet(self, x, N, logits, workspace, stream=None):
         _check(load_library().hawq_forward_resnet(self._h, _p(x), N, _p(logits), _p(workspace),

@@ -119,6 +119,9 @@ struct hawq_net {
     std::vector<Step> steps;
     std::vector<int64_t> slot_bytes_per_image;
     void *arena = nullptr;
+    // a large batch runs as two parts on two streams (see hawq_forward_resnet): the second stream and the fork / join events
+    hipStream_t aux_stream = nullptr;
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
 };
 
 namespace {
@@ -175,6 +178,22 @@ size_t slot_offset(const hawq_net *net, int slot, int N) {
     size_t off = 0;
     for (int i = 0; i < slot; ++i) off += align_up((size_t)net->slot_bytes_per_image[i] * N, 256);
     return off;
+}
+
+size_t workspace_one_part(const hawq_net *net, int N) { return slot_offset(net, (int)net->slot_bytes_per_image.size(), N); }
+
+// Batch split.  Every kernel of a forward pays a ramp-up and a tail in which part of the chip idles (tiles do not divide
+// evenly over 256 CUs, pipelines fill and drain), about a fifth of a ResNet50 forward at batch 128.  Images are
+// independent, so a large batch is run as two parts on two streams: the second part's kernels fill the first part's
+// gaps (measured 5 % on ResNet50 at batch 128 with equal parts; nothing at batch 64, a loss with three or four parts).
+// Returns the size of the first part, 0 for no split.
+int g_split_override = 0;   // 0: rule below; -1: never split; n > 0: first part of n images (measurement hook)
+int split_first_part(const hawq_net *net, int N) {
+    if (net->keep || !net->aux_stream) return 0;
+    if (g_split_override < 0) return 0;
+    if (g_split_override > 0) return g_split_override < N ? g_split_override : 0;
+    if (N < 96) return 0;
+    return ((N / 2) + 7) & ~7;
 }
 
 }  // namespace
@@ -325,6 +344,13 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     if (hipMemcpy(net->arena, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipFree(net->arena);
         return fail(HAWQ_ERR_DEVICE);
+    }
+    // second stream (default priority) and the events that order it against the caller's stream
+    if (hipStreamCreateWithFlags(&net->aux_stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&net->fork_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&net->join_ev, hipEventDisableTiming) != hipSuccess) {
+        hawq_net_destroy(net);
+        return HAWQ_ERR_DEVICE;
     }
     const uint8_t *A = (const uint8_t *)net->arena;
 
@@ -512,13 +538,25 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
 void hawq_net_destroy(hawq_net *net) {
     if (!net) return;
     if (net->arena) (void)hipFree(net->arena);
+    if (net->aux_stream) { (void)hipStreamSynchronize(net->aux_stream); (void)hipStreamDestroy(net->aux_stream); }
+    if (net->fork_ev) (void)hipEventDestroy(net->fork_ev);
+    if (net->join_ev) (void)hipEventDestroy(net->join_ev);
     delete net;
 }
 
 size_t hawq_net_workspace_bytes(const hawq_net *net, int32_t N) {
     if (!net || N <= 0) return 0;
-    return slot_offset(net, (int)net->slot_bytes_per_image.size(), N);
+    // room for the batch as one part and as two (256-byte rounding per tensor makes the two layouts differ slightly)
+    size_t need = workspace_one_part(net, N);
+    const int n1 = split_first_part(net, N);
+    if (n1 > 0) {
+        const size_t two = workspace_one_part(net, n1) + workspace_one_part(net, N - n1);
+        if (two > need) need = two;
+    }
+    return need;
 }
+
+int32_t hawq_net_split_first(const hawq_net *net, int32_t N) { return (net && N > 0) ? split_first_part(net, N) : 0; }
 
 int32_t hawq_net_num_steps(const hawq_net *net) { return net ? (int32_t)net->steps.size() : 0; }
 
@@ -560,17 +598,30 @@ hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, dou
     return HAWQ_OK;
 }
 
-static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
-                               size_t workspace_bytes, hipStream_t stream, hipEvent_t *ev) {
-    if (!net || !x || !logits || !workspace) return HAWQ_ERR_NULL;
-    if (N <= 0) return HAWQ_ERR_SHAPE;
-    if (workspace_bytes < hawq_net_workspace_bytes(net, N)) return HAWQ_ERR_WORKSPACE;
-    if ((uintptr_t)workspace & 255) return HAWQ_ERR_UNSUPPORTED;
-    uint8_t *ws = (uint8_t *)workspace;
-    auto tptr = [&](int t) -> uint8_t * { return ws + slot_offset(net, net->tensors[t].slot, N); };
-    char deferred[256] = {0};   // transition steps whose work runs with their block's last convolution
-    if (net->steps.size() > sizeof deferred) return HAWQ_ERR_UNSUPPORTED;
-    for (size_t s = 0; s < net->steps.size(); ++s) {
+// One part of a batch: its images, outputs, workspace and the stream its launches go to
+struct Part {
+    const void *x;
+    int32_t N;
+    int32_t *logits;
+    uint8_t *ws;
+    hipStream_t stream;
+    char deferred[256];   // transition steps whose work runs with their block's last convolution
+};
+
+// Launch every step for every part, step by step (so that the parts' launches reach their streams interleaved).
+// ev (one part only): an event before and after each step.
+static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipEvent_t *ev) {
+    if (net->steps.size() > sizeof parts[0].deferred) return HAWQ_ERR_UNSUPPORTED;
+    for (size_t s = 0; s < net->steps.size(); ++s)
+    for (int pi = 0; pi < n_parts; ++pi) {
+        Part &part = parts[pi];
+        const void *x = part.x;
+        const int32_t N = part.N;
+        int32_t *logits = part.logits;
+        uint8_t *ws = part.ws;
+        hipStream_t stream = part.stream;
+        char *deferred = part.deferred;
+        auto tptr = [&](int t) -> uint8_t * { return ws + slot_offset(net, net->tensors[t].slot, N); };
         const Step &st = net->steps[s];
         if (ev && hipEventRecord(ev[2 * s], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
         hawq_status rc = HAWQ_OK;
@@ -659,6 +710,38 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
     }
     return HAWQ_OK;
 }
+
+static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
+                               size_t workspace_bytes, hipStream_t stream, hipEvent_t *ev) {
+    if (!net || !x || !logits || !workspace) return HAWQ_ERR_NULL;
+    if (N <= 0) return HAWQ_ERR_SHAPE;
+    if (workspace_bytes < hawq_net_workspace_bytes(net, N)) return HAWQ_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 255) return HAWQ_ERR_UNSUPPORTED;
+    Part parts[2] = {};
+    parts[0].x = x; parts[0].N = N; parts[0].logits = logits; parts[0].ws = (uint8_t *)workspace; parts[0].stream = stream;
+    const int n1 = ev ? 0 : split_first_part(net, N);   // (per-step timing: one part, one stream)
+    if (n1 <= 0) return run_parts(net, parts, 1, ev);
+    // two parts: images [0, n1) on the caller's stream, [n1, N) on the net's second stream, which starts after everything
+    // already queued on the caller's stream and which the caller's stream waits for at the end
+    const size_t image_bytes = (size_t)net->hw * net->hw * 3;
+    parts[0].N = n1;
+    parts[1].x = (const uint8_t *)x + (size_t)n1 * image_bytes;
+    parts[1].N = N - n1;
+    parts[1].logits = logits + (size_t)n1 * net->classes;
+    parts[1].ws = (uint8_t *)workspace + workspace_one_part(net, n1);
+    parts[1].stream = net->aux_stream;
+    if (hipEventRecord(net->fork_ev, stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+    if (hipStreamWaitEvent(net->aux_stream, net->fork_ev, 0) != hipSuccess) return HAWQ_ERR_DEVICE;
+    const hawq_status rc = run_parts(net, parts, 2, nullptr);
+    // join even after a failed launch, so that the caller's stream never runs ahead of work queued on the second one
+    if (hipEventRecord(net->join_ev, net->aux_stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+    if (hipStreamWaitEvent(stream, net->join_ev, 0) != hipSuccess) return HAWQ_ERR_DEVICE;
+    return rc;
+}
+
+// Measurement hook (not part of the documented interface): 0 = the library's rule, -1 = never split a batch, n = first part of n images.
+// Set it before sizing the workspace.
+void hawq_tune_set_split(int32_t n_first) { g_split_override = n_first; }
 
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream) {

@@ -113,3 +113,43 @@ def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed
         assert np.array_equal(got[i], want[j]), "image %d of the full batch differs from the oracle" % i
     assert len({got[i].tobytes() for i in range(batch - 1)}) == batch - 1   # distinct images, distinct logits
     hn.close()
+
+
+@pytest.mark.parametrize("arch,N,first", [(18, 13, 5), (50, 6, 4), (18, 9, 8)])
+def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first):
+    """A large batch runs as two parts on two streams.  Forced here at small sizes (odd parts, the second part's image,
+    logits and workspace offsets): same bits as the unsplit forward and as the oracle; called on a side stream right
+    behind the copy that delivers the images, twice in a row with different images (the second call must not
+    overtake the first on the library's own stream), and once more after the hook is reset."""
+    import torch
+    net = wl.make_resnet(arch, seed=31 + N, image_hw=64, int32_shortcut=(arch == 50))
+    xa = wl.make_image_batch(3, N, image_hw=64)
+    xb = wl.make_image_batch(4, N, image_hw=64)
+    want_a, want_b = onet.forward(net, xa), onet.forward(net, xb)
+    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"], image_hw=64)
+    try:
+        hawq.hawq_tune_set_split(first)
+        ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xA5)
+        side = torch.cuda.Stream()
+        pinned_a, pinned_b = torch.from_numpy(xa).pin_memory(), torch.from_numpy(xb).pin_memory()
+        xd = torch.empty(xa.shape, dtype=torch.uint8, device="cuda")
+        la = torch.zeros((N, 1000), dtype=torch.int32, device="cuda")
+        lb = torch.zeros((N, 1000), dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            xd.copy_(pinned_a, non_blocking=True)
+            hn.hawq_forward_resnet(xd, N, la, ws, side.cuda_stream)
+            xd.copy_(pinned_b, non_blocking=True)          # overwrites the images: must wait for both parts of the first call
+            hn.hawq_forward_resnet(xd, N, lb, ws, side.cuda_stream)
+        side.synchronize()
+        assert np.array_equal(la.cpu().numpy(), want_a)
+        assert np.array_equal(lb.cpu().numpy(), want_b)
+        hawq.hawq_tune_set_split(-1)
+        lc = torch.zeros((N, 1000), dtype=torch.int32, device="cuda")
+        hn.hawq_forward_resnet(xd, N, lc, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(lc.cpu().numpy(), want_b)
+    finally:
+        hawq.hawq_tune_set_split(0)
+        hn.close()
