@@ -153,3 +153,42 @@ def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first):
     finally:
         hawq.hawq_tune_set_split(0)
         hn.close()
+
+
+def test_forward_captured_in_a_graph_replays_like_eager(hawq):
+    """The forward (here split over the caller's stream and the library's second stream) recorded into a HIP graph:
+    every replay, with new images and eager work in between, gives the eager bits."""
+    import torch
+    N = 12
+    net = wl.make_resnet(18, seed=5, image_hw=64)
+    hn = hawq.HawqNet(18, net["layers"], net["pool_b"], net["pool_c"], image_hw=64)
+    try:
+        hawq.hawq_tune_set_split(8)
+        assert hn.split_first(N) == 8
+        ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
+        x = torch.from_numpy(wl.make_image_batch(1, N, image_hw=64)).cuda()
+        logits = torch.zeros((N, 1000), dtype=torch.int32, device="cuda")
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            hn.hawq_forward_resnet(x, N, logits, ws, s.cuda_stream)
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                hn.hawq_forward_resnet(x, N, logits, ws, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for i in range(3):
+            xi = wl.make_image_batch(20 + i, N, image_hw=64)
+            x.copy_(torch.from_numpy(xi).cuda())
+            logits.zero_()
+            ws.fill_(i)
+            g.replay()
+            torch.cuda.synchronize()
+            got = logits.cpu().numpy()
+            logits.zero_()
+            hn.hawq_forward_resnet(x, N, logits, ws)      # eager, between the replays
+            torch.cuda.synchronize()
+            assert np.array_equal(got, logits.cpu().numpy()), "replay %d" % i
+            assert np.array_equal(got, onet.forward(net, xi)), "replay %d against the oracle" % i
+    finally:
+        hawq.hawq_tune_set_split(0)
+        hn.close()
