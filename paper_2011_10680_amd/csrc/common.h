@@ -39,6 +39,9 @@ struct ConvArgs {
     // transition layer would store, and that value enters the sum rescaled by (res_b, res_c) -- the two-launch result
     // without the tensor's round trip through memory
     int32_t mid_s8;
+    // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
+    // that take a whole CU's LDS for one workgroup are avoided, they would keep the other stream's workgroups off that CU
+    int32_t corun;
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }

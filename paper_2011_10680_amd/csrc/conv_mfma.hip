@@ -632,7 +632,8 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
         // four, 26.2 us with the ring of eight.
         const int64_t nblocks = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
         const int steps = a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64));
-        return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16);
+        // (not when another stream's kernels share the chip: eight buffers are 142 KB of a CU's 160 KB of LDS)
+        return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16 && !a.corun);
     }
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     // a few small tiles with a long reduction (the fully connected layer: 32 tiles x 32 K-steps at batch 128) advance one

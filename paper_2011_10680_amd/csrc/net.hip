@@ -636,6 +636,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                                 a, x_hi, xs_hi);
             if (rc != HAWQ_OK) return rc;
             a.mid_s8 = 1; a.res_b = l.res_b; a.res_c = l.res_c;
+            a.corun = n_parts > 1;
             if (st.pair_last >= 0) {
                 if (pair_runs_fused(net, N, (int)s) && (conv_pws_dual_eligible(a, x_hi, xs_hi) || conv_mfma_dual_eligible(a, x_hi, xs_hi))) {
                     deferred[s] = 1;
@@ -663,6 +664,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             const bool raw = st.kind == STEP_FC || st.raw;
             rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
                                 outp, true, a, x_hi);
+            a.corun = n_parts > 1;
             if (rc == HAWQ_OK) {
                 if (st.kind == STEP_STEM && st.fused_pool && conv_stem_eligible(a)) {
                     const Step &pool = net->steps[s + 1];
@@ -688,6 +690,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             int x_hi, xs_hi;
             rc = make_dual_args(&d, in, st.w, st.bias, st.b, st.c, &dsc, tptr(st.res), st.w_s, st.bias_s, st.b_s, st.c_s, outp,
                                 true, a, x_hi, xs_hi);
+            a.corun = n_parts > 1;
             if (rc == HAWQ_OK) rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
             break;
         }
