@@ -91,6 +91,7 @@ def conv_sweep(hawq, torch, wl, np):
         ops = 2.0 * N * P * Q * K * R * S * C
         return dict(N=N, H=H, W=W, C=C, K=K, R=R, stride=stride, bits=bits, us=round(us, 2), tops=round(ops / us / 1e6, 1),
                     frac_mfma_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
+    loop_peak = hawq.hawq_probe_mfma_peak()      # TOP/s of a register-only INT8 MFMA loop on this device
     rows = []
     for N in (1, 128):
         rows.append(dict(config="single 3x3 layer", **run(N, 56, 56, 64, 64, 3, 3, 1, 1, 8, 1000)))
@@ -98,7 +99,10 @@ def conv_sweep(hawq, torch, wl, np):
         for name, N, H, W, C, K, R, S, stride, pad in wl.int4_sweep_shapes(batch):
             for bits in (4, 8):
                 rows.append(dict(config="sweep " + name, **run(N, H, W, C, K, R, S, stride, pad, bits, 1001)))
-    return {"workload": "single-layer configurations (event-timed launches include ~2 us of launch overhead)", "rows": rows}
+    for r in rows:
+        r["frac_mfma_loop_peak"] = round(r["tops"] / loop_peak, 4)
+    return {"workload": "single-layer configurations (event-timed launches include ~2 us of launch overhead)",
+            "mfma_peak_tops": PEAK_INT8_TOPS, "mfma_loop_peak_tops": round(loop_peak, 1), "rows": rows}
 
 
 def module_ops(hawq, torch, steps, warmup):
@@ -213,6 +217,7 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
+    loop_peak = hawq.hawq_probe_mfma_peak()
     # per-launch device times (HIP events recorded by the library on the same stream), median of a few passes
     reps = max(3, min(10, args.steps))
     per = np.array([hn.hawq_forward_resnet_timed(x, N, logits, ws, stream) for _ in range(reps)])
@@ -250,6 +255,8 @@ def main():
                        % ("2 x " if first else "", sum(r["mbytes"] > 0 for r in rows)),
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
+                # the same against what a register-only INT8 MFMA loop sustains on this device, measured now
+                mfma_loop_peak_tops=loop_peak, mfma_frac_of_loop_peak=achieved_tops / loop_peak,
                 # the matrix-core convolutions alone, from per-launch events (each interval also holds a few
                 # microseconds of launch and event overhead that the untimed forward does not pay)
                 conv_kernels=dict(launches=len(conv_rows), launches_ms=conv_ms, gbs=conv_bytes / (conv_ms * 1e-3) / 1e9,

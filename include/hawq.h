@@ -295,6 +295,20 @@ hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, dou
  * in this process.  Results are identical for every setting. */
 void hawq_tune_set_tile(int32_t tile);
 
+/* Measurement hook for the batch split of hawq_forward_resnet: 0 = the built-in rule (default), -1 = never split,
+ * n > 0 = first part of n images (the rest forms the second part) for every later call in this process.  Set it before
+ * sizing the workspace.  Results are identical for every setting. */
+void hawq_tune_set_split(int32_t n_first);
+
+/*
+ * Measurement helper: TOP/s of a register-only loop of independent INT8 matrix instructions (32x32x32, four
+ * accumulators per wave, sixteen waves per compute unit, `iters` rounds, no memory traffic in the loop) on the current
+ * device's default stream -- the sustained matrix-core rate to hold a convolution's TOP/s against, next to the
+ * datasheet peak.  Synchronous; allocates and frees 1 MB of device memory.  tops: host pointer.
+ * HAWQ_ERR_RANGE unless 1 <= iters <= 1000000.
+ */
+hawq_status hawq_probe_mfma_peak(int32_t iters, double *tops);
+
 const char *hawq_status_string(hawq_status s);
 
 #ifdef __cplusplus

@@ -97,6 +97,8 @@ def load_library():
     lib.hawq_tune_set_tile.argtypes = [i32]
     lib.hawq_net_split_first.restype = i32
     lib.hawq_net_split_first.argtypes = [vp, i32]
+    lib.hawq_probe_mfma_peak.restype = ctypes.c_int
+    lib.hawq_probe_mfma_peak.argtypes = [i32, ctypes.POINTER(ctypes.c_double)]
     lib.hawq_tune_set_split.restype = None
     lib.hawq_tune_set_split.argtypes = [i32]
     lib.hawq_status_string.restype = ctypes.c_char_p
@@ -178,6 +180,13 @@ def hawq_concat_dyadic(n_pixels, branches, y_dt, y_lo, y_hi, y, stream=None):
 
 def hawq_tune_set_tile(tile):
     load_library().hawq_tune_set_tile(int(tile))
+
+
+def hawq_probe_mfma_peak(iters=4000):
+    """TOP/s of a register-only INT8 MFMA loop on the current device (see the header)."""
+    tops = ctypes.c_double(0.0)
+    _check(load_library().hawq_probe_mfma_peak(int(iters), ctypes.byref(tops)), "hawq_probe_mfma_peak")
+    return tops.value
 
 
 def hawq_tune_set_split(n_first):

@@ -121,6 +121,10 @@ def test_other_entry_points_validate_on_host(lib):
     assert lib.hawq_avgpool_int(1, 7, 7, 64, 0, 0, P, None, P, 0, 127, P, None) == 1
     assert lib.hawq_maxpool_int(1, 8, 8, 63, 0, 2, P, 0, 15, P, None) == 2
     assert lib.hawq_forward_resnet(None, P, 1, P, P, 0, None) == 1
+    assert lib.hawq_probe_mfma_peak(100, None) == 1
+    t = ctypes.c_double(0)
+    assert lib.hawq_probe_mfma_peak(0, ctypes.byref(t)) == 4 and lib.hawq_probe_mfma_peak(2000000, ctypes.byref(t)) == 4
+    assert lib.hawq_net_split_first(None, 128) == 0
     pool = lambda *a: lib.hawq_pool2d_sum_int(*a, None)
     assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 4, None, None, None, 0, 0, P) == 1
     assert pool(1, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 4, P, P, None, 0, 0, P) == 1          # b without c

@@ -93,3 +93,10 @@ def test_maxpool(hawq, N, H, W, C, x_dt, y_dt, hi):
     torch.cuda.synchronize()
     want = oracle.maxpool_int(x, N=N, H=H, W=W, C=C, x_dt=x_dt, y_dt=y_dt, y_lo=lo, y_hi=hi)
     assert_same(y.cpu().numpy(), want)
+
+
+def test_mfma_loop_probe_reports_a_plausible_rate(hawq):
+    """The register-only INT8 MFMA loop: between a fifth of and the whole datasheet peak (5.03 POP/s), and stable."""
+    a, b = hawq.hawq_probe_mfma_peak(2000), hawq.hawq_probe_mfma_peak(2000)
+    assert 1000.0 < a < 5100.0 and 1000.0 < b < 5100.0
+    assert abs(a - b) / a < 0.2
