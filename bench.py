@@ -158,8 +158,8 @@ def main():
                          "pool and the concatenation with one dyadic number per branch, 128 x 35 x 35 x 288) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path shards by batch with no exchange; "
-              "see DESIGN.md) -- run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (images are independent: more GPUs would each take a share of "
+              "the batch, with no exchange) -- run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

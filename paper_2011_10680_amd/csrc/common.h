@@ -39,6 +39,10 @@ struct ConvArgs {
     // transition layer would store, and that value enters the sum rescaled by (res_b, res_c) -- the two-launch result
     // without the tensor's round trip through memory
     int32_t mid_s8;
+    // w_t / ws_t (optional, the network plan provides them): the same weights as w / ws in blocked order for the
+    // implicit-GEMM kernel -- [ceil(K/64)][row bytes / 64][64 channels][64 bytes], i.e. the [K][R*S*C] byte matrix cut
+    // into 64-channel x 64-byte blocks, rows past K zero -- so that one K-step of a channel tile is contiguous memory
+    const void *w_t, *ws_t;
     // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
     // that take a whole CU's LDS for one workgroup are avoided, they would keep the other stream's workgroups off that CU
     int32_t corun;

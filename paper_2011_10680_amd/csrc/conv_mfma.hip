@@ -105,16 +105,20 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     const int steps1 = a.R * a.S * cchunks;             // K-steps of the (main) convolution
     const int steps = steps1 + (DUAL ? a.Cs / 64 : 0);  // ... followed by those of the shortcut convolution
     const int64_t wrow_bytes = (int64_t)a.R * a.S * Cb;
+    // Weights in blocked order (see ConvArgs::w_t): a channel tile's K-step is 4 KB (64 channels) or 8 KB of contiguous
+    // memory instead of 64-byte pieces a filter apart -- whole cache lines, and fewer of them, per LDS-DMA instruction.
+    const bool tiled = DMA && a.w_t != nullptr && (!DUAL || a.ws_t != nullptr);
+    const int wstep = tiled ? 4096 : BKB;          // bytes from one K-step to the next
     // (the rounded-up loop fetches at most 2*NBUF - 2 entries past the last step)
     for (int i = tid; i < steps + 2 * NBUF; i += T) {
         const int st = i < steps ? i : steps - 1;      // past the last step the activation address stays put ...
         // ... and the weight offset leaves the buffer: the weights read as zeros, padded iterations add nothing
         if (DUAL && st >= steps1) {
-            steptab[i] = make_int4(i < steps ? (st - steps1) * 64 : 0x40000000, (st - steps1) * 64, 0, 0);
+            steptab[i] = make_int4(i < steps ? (st - steps1) * wstep : 0x40000000, (st - steps1) * 64, 0, 0);
         } else {
             const int cc = st % cchunks, t = st / cchunks;
             const int s_ = t % a.S, r_ = t / a.S;
-            steptab[i] = make_int4(i < steps ? i * BKB : 0x40000000, (r_ * a.W + s_) * Cb + cc * BKB,
+            steptab[i] = make_int4(i < steps ? i * wstep : 0x40000000, (r_ * a.W + s_) * Cb + cc * BKB,
                                    r_ | (s_ << 16), 0);
         }
     }
@@ -126,8 +130,8 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // hardware returns zeros -- no branch, no select, and the address is one 32-bit add.
     constexpr uint32_t kInvalid = 0x80000000u;     // >= any tensor size the interface accepts
     // (not const: the two-convolution form switches descriptors and offsets to the shortcut's tensors once)
-    __amdgpu_buffer_rsrc_t rsrc_w =
-        __builtin_amdgcn_make_buffer_rsrc((void *)a.w, 0, (int)((int64_t)a.K * wrow_bytes), 0x00020000);
+    __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(tiled ? a.w_t : a.w), 0, (int)(tiled ? (int64_t)((a.K + 63) / 64) * steps1 * 4096 : (int64_t)a.K * wrow_bytes), 0x00020000);
     __amdgpu_buffer_rsrc_t rsrc_x =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.N * a.H * a.W * Cb), 0x00020000);
     int a_row[NA], a_ch[NA];
@@ -141,7 +145,9 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         a_ch[j] = DMA ? ((i % CPR) ^ swz(a_row[j])) : (i % CPR);
         const int k = k0 + a_row[j];
         const bool ok = (i < BC * CPR) && (k < a.K);
-        a_voff[j] = ok ? (uint32_t)(k * (int)wrow_bytes + a_ch[j] * 16) : kInvalid;
+        a_voff[j] = !ok ? kInvalid
+                        : tiled ? (uint32_t)((k >> 6) * steps1 * 4096 + (k & 63) * 64 + a_ch[j] * 16)
+                                : (uint32_t)(k * (int)wrow_bytes + a_ch[j] * 16);
     }
     int b_row[NB], b_ch[NB], b_ih0[NB], b_iw0[NB];
     uint32_t b_voff[NB];   // offset of tap (0,0), channel chunk 0 (may be "negative" inside the padding)
@@ -180,7 +186,9 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
 #pragma unroll
         for (int j = 0; j < NA; ++j) {
             const int k = k0 + a_row[j];
-            accm[0][0][j] = (int)(k < a.K ? (uint32_t)(k * a.Cs + a_ch[j] * 16) : kInvalid);
+            accm[0][0][j] = (int)(k >= a.K ? kInvalid
+                                           : tiled ? (uint32_t)((k >> 6) * (a.Cs / 64) * 4096 + (k & 63) * 64 + a_ch[j] * 16)
+                                                   : (uint32_t)(k * a.Cs + a_ch[j] * 16));
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
@@ -209,7 +217,8 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         (void)step;
         if constexpr (DUAL) {
             if (tab_i == steps1) {   // first K-step of the shortcut convolution: from here on its tensors are fetched
-                rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.ws, 0, (int)((int64_t)a.K * a.Cs), 0x00020000);
+                rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)(tiled ? a.ws_t : a.ws), 0,
+                                                           (int)(tiled ? (int64_t)((a.K + 63) / 64) * (a.Cs / 64) * 4096 : (int64_t)a.K * a.Cs), 0x00020000);
                 rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.xs, 0, (int)((int64_t)a.N * a.Hs * a.Ws * a.Cs), 0x00020000);
                 // the shortcut's offsets were parked in the not yet used second accumulator set (see below)
 #pragma unroll

@@ -90,6 +90,7 @@ struct Step {
     hawq_conv_desc desc{};        // N filled per call
     hawq_conv_desc desc_s{};      // STEP_CONV_DUAL: the transition convolution (reads tensor `res`)
     const uint8_t *w_s = nullptr;             // ... its parameters
+    const uint8_t *w_t = nullptr, *w_s_t = nullptr;   // the weights (and the shortcut's) in the implicit-GEMM kernel's blocked order
     const int32_t *bias_s = nullptr, *b_s = nullptr;
     const uint8_t *c_s = nullptr;
     bool raw = false;             // STEP_CONV: store the INT32 accumulator + bias, no requantisation
@@ -290,13 +291,18 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto cont_dt = [&](int i) { return is8(i) ? HAWQ_U8 : HAWQ_U4; };     // container of the tensor layer i reads
 
     // ---- parameter arena layout ----
-    struct Off { size_t w, bias, b, c, rb, rc; };
+    struct Off { size_t w, wt, bias, b, c, rb, rc; };
+    // row of the [K][R*S*C] weight matrix in bytes as stored, and whether a blocked copy is made for the implicit-GEMM
+    // kernel (64-byte K-steps: 8-bit form with C % 64 == 0, packed 4-bit form with C % 128 == 0)
+    auto wrow = [&](int i) { return (int64_t)tensor_bytes((int64_t)L[i].R * L[i].S * L[i].C, is8(i) ? HAWQ_S8 : HAWQ_S4); };
+    auto blocked = [&](int i) { return !L[i].is_stem && L[i].C % (is8(i) ? 64 : 128) == 0; };
     std::vector<Off> off(nl);
     size_t total = 0;
     auto take = [&](size_t bytes) { size_t o = total; total = align_up(total + bytes, 256); return o; };
     for (int i = 0; i < nl; ++i) {
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
         off[i].w = take((size_t)tensor_bytes(nw, is8(i) ? HAWQ_S8 : HAWQ_S4));
+        off[i].wt = blocked(i) ? take((size_t)((L[i].K + 63) / 64) * (size_t)wrow(i) * 64) : 0;
         off[i].bias = take(4 * (size_t)L[i].K);
         off[i].b = take(4 * (size_t)L[i].K);
         off[i].c = take((size_t)L[i].K);
@@ -317,6 +323,14 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             }
         } else {
             memcpy(&host[off[i].w], lp[i].w, (size_t)tensor_bytes(nw, lp[i].bits == 4 ? HAWQ_S4 : HAWQ_S8));
+        }
+        if (blocked(i)) {   // [K][row] -> [K/64][row/64][64][64], rows past K stay zero
+            const int64_t row = wrow(i), nsteps = row / 64;
+            const uint8_t *src = &host[off[i].w];
+            uint8_t *dst = &host[off[i].wt];
+            for (int k = 0; k < L[i].K; ++k)
+                for (int64_t st = 0; st < nsteps; ++st)
+                    memcpy(dst + (((int64_t)(k >> 6) * nsteps + st) * 64 + (k & 63)) * 64, src + k * row + st * 64, 64);
         }
         memcpy(&host[off[i].bias], lp[i].bias, 4 * (size_t)L[i].K);
         if (!L[i].is_fc) {
@@ -384,6 +398,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         if (raw) { d.y_dtype = HAWQ_S32; d.relu = 0; d.y_lo = INT32_MIN; d.y_hi = INT32_MAX; }
         d.x_hi = in_hi;
         st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
+        st.w_t = blocked(i) ? A + off[i].wt : nullptr;
         st.b = (const int32_t *)(A + off[i].b); st.c = A + off[i].c;
         if (res_t >= 0) { st.res_b = (const int32_t *)(A + off[i].rb); st.res_c = A + off[i].rc; }
         st.out = new_tensor(L[i].P, L[i].Q, L[i].K, d.y_dtype);
@@ -464,6 +479,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                 d.H = L[ds].H; d.W = L[ds].W; d.C = L[ds].C; d.R = d.S = 1; d.stride_h = d.stride_w = L[ds].stride; d.pad_h = d.pad_w = 0;
                 d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);   // (8-bit form: block_in_dt is HAWQ_U8)
                 st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
+                st.w_s_t = blocked(ds) ? A + off[ds].wt : nullptr;
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
                 st.bytes_per_image += (double)L[ds].P * L[ds].Q * L[ds].C;   // a strided 1x1 touches only the sampled pixels
@@ -525,6 +541,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         d.x_dtype = HAWQ_U8; d.w_dtype = HAWQ_S8; d.y_dtype = HAWQ_S32; d.res_dtype = HAWQ_U8; d.x_hi = 127;
         d.y_lo = INT32_MIN; d.y_hi = INT32_MAX;
         st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
+        st.w_t = blocked(i) ? A + off[i].wt : nullptr;
         st.macs_per_image = (double)L[i].C * L[i].K;
         st.bytes_per_image = (double)L[i].C + 4.0 * L[i].K;
         st.bytes_fixed = (double)L[i].C * L[i].K + 4.0 * L[i].K;
@@ -637,6 +654,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             if (rc != HAWQ_OK) return rc;
             a.mid_s8 = 1; a.res_b = l.res_b; a.res_c = l.res_c;
             a.corun = n_parts > 1;
+            a.w_t = l.w_t; a.ws_t = d.w_t;
             if (st.pair_last >= 0) {
                 if (pair_runs_fused(net, N, (int)s) && (conv_pws_dual_eligible(a, x_hi, xs_hi) || conv_mfma_dual_eligible(a, x_hi, xs_hi))) {
                     deferred[s] = 1;
@@ -665,6 +683,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             rc = make_conv_args(&d, in, st.w, st.bias, raw ? nullptr : st.b, raw ? nullptr : st.c, res, st.res_b, st.res_c,
                                 outp, true, a, x_hi);
             a.corun = n_parts > 1;
+            a.w_t = st.w_t;
             if (rc == HAWQ_OK) {
                 if (st.kind == STEP_STEM && st.fused_pool && conv_stem_eligible(a)) {
                     const Step &pool = net->steps[s + 1];
@@ -691,6 +710,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             rc = make_dual_args(&d, in, st.w, st.bias, st.b, st.c, &dsc, tptr(st.res), st.w_s, st.bias_s, st.b_s, st.c_s, outp,
                                 true, a, x_hi, xs_hi);
             a.corun = n_parts > 1;
+            a.w_t = st.w_t; a.ws_t = st.w_s_t;
             if (rc == HAWQ_OK) rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
             break;
         }
