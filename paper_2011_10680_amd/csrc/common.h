@@ -44,7 +44,7 @@ struct ConvArgs {
     // into 64-channel x 64-byte blocks, rows past K zero -- so that one K-step of a channel tile is contiguous memory
     const void *w_t, *ws_t;
     // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
-    // that take a whole CU's LDS for one workgroup are avoided, they would keep the other stream's workgroups off that CU
+    // meant for a launch that is alone (small tiles with a deep LDS ring when there are few tiles) are not chosen
     int32_t corun;
 };
 

@@ -32,7 +32,7 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // Minimum waves per SIMD the register allocation must leave room for, by the wave's share of the tile:
 // 2 for 64x64 per wave (64 accumulator registers per lane), 3-4 for 64x32, 6 for 32x32 (the latency-bound
 // shapes live on occupancy).
-// NBUF: LDS buffers in the operand ring (4, or 8 for the LDS-DMA path when one workgroup has a CU to itself)
+// NBUF: LDS buffers in the operand ring (4, or 8 for the 64x64 tile of the LDS-DMA path: few tiles, long reductions)
 // DUALM != 0: block output with a convolution on both branches (Section 3.3's residual equation with two INT32
 // accumulators, Figure 2): after the main convolution's K-steps the same pipeline runs on through the K-steps of the 1x1
 // shortcut convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds
@@ -597,7 +597,7 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s, bool de
     const uint32_t n_ctiles = (a.K + BC - 1) / BC;
     const uint32_t n_mtiles = (a.M + BP - 1) / BP;
     const uint32_t nblocks = n_ctiles * n_mtiles;
-    if constexpr ((BC == 128 && BP == 128 && WC == 4) || (BC == 64 && BP == 64)) {
+    if constexpr (BC == 64 && BP == 64) {
         if (deep && !is4(a.x_dt)) {
             conv_mfma_kernel<BC, BP, WC, WP, false, 8><<<nblocks, WC * WP * 64, 0, s>>>(a, n_ctiles, nblocks, vec);
             return check_launch();
@@ -634,15 +634,16 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     // per-channel parameter read in the epilogue serves two pixels); 64-channel layers take 64x128,
     // tiny problems 64x64.
     if (a.K >= 128 && a.M >= 1024) {
-        // At most one workgroup per CU and a long reduction (the 7x7 layers of a ResNet at batch 128): nothing
-        // else on the CU hides a late operand, and the weights come cold from HBM, so the ring is eight buffers
-        // deep there (operands requested seven K-steps ahead instead of three).  A small gain only: the 3x3
-        // 512 -> 512 layer takes 19.9 us with weights resident in cache, 27.6 us with cold weights and the ring of
-        // four, 26.2 us with the ring of eight.
         const int64_t nblocks = (int64_t)((a.K + 127) / 128) * ((a.M + 127) / 128);
         const int steps = a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64));
-        // (not when another stream's kernels share the chip: eight buffers are 142 KB of a CU's 160 KB of LDS)
-        return launch_cfg<128, 128, 4, 2>(a, vec, s, nblocks <= 256 && steps >= 16 && !a.corun);
+        // Few tiles and a long reduction (the 7x7 layers of a ResNet at batch 64: 100 tiles of 128x128 for 256 CUs, 72
+        // K-steps): every workgroup is alone on its CU and advances one memory latency per ring depth.  Quarter-size
+        // tiles put a workgroup on every CU, with the ring of eight (20.0 -> 17.3 us for 7x7 3x3 512 -> 512 at batch 64).
+        // Not when another stream's kernels share the chip: they fill the idle CUs better (measured).
+        if (!a.corun && a.K >= 512 && nblocks <= 112 && steps >= 32) return launch_cfg<64, 64, 2, 2>(a, vec, s, true);
+        // (A ring of eight for the 128x128 tile, for launches with at most one workgroup per CU, paid off while the
+        // weights came as 64-byte pieces; with the blocked copy it measures the same or slower, and it is gone.)
+        return launch_cfg<128, 128, 4, 2>(a, vec, s);
     }
     if (a.M >= 4096) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     // a few small tiles with a long reduction (the fully connected layer: 32 tiles x 32 K-steps at batch 128) advance one
