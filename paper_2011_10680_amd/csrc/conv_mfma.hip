@@ -587,6 +587,15 @@ hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s) {
     const uint32_t n_ctiles = (a.K + 127) / 128, n_mtiles = (a.M + 127) / 128;
     // four waves of 64 channels x 64 pixels: two accumulator sets of that size need the register budget of two waves per
     // SIMD (the eight-wave form would spill inside the K loop, and a reload there waits for every operand in flight)
+    // few tiles, long reduction, the chip to itself: quarter-size tiles (see launch_conv_mfma; 40.4 -> 36.6 us for the 7x7
+    // 3x3 512 -> 512 + 1x1 256 -> 512 block output at batch 64; a ring of eight changes nothing here)
+    const int steps = a.R * a.S * (a.C / 64) + a.Cs / 64;
+    if (!a.corun && a.K >= 512 && n_ctiles * n_mtiles <= 112 && steps >= 32) {
+        const uint32_t nc = (a.K + 63) / 64, nm = (a.M + 63) / 64;
+        if (a.mid_s8) conv_mfma_kernel<64, 64, 2, 2, false, 4, 2><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+        else conv_mfma_kernel<64, 64, 2, 2, false, 4, 1><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+        return check_launch();
+    }
     if (a.mid_s8) conv_mfma_kernel<128, 128, 2, 2, false, 4, 2><<<n_ctiles * n_mtiles, 256, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
     else conv_mfma_kernel<128, 128, 2, 2, false, 4, 1><<<n_ctiles * n_mtiles, 256, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
     return check_launch();

@@ -88,6 +88,8 @@ _SHAPES = [
     (2, 14, 128, 128, 3, 64, 2),      # ResNet18: 3x3 main branch (zero padding) + strided 1x1 shortcut
     (1, 9, 64, 192, 1, 128, 1),       # K not a multiple of the channel tile
     (5, 16, 256, 144, 3, 192, 1),     # ragged everything
+    (3, 7, 512, 512, 3, 256, 2),      # stage 4 of ResNet18: few tiles, 72 + 4 K-steps -> the quarter-size tiles
+    (2, 7, 512, 600, 3, 320, 2),      # the same with a ragged channel tile and five shortcut K-steps
 ]
 
 
