@@ -258,6 +258,9 @@ int32_t hawq_net_num_steps(const hawq_net *net);
  * Where step `step` leaves its output inside the workspace for batch N, and what it is
  * (valid until a later step reuses the slot; permanent with keep_activations).
  * name: at least 24 bytes.  dtype: hawq_dtype of the stored tensor.
+ * The offsets describe a batch that runs as one part (always the case with keep_activations); when
+ * hawq_net_split_first(net, N) is not 0 the two parts have their own regions of the workspace, the first laid out
+ * as for a batch of that many images at the start, the second behind it.
  */
 hawq_status hawq_net_step_output(const hawq_net *net, int32_t N, int32_t step, char *name, size_t *offset,
                                  size_t *bytes, int32_t *dtype, int32_t *dims4 /* N,P,Q,K */);
