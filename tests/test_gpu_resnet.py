@@ -115,7 +115,7 @@ def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed
     hn.close()
 
 
-@pytest.mark.parametrize("arch,N,first", [(18, 13, 5), (50, 6, 4), (18, 9, 8)])
+@pytest.mark.parametrize("arch,N,first", [(18, 13, 5), (50, 6, 4), (18, 9, 8), (18, 100, 0)])   # (first = 0: the library's rule, 56 + 44)
 def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first):
     """A large batch runs as two parts on two streams.  Forced here at small sizes (odd parts, the second part's image,
     logits and workspace offsets): same bits as the unsplit forward and as the oracle; called on a side stream right
@@ -129,6 +129,7 @@ def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first):
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"], image_hw=64)
     try:
         hawq.hawq_tune_set_split(first)
+        assert hn.split_first(N) == (first if first else 56)
         ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
         ws.fill_(0xA5)
         side = torch.cuda.Stream()
