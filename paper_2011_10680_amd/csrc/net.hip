@@ -230,7 +230,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto &L = net->layers;
     const int nl = (int)L.size();
     if (n_layers != nl) { delete net; return HAWQ_ERR_SHAPE; }
-    auto fail = [&](hawq_status st) { delete net; return st; };
+    auto fail = [&](hawq_status st) { hawq_net_destroy(net); return st; };   // (frees whatever has been created so far)
 
     // ---- validate parameters (host data: ranges can be checked here) ----
     for (int i = 0; i < nl; ++i) {
@@ -355,17 +355,12 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     memcpy(&host[off_pb], pool_b, 4 * (size_t)c_last);
     memcpy(&host[off_pc], pool_c, (size_t)c_last);
     if (hipMalloc(&net->arena, total) != hipSuccess) return fail(HAWQ_ERR_DEVICE);
-    if (hipMemcpy(net->arena, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipFree(net->arena);
-        return fail(HAWQ_ERR_DEVICE);
-    }
+    if (hipMemcpy(net->arena, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) return fail(HAWQ_ERR_DEVICE);
     // second stream (default priority) and the events that order it against the caller's stream
     if (hipStreamCreateWithFlags(&net->aux_stream, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&net->fork_ev, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&net->join_ev, hipEventDisableTiming) != hipSuccess) {
-        hawq_net_destroy(net);
-        return HAWQ_ERR_DEVICE;
-    }
+        hipEventCreateWithFlags(&net->join_ev, hipEventDisableTiming) != hipSuccess)
+        return fail(HAWQ_ERR_DEVICE);
     const uint8_t *A = (const uint8_t *)net->arena;
 
     // ---- steps ----
