@@ -196,9 +196,13 @@ int g_split_override = 0;   // 0: rule below; -1: never split; n > 0: first part
 int split_first_part(const hawq_net *net, int N) {
     if (net->keep || !net->aux_stream) return 0;
     if (g_split_override < 0) return 0;
-    if (g_split_override > 0) return g_split_override < N ? g_split_override : 0;
-    if (N < 96) return 0;
-    return ((N / 2) + 7) & ~7;
+    int n1 = ((N / 2) + 7) & ~7;
+    if (g_split_override > 0) n1 = g_split_override;
+    else if (N < 96) return 0;
+    if (n1 >= N) return 0;
+    // the second part's images start n1 images into the batch: conv1's kernel wants that address 16-byte aligned
+    if (((size_t)n1 * net->hw * net->hw * 3) % 16 != 0) return 0;
+    return n1;
 }
 
 }  // namespace

@@ -115,21 +115,24 @@ def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed
     hn.close()
 
 
-@pytest.mark.parametrize("arch,N,first", [(18, 13, 5), (50, 6, 4), (18, 9, 8), (18, 100, 0)])   # (first = 0: the library's rule, 56 + 44)
-def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first):
+@pytest.mark.parametrize("arch,N,first,hw", [(18, 13, 5, 64), (50, 6, 4, 64), (18, 9, 8, 64),
+                                             (18, 100, 0, 64),    # first = 0: the library's rule, 56 + 44
+                                             (18, 100, 0, 34),    # the same at another image size
+                                             (18, 100, 0, 33)])   # odd image side: the second part would start misaligned -> one part
+def test_batch_split_over_two_streams_same_bits(hawq, arch, N, first, hw):
     """A large batch runs as two parts on two streams.  Forced here at small sizes (odd parts, the second part's image,
     logits and workspace offsets): same bits as the unsplit forward and as the oracle; called on a side stream right
     behind the copy that delivers the images, twice in a row with different images (the second call must not
     overtake the first on the library's own stream), and once more after the hook is reset."""
     import torch
-    net = wl.make_resnet(arch, seed=31 + N, image_hw=64, int32_shortcut=(arch == 50))
-    xa = wl.make_image_batch(3, N, image_hw=64)
-    xb = wl.make_image_batch(4, N, image_hw=64)
+    net = wl.make_resnet(arch, seed=31 + N, image_hw=hw, int32_shortcut=(arch == 50))
+    xa = wl.make_image_batch(3, N, image_hw=hw)
+    xb = wl.make_image_batch(4, N, image_hw=hw)
     want_a, want_b = onet.forward(net, xa), onet.forward(net, xb)
-    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"], image_hw=64)
+    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"], image_hw=hw)
     try:
         hawq.hawq_tune_set_split(first)
-        assert hn.split_first(N) == (first if first else 56)
+        assert hn.split_first(N) == (first if first else (0 if hw % 2 else 56))
         ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
         ws.fill_(0xA5)
         side = torch.cuda.Stream()
