@@ -1,6 +1,7 @@
 // Whole-network plan for the integer-only ResNet18 / ResNet50 forward (Figure 2, Section 3.3):
-// topology, storage rule for mixed precision, workspace slot assignment, parameter arena and the
-// launch sequence.  Host code only; the kernels live in the other translation units.
+// topology, storage rule for mixed precision, workspace slot assignment, parameter arena (weights also in the
+// implicit-GEMM kernel's blocked order) and the launch sequence (a large batch as two parts on two streams).
+// Host code only; the kernels live in the other translation units.
 #include <cstdio>
 #include <cstring>
 #include <string>
