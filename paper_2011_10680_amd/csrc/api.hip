@@ -86,7 +86,7 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     a.res = (const uint8_t *)residual; a.res_b = residual ? res_b : nullptr; a.res_c = residual ? res_c : nullptr;
     a.y = (uint8_t *)y;
     a.xs = nullptr; a.ws = nullptr; a.bias_s = nullptr; a.b_s = nullptr; a.c_s = nullptr;
-    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.w_t = nullptr; a.ws_t = nullptr;
+    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.w_t = nullptr; a.ws_t = nullptr; a.dual16 = 0;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.P = (int32_t)P; a.Q = (int32_t)Q; a.M = (int32_t)M;

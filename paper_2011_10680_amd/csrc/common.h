@@ -46,6 +46,9 @@ struct ConvArgs {
     // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
     // meant for a launch that is alone (small tiles with a deep LDS ring when there are few tiles) are not chosen
     int32_t corun;
+    // dual16 (two-convolution form, set by the network plan from host data): every (b, c) and (b_s, c_s) is in the narrow
+    // evaluation's range and |rq(acc + bias, b, c)| of the main branch cannot exceed 32767 for any input
+    int32_t dual16;
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }

@@ -38,6 +38,10 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // shortcut convolution (other tensors, same tile) into a second set of accumulators, and the epilogue rescales and adds
 // both (DUALM = 1) -- or first rounds the shortcut accumulator to the signed 8-bit value a separate transition layer would
 // have stored (DUALM = 2: the bits of the two-launch form without the tensor's round trip; see epilogue_tile_dual).
+// DUALM = 3 is DUALM = 1 for callers that know (from the weights and parameters, on the host) that the main branch's
+// rescaled term fits 16 bits and that every parameter is in the narrow range: when the main convolution is complete its
+// accumulators are rescaled at once and kept as packed 16-bit pairs, half the registers of a second accumulator set,
+// which is what lets this form run as eight waves like the plain kernel (see epilogue_tile_dual16).
 // PK (4-bit operands whose channel count is a multiple of 128): the packed bytes take the LDS-DMA path unchanged -- a
 // K-step is then one tap and 128 input channels, still 64 bytes per row -- and are split into nibbles only between the
 // LDS fragment read and the MFMA (see unpack_pk below): per multiply-accumulate half the operand traffic of the INT8
@@ -84,7 +88,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         else return lds7;
     };
     __shared__ ChanMain par_m[BC];
-    __shared__ ChanRes par_r[DUALM == 1 ? 1 : BC];
+    __shared__ ChanRes par_r[(DUALM == 1 || DUALM == 3) ? 1 : BC];
     __shared__ ChanMain par_s[DUAL ? BC : 1];   // the shortcut convolution's staged parameters
     // Per K-step addressing, tabulated once per workgroup: {weight offset, activation tap offset, r | s << 16}.
     // Deriving these in the loop costs each wave some twenty scalar instructions per step, and the one scalar
@@ -171,7 +175,10 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     }
 
     v16i acc[TP][TC];
-    v16i accm[DUAL ? TP : 1][DUAL ? TC : 1];   // two-convolution form: the finished main-branch accumulators
+    constexpr bool D16 = DUALM == 3;
+    // two-convolution form: the finished main-branch accumulators (D16: their rescaled values, two per register)
+    v16i accm[DUAL ? (D16 ? 1 : TP) : 1][DUAL ? (D16 ? (TP * TC + 1) / 2 : TC) : 1];
+    const int chl_early = wc * (BC / WC) + (lane >> 5) * 16 * TC;   // the lane's first channel within the tile (as in the epilogue)
 #pragma unroll
     for (int tp = 0; tp < TP; ++tp)
 #pragma unroll
@@ -442,7 +449,18 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
                 for (int tp = 0; tp < TP; ++tp)
 #pragma unroll
                     for (int tc = 0; tc < TC; ++tc) {
-                        accm[tp][tc] = acc[tp][tc];
+                        if constexpr (D16) {
+                            // t = rq(acc + bias, b, c) in the narrow evaluation (high word of acc * (b << (32-c)) + rounding)
+#pragma unroll
+                            for (int i = 0; i < 16; i += 2) {
+                                const ChanMain &p0 = par_m[chl_early + 16 * tc + i], &p1 = par_m[chl_early + 16 * tc + i + 1];
+                                const int32_t t0 = (int32_t)(((int64_t)acc[tp][tc][i] * (int64_t)p0.bs + p0.Rs) >> 32);
+                                const int32_t t1 = (int32_t)(((int64_t)acc[tp][tc][i + 1] * (int64_t)p1.bs + p1.Rs) >> 32);
+                                accm[0][(tp * TC + tc) / 2][((tp * TC + tc) % 2) * 8 + i / 2] = (int)(((uint32_t)t0 & 0xffffu) | ((uint32_t)t1 << 16));
+                            }
+                        } else {
+                            accm[tp][tc] = acc[tp][tc];
+                        }
 #pragma unroll
                         for (int i = 0; i < 16; ++i) acc[tp][tc][i] = 0;
                     }
@@ -526,7 +544,14 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             mm[tp] = m0 + wp * (BP / WP) + tp * 32 + rho;
             valid[tp] = mm[tp] < a.M;
         }
-        epilogue_tile_dual<TC, TP, 0, DUALM == 2>(a, par_m, par_s, par_r, mm, valid, k0, chl, accm, acc, wide);
+        if constexpr (D16) {
+            uint32_t t16[TP * TC * 8];
+#pragma unroll
+            for (int j = 0; j < TP * TC * 8; ++j) t16[j] = (uint32_t)accm[0][j / 16][j % 16];
+            epilogue_tile_dual16<TC, TP>(a, par_s, mm, valid, k0, chl, t16, acc);
+        } else {
+            epilogue_tile_dual<TC, TP, 0, DUALM == 2>(a, par_m, par_s, par_r, mm, valid, k0, chl, accm, acc, wide);
+        }
     } else {
     if (tile_epi) {
         int64_t mm[TP];
@@ -587,6 +612,17 @@ hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s) {
     const uint32_t n_ctiles = (a.K + 127) / 128, n_mtiles = (a.M + 127) / 128;
     // four waves of 64 channels x 64 pixels: two accumulator sets of that size need the register budget of two waves per
     // SIMD (the eight-wave form would spill inside the K loop, and a reload there waits for every operand in flight)
+    if (a.dual16 && !a.mid_s8) {
+        // the eight-wave form (the caller vouches for the 16-bit bound and the narrow parameters)
+        const int steps16 = a.R * a.S * (a.C / 64) + a.Cs / 64;
+        if (!a.corun && a.K >= 512 && n_ctiles * n_mtiles <= 112 && steps16 >= 32) {
+            const uint32_t nc = (a.K + 63) / 64, nm = (a.M + 63) / 64;
+            conv_mfma_kernel<64, 64, 2, 2, false, 4, 3><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+        } else {
+            conv_mfma_kernel<128, 128, 4, 2, false, 4, 3><<<n_ctiles * n_mtiles, 512, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
+        }
+        return check_launch();
+    }
     // few tiles, long reduction, the chip to itself: quarter-size tiles (see launch_conv_mfma; 40.4 -> 36.6 us for the 7x7
     // 3x3 512 -> 512 + 1x1 256 -> 512 block output at batch 64; a ring of eight changes nothing here)
     const int steps = a.R * a.S * (a.C / 64) + a.Cs / 64;

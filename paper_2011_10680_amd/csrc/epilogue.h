@@ -562,6 +562,62 @@ __device__ __forceinline__ void epilogue_lane(const ConvArgs &a, const LaneParam
 //   MID == true :  the shortcut accumulator first becomes the signed 8-bit tensor a separate transition layer would have
 //                  stored, sc = clamp(rq(accs + bias_s, b_s, c_s), -128, 127), and enters the sum as rq(sc, res_b, res_c)
 //                  (pr: staged res_b / res_c) -- bit for bit the result of the two-launch form, without the round trip.
+// The two-accumulator block output when the main branch's rescaled term is known (from the weights, on the host) to fit
+// 16 bits and every parameter is in the narrow evaluation's range: the caller has already turned the finished main
+// accumulators into t = rq(accm + bias, b, c) and keeps them as packed 16-bit pairs (t16[.][8 (tp*TC+tc) + i/2], low half
+// first), which frees half the registers of a second accumulator set.  y = clamp(t + rq(accs + bias_s, b_s, c_s)).
+template <int TC, int TP>
+__device__ __forceinline__ void epilogue_tile_dual16(const ConvArgs &a, const ChanMain *ps, const int64_t (&m)[TP],
+                                                     const bool (&valid)[TP], int k0, int chl,
+                                                     const uint32_t (&t16)[TP * TC * 8], const v16i (&accs)[TP][TC]) {
+    const bool y4 = is4(a.y_dt);
+    int32_t lo = a.lo, hi = a.hi;
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    static_for<0, TC>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        const int chg = k0 + chl + 16 * g;
+        if (chg >= a.K) return;
+        int32_t y[TP][16];
+        static_for<0, 16>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const ChanMain &p2 = ps[chl + 16 * g + i];
+            const int32_t bs2 = p2.bs;
+            const int64_t Rs2 = p2.Rs;
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) {
+                const uint32_t w = t16[8 * (tp * TC + g) + i / 2];
+                const int32_t t = (i & 1) ? ((int32_t)w >> 16) : (int32_t)(int16_t)(w & 0xffffu);
+                const int32_t v = t + (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                int32_t r;
+                asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+                y[tp][i] = r;
+            }
+        });
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            if (!valid[tp]) continue;
+            if (y4) {
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    w0 |= (uint32_t)y[tp][i] << (4 * i);
+                    w1 |= (uint32_t)y[tp][8 + i] << (4 * i);
+                }
+                *(uint2 *)(a.y + ((m[tp] * (int64_t)a.K + chg) >> 1)) = make_uint2(w0, w1);
+            } else {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 1], (uint32_t)y[tp][4 * q], 0x0c0c0400u);
+                    const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
+                    w[q] = t0 | t1;
+                }
+                *(uint4 *)(a.y + (m[tp] * (int64_t)a.K + chg)) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    });
+}
+
 // YMODE 0: plain global stores of the valid pixels; 2: every lane issues a buffer store (invalid pixels out of range).
 template <int TC, int TP, int YMODE = 0, bool MID = false>
 __device__ __forceinline__ void epilogue_tile_dual(const ConvArgs &a, const ChanMain *pm, const ChanMain *ps, const ChanRes *pr,

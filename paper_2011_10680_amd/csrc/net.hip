@@ -92,6 +92,7 @@ struct Step {
     hawq_conv_desc desc_s{};      // STEP_CONV_DUAL: the transition convolution (reads tensor `res`)
     const uint8_t *w_s = nullptr;             // ... its parameters
     const uint8_t *w_t = nullptr, *w_s_t = nullptr;   // the weights (and the shortcut's) in the implicit-GEMM kernel's blocked order
+    bool dual16 = false;                      // STEP_CONV_DUAL: the main branch's rescaled term provably fits 16 bits (see ConvArgs)
     const int32_t *bias_s = nullptr, *b_s = nullptr;
     const uint8_t *c_s = nullptr;
     bool raw = false;             // STEP_CONV: store the INT32 accumulator + bias, no requantisation
@@ -484,6 +485,22 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                 d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);   // (8-bit form: block_in_dt is HAWQ_U8)
                 st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
                 st.w_s_t = blocked(ds) ? A + off[ds].wt : nullptr;
+                {   // may the eight-wave kernel keep the main branch's rescaled term in 16 bits?  Worst case over all inputs.
+                    const int8_t *wm = (const int8_t *)&host[off[last].w];
+                    const int64_t row = (int64_t)L[last].R * L[last].S * L[last].C;
+                    auto narrow = [](int32_t b, int c) { return c <= 32 && ((int64_t)b >> (c - 1)) == 0; };
+                    bool ok = true;
+                    for (int k = 0; k < L[last].K && ok; ++k) {
+                        int64_t sum = 0;
+                        for (int64_t e = 0; e < row; ++e) sum += wm[k * row + e] < 0 ? -(int64_t)wm[k * row + e] : wm[k * row + e];
+                        const int64_t bias = lp[last].bias[k];
+                        const int64_t amax = (int64_t)act_hi(u_bits) * sum + (bias < 0 ? -bias : bias);
+                        const int c = lp[last].c[k];
+                        ok = narrow(lp[last].b[k], c) && narrow(lp[ds].b[k], lp[ds].c[k]) &&
+                             ((amax * (int64_t)lp[last].b[k]) >> c) + 2 <= 32767;
+                    }
+                    st.dual16 = ok;
+                }
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
                 st.bytes_per_image += (double)L[ds].P * L[ds].Q * L[ds].C;   // a strided 1x1 touches only the sampled pixels
@@ -715,6 +732,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                                 true, a, x_hi, xs_hi);
             a.corun = n_parts > 1;
             a.w_t = st.w_t; a.ws_t = st.w_s_t;
+            a.dual16 = st.dual16;
             if (rc == HAWQ_OK) rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
             break;
         }

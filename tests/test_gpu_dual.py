@@ -218,3 +218,27 @@ def test_network_batch_that_pairs_transition_and_last_convolution(hawq, int32_sc
     assert np.array_equal(onet.forward(net, x[:2]), want[:2])
     got, _, _ = _forward_gpu(hawq, net, x, False)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("arch", [18, 50])
+def test_network_int32_shortcuts_when_the_16_bit_form_does_not_apply(hawq, arch):
+    """All-8-bit networks normally run a transition block's two-accumulator launch in the eight-wave form that keeps the
+    main branch's rescaled term in 16 bits; the plan allows that only when a bound computed from the weights shows
+    the term fits.  A bias of 2^30 on a few channels of each block's last convolution breaks the bound (those outputs
+    saturate): the plan must fall back to the form with two full accumulator sets, same bits as the oracle."""
+    net = wl.make_resnet(arch, seed=2000 + arch, image_hw=64, int32_shortcut=True)
+    for l in net["layers"]:
+        if l["name"].endswith(".0.c2" if arch == 18 else ".0.c3"):
+            l["bias"] = l["bias"].copy()
+            l["bias"][0] = 1 << 30
+            l["bias"][5] = -(1 << 30)
+    x = wl.make_image_batch(11, 3, image_hw=64)
+    want = onet.forward(net, x)
+    import torch
+    hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"], image_hw=64)
+    ws = torch.empty(hn.workspace_bytes(3), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((3, 1000), dtype=torch.int32, device="cuda")
+    hn.hawq_forward_resnet(torch.from_numpy(x).cuda(), 3, logits, ws)
+    torch.cuda.synchronize()
+    hn.close()
+    assert np.array_equal(logits.cpu().numpy(), want)
