@@ -41,7 +41,8 @@ constexpr int kMaxSteps = 320;   // K-steps (R*S*C/64, plus the pipeline's run-o
 // DUALM = 3 is DUALM = 1 for callers that know (from the weights and parameters, on the host) that the main branch's
 // rescaled term fits 16 bits and that every parameter is in the narrow range: when the main convolution is complete its
 // accumulators are rescaled at once and kept as packed 16-bit pairs, half the registers of a second accumulator set,
-// which is what lets this form run as eight waves like the plain kernel (see epilogue_tile_dual16).
+// which is what lets this form run as eight waves like the plain kernel (see epilogue_tile_dual16).  DUALM = 4: the same
+// for the stored-shortcut arithmetic of DUALM = 2.
 // PK (4-bit operands whose channel count is a multiple of 128): the packed bytes take the LDS-DMA path unchanged -- a
 // K-step is then one tap and 128 input channels, still 64 bytes per row -- and are split into nibbles only between the
 // LDS fragment read and the MFMA (see unpack_pk below): per multiply-accumulate half the operand traffic of the INT8
@@ -88,7 +89,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
         else return lds7;
     };
     __shared__ ChanMain par_m[BC];
-    __shared__ ChanRes par_r[(DUALM == 1 || DUALM == 3) ? 1 : BC];
+    __shared__ ChanRes par_r[(DUALM == 1 || DUALM == 3) ? 1 : BC];   // (two-convolution forms: only the stored-shortcut ones use it)
     __shared__ ChanMain par_s[DUAL ? BC : 1];   // the shortcut convolution's staged parameters
     // Per K-step addressing, tabulated once per workgroup: {weight offset, activation tap offset, r | s << 16}.
     // Deriving these in the loop costs each wave some twenty scalar instructions per step, and the one scalar
@@ -175,7 +176,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     }
 
     v16i acc[TP][TC];
-    constexpr bool D16 = DUALM == 3;
+    constexpr bool D16 = DUALM >= 3;
     // two-convolution form: the finished main-branch accumulators (D16: their rescaled values, two per register)
     v16i accm[DUAL ? (D16 ? 1 : TP) : 1][DUAL ? (D16 ? (TP * TC + 1) / 2 : TC) : 1];
     const int chl_early = wc * (BC / WC) + (lane >> 5) * 16 * TC;   // the lane's first channel within the tile (as in the epilogue)
@@ -348,7 +349,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
     // hot epilogue: 8-bit / 4-bit requantised outputs with whole 16-channel groups
     const bool tile_epi = vec_epilogue && a.b != nullptr && a.y_dt != HAWQ_S32;
     int wide = 0;
-    if constexpr (DUAL) wide = stage_params_dual(a, k0, BC, par_m, par_s, DUALM == 2 ? par_r : nullptr);
+    if constexpr (DUAL) wide = stage_params_dual(a, k0, BC, par_m, par_s, (DUALM == 2 || DUALM == 4) ? par_r : nullptr);
     else if (tile_epi) wide = stage_params(a, k0, BC, par_m, par_r);
     // the lane's shortcut bytes are fetched now, a whole K loop ahead of their use in the epilogue
     uint32_t resw[TP][TC][4] = {};
@@ -548,7 +549,7 @@ conv_mfma_kernel(const ConvArgs a, const uint32_t n_ctiles, const uint32_t nbloc
             uint32_t t16[TP * TC * 8];
 #pragma unroll
             for (int j = 0; j < TP * TC * 8; ++j) t16[j] = (uint32_t)accm[0][j / 16][j % 16];
-            epilogue_tile_dual16<TC, TP>(a, par_s, mm, valid, k0, chl, t16, acc);
+            epilogue_tile_dual16<TC, TP, DUALM == 4>(a, par_s, par_r, mm, valid, k0, chl, t16, acc);
         } else {
             epilogue_tile_dual<TC, TP, 0, DUALM == 2>(a, par_m, par_s, par_r, mm, valid, k0, chl, accm, acc, wide);
         }
@@ -612,12 +613,15 @@ hawq_status launch_conv_mfma_dual(const ConvArgs &a, hipStream_t s) {
     const uint32_t n_ctiles = (a.K + 127) / 128, n_mtiles = (a.M + 127) / 128;
     // four waves of 64 channels x 64 pixels: two accumulator sets of that size need the register budget of two waves per
     // SIMD (the eight-wave form would spill inside the K loop, and a reload there waits for every operand in flight)
-    if (a.dual16 && !a.mid_s8) {
+    if (a.dual16) {
         // the eight-wave form (the caller vouches for the 16-bit bound and the narrow parameters)
         const int steps16 = a.R * a.S * (a.C / 64) + a.Cs / 64;
         if (!a.corun && a.K >= 512 && n_ctiles * n_mtiles <= 112 && steps16 >= 32) {
             const uint32_t nc = (a.K + 63) / 64, nm = (a.M + 63) / 64;
-            conv_mfma_kernel<64, 64, 2, 2, false, 4, 3><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+            if (a.mid_s8) conv_mfma_kernel<64, 64, 2, 2, false, 4, 4><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+            else conv_mfma_kernel<64, 64, 2, 2, false, 4, 3><<<nc * nm, 256, 0, s>>>(a, nc, nc * nm, 1);
+        } else if (a.mid_s8) {
+            conv_mfma_kernel<128, 128, 4, 2, false, 4, 4><<<n_ctiles * n_mtiles, 512, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
         } else {
             conv_mfma_kernel<128, 128, 4, 2, false, 4, 3><<<n_ctiles * n_mtiles, 512, 0, s>>>(a, n_ctiles, n_ctiles * n_mtiles, 1);
         }

@@ -565,14 +565,15 @@ __device__ __forceinline__ void epilogue_lane(const ConvArgs &a, const LaneParam
 // The two-accumulator block output when the main branch's rescaled term is known (from the weights, on the host) to fit
 // 16 bits and every parameter is in the narrow evaluation's range: the caller has already turned the finished main
 // accumulators into t = rq(accm + bias, b, c) and keeps them as packed 16-bit pairs (t16[.][8 (tp*TC+tc) + i/2], low half
-// first), which frees half the registers of a second accumulator set.  y = clamp(t + rq(accs + bias_s, b_s, c_s)).
-template <int TC, int TP>
-__device__ __forceinline__ void epilogue_tile_dual16(const ConvArgs &a, const ChanMain *ps, const int64_t (&m)[TP],
+// first), which frees half the registers of a second accumulator set.  y = clamp(t + rq(accs + bias_s, b_s, c_s)); MID: the
+// stored-shortcut arithmetic, y = clamp(t + rq(clamp(rq(accs + bias_s, b_s, c_s), -128, 127), res_b, res_c)).
+template <int TC, int TP, bool MID = false>
+__device__ __forceinline__ void epilogue_tile_dual16(const ConvArgs &a, const ChanMain *ps, const ChanRes *pr, const int64_t (&m)[TP],
                                                      const bool (&valid)[TP], int k0, int chl,
                                                      const uint32_t (&t16)[TP * TC * 8], const v16i (&accs)[TP][TC]) {
     const bool y4 = is4(a.y_dt);
-    int32_t lo = a.lo, hi = a.hi;
-    asm volatile("" : "+v"(lo), "+v"(hi));
+    int32_t lo = a.lo, hi = a.hi, m128 = -128, p127 = 127;
+    asm volatile("" : "+v"(lo), "+v"(hi), "+v"(m128), "+v"(p127));
     static_for<0, TC>([&](auto gc) {
         constexpr int g = decltype(gc)::value;
         const int chg = k0 + chl + 16 * g;
@@ -583,11 +584,19 @@ __device__ __forceinline__ void epilogue_tile_dual16(const ConvArgs &a, const Ch
             const ChanMain &p2 = ps[chl + 16 * g + i];
             const int32_t bs2 = p2.bs;
             const int64_t Rs2 = p2.Rs;
+            ChanRes p3 = ChanRes{0, 1, 1, 0};
+            if (MID) p3 = pr[chl + 16 * g + i];
 #pragma unroll
             for (int tp = 0; tp < TP; ++tp) {
                 const uint32_t w = t16[8 * (tp * TC + g) + i / 2];
                 const int32_t t = (i & 1) ? ((int32_t)w >> 16) : (int32_t)(int16_t)(w & 0xffffu);
-                const int32_t v = t + (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                int32_t sc = (int32_t)(((int64_t)accs[tp][g][i] * (int64_t)bs2 + Rs2) >> 32);
+                if (MID) {
+                    int32_t s8;
+                    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(s8) : "v"(sc), "v"(m128), "v"(p127));
+                    sc = (__mul24(s8, p3.rb) + p3.rround) >> p3.rc;
+                }
+                const int32_t v = t + sc;
                 int32_t r;
                 asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
                 y[tp][i] = r;

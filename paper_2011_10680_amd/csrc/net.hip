@@ -92,7 +92,7 @@ struct Step {
     hawq_conv_desc desc_s{};      // STEP_CONV_DUAL: the transition convolution (reads tensor `res`)
     const uint8_t *w_s = nullptr;             // ... its parameters
     const uint8_t *w_t = nullptr, *w_s_t = nullptr;   // the weights (and the shortcut's) in the implicit-GEMM kernel's blocked order
-    bool dual16 = false;                      // STEP_CONV_DUAL: the main branch's rescaled term provably fits 16 bits (see ConvArgs)
+    bool dual16 = false;   // two-convolution launches (STEP_CONV_DUAL, fused pairs): the main branch's rescaled term provably fits 16 bits
     const int32_t *bias_s = nullptr, *b_s = nullptr;
     const uint8_t *c_s = nullptr;
     bool raw = false;             // STEP_CONV: store the INT32 accumulator + bias, no requantisation
@@ -388,6 +388,25 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     };
     auto reader_bits_after = [&](int i) { const int j = reader_after(i); return j < 0 ? 8 : lp[j].bits; };
     auto reader_dt_after = [&](int i) { const int j = reader_after(i); return j < 0 ? (int)HAWQ_U8 : cont_dt(j); };
+    // May the eight-wave two-accumulator kernel keep the main branch's rescaled term in 16 bits?  Worst case over all
+    // inputs, from the host copies: every multiplier in the narrow evaluation's range and, per output channel,
+    // (in_max sum|w| + |bias|) b / 2^c below 32767.  with_res: the stored-shortcut form, whose second rescaling counts too.
+    auto fits16 = [&](int last, int ds, int in_bits_main, bool with_res) {
+        const int8_t *wm = (const int8_t *)&host[off[last].w];
+        const int64_t row = (int64_t)L[last].R * L[last].S * L[last].C;
+        auto narrow = [](int32_t b, int c) { return c >= 1 && c <= 32 && ((int64_t)b >> (c - 1)) == 0; };
+        for (int k = 0; k < L[last].K; ++k) {
+            int64_t sum = 0;
+            for (int64_t e = 0; e < row; ++e) sum += wm[k * row + e] < 0 ? -(int64_t)wm[k * row + e] : wm[k * row + e];
+            const int64_t bias = lp[last].bias[k];
+            const int64_t amax = (int64_t)act_hi(in_bits_main) * sum + (bias < 0 ? -bias : bias);
+            const int c = lp[last].c[k];
+            if (!narrow(lp[last].b[k], c) || !narrow(lp[ds].b[k], lp[ds].c[k])) return false;
+            if (((amax * (int64_t)lp[last].b[k]) >> c) + 2 > 32767) return false;
+            if (with_res && (lp[last].res_c[k] > 31 || lp[last].res_b[k] >= (1 << 22))) return false;
+        }
+        return true;
+    };
     auto conv_step = [&](int i, int in_t, int in_dt, int in_hi, int res_t, int res_dt, int out_bits, int out_dt, bool signed_out,
                          bool relu, bool raw = false) {
         Step st;
@@ -485,22 +504,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                 d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);   // (8-bit form: block_in_dt is HAWQ_U8)
                 st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
                 st.w_s_t = blocked(ds) ? A + off[ds].wt : nullptr;
-                {   // may the eight-wave kernel keep the main branch's rescaled term in 16 bits?  Worst case over all inputs.
-                    const int8_t *wm = (const int8_t *)&host[off[last].w];
-                    const int64_t row = (int64_t)L[last].R * L[last].S * L[last].C;
-                    auto narrow = [](int32_t b, int c) { return c <= 32 && ((int64_t)b >> (c - 1)) == 0; };
-                    bool ok = true;
-                    for (int k = 0; k < L[last].K && ok; ++k) {
-                        int64_t sum = 0;
-                        for (int64_t e = 0; e < row; ++e) sum += wm[k * row + e] < 0 ? -(int64_t)wm[k * row + e] : wm[k * row + e];
-                        const int64_t bias = lp[last].bias[k];
-                        const int64_t amax = (int64_t)act_hi(u_bits) * sum + (bias < 0 ? -bias : bias);
-                        const int c = lp[last].c[k];
-                        ok = narrow(lp[last].b[k], c) && narrow(lp[ds].b[k], lp[ds].c[k]) &&
-                             ((amax * (int64_t)lp[last].b[k]) >> c) + 2 <= 32767;
-                    }
-                    st.dual16 = ok;
-                }
+                st.dual16 = fits16(last, ds, u_bits, false);
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
                 st.bytes_per_image += (double)L[ds].P * L[ds].Q * L[ds].C;   // a strided 1x1 touches only the sampled pixels
@@ -536,6 +540,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         if (ds_step >= 0 && !net->keep && is8(last) && is8(ds)) {
             net->steps[ds_step].pair_last = (int)net->steps.size() - 1;
             net->steps.back().pair_ds = ds_step;
+            net->steps.back().dual16 = fits16(last, ds, u_bits, true);
         }
         in_bits = out_bits;
         li = j;
@@ -676,6 +681,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             a.mid_s8 = 1; a.res_b = l.res_b; a.res_c = l.res_c;
             a.corun = n_parts > 1;
             a.w_t = l.w_t; a.ws_t = d.w_t;
+            a.dual16 = l.dual16;
             if (st.pair_last >= 0) {
                 if (pair_runs_fused(net, N, (int)s) && (conv_pws_dual_eligible(a, x_hi, xs_hi) || conv_mfma_dual_eligible(a, x_hi, xs_hi))) {
                     deferred[s] = 1;

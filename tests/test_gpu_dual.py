@@ -220,13 +220,13 @@ def test_network_batch_that_pairs_transition_and_last_convolution(hawq, int32_sc
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("arch", [18, 50])
-def test_network_int32_shortcuts_when_the_16_bit_form_does_not_apply(hawq, arch):
+@pytest.mark.parametrize("arch,int32_sc", [(18, True), (50, True), (50, False)])
+def test_network_int32_shortcuts_when_the_16_bit_form_does_not_apply(hawq, arch, int32_sc):
     """All-8-bit networks normally run a transition block's two-accumulator launch in the eight-wave form that keeps the
     main branch's rescaled term in 16 bits; the plan allows that only when a bound computed from the weights shows
     the term fits.  A bias of 2^30 on a few channels of each block's last convolution breaks the bound (those outputs
     saturate): the plan must fall back to the form with two full accumulator sets, same bits as the oracle."""
-    net = wl.make_resnet(arch, seed=2000 + arch, image_hw=64, int32_shortcut=True)
+    net = wl.make_resnet(arch, seed=2000 + arch, image_hw=64, int32_shortcut=int32_sc)   # (False: the stored-shortcut pairs)
     for l in net["layers"]:
         if l["name"].endswith(".0.c2" if arch == 18 else ".0.c3"):
             l["bias"] = l["bias"].copy()
