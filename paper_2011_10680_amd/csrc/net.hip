@@ -174,10 +174,11 @@ bool pair_runs_fused(const hawq_net *net, int N, int ds_step) {
     const Step &d = net->steps[ds_step];
     if (d.pair_last < 0 || net->keep) return false;
     (void)N;
-    // A 3x3 main convolution (ResNet18) runs faster as two launches: the two-accumulator kernel has only the four-wave
-    // form, a third slower per multiply-accumulate than the plain kernel, and a 3x3 convolution is all multiply-accumulates
-    // (7x7, 512 -> 512 at batch 64: 37 us as one launch, 8 + 18 us as two; ResNet18 batch 64 189 k -> 201 k images/s).
-    if (net->steps[d.pair_last].desc.R == 3) return false;
+    // A 3x3 main convolution (ResNet18) in the four-wave two-accumulator kernel runs slower than as two launches: that
+    // kernel is a third slower per multiply-accumulate than the plain one, and a 3x3 convolution is all
+    // multiply-accumulates (7x7, 512 -> 512 at batch 64: 37 us as one launch, 8 + 18 us as two).  One launch only where
+    // the eight-wave 16-bit form applies (ResNet18 batch 64, stored form: 189 k four-wave, 202 k two launches, 210 k).
+    if (net->steps[d.pair_last].desc.R == 3 && !net->steps[d.pair_last].dual16) return false;
     return true;   // 8-bit operands on both branches (checked when the plan was made): one of the two-convolution kernels applies
 }
 
