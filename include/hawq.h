@@ -235,7 +235,9 @@ hawq_status hawq_net_layer_info(int32_t arch, int32_t image_hw, int32_t num_clas
 /*
  * Build a network: validates the parameters (here b and c are host data, so 0 <= b < 2^31 and
  * 1 <= c <= 62 ARE checked -> HAWQ_ERR_RANGE), allocates one device arena, uploads weights
- * (conv1 re-tiled for its kernel) and parameters.  pool_b / pool_c: [C_last] host arrays of
+ * (conv1 re-tiled for its kernel; every other layer also in the blocked order the implicit-GEMM kernel reads, so the
+ * arena holds about twice the weights' size) and parameters, and creates the second stream and two events that
+ * hawq_forward_resnet uses for large batches.  pool_b / pool_c: [C_last] host arrays of
  * the average pool's dyadic multiplier.  keep_activations != 0 gives every layer's output its own
  * workspace slot (for layer-by-layer comparison) instead of reusing buffers.
  * Synchronous; call outside any timed region.  Free with hawq_net_destroy.
