@@ -31,6 +31,8 @@ WORKLOADS = {
     "resnet50_mixed_b256": dict(arch=50, batch=256, mixed=True, seed=1004),
     "resnet50_int4_b128": dict(arch=50, batch=128, mixed="all4", seed=1005),
     "resnet50_int8_b128_stored": dict(arch=50, batch=128, mixed=False, seed=1003),
+    "resnet50_int8_b256_stored": dict(arch=50, batch=256, mixed=False, seed=1004),   # the all-INT8 twin of resnet50_mixed_b256
+    "resnet50_int4_b256": dict(arch=50, batch=256, mixed="all4", seed=1004),
     "resnet18_int8_b64_stored": dict(arch=18, batch=64, mixed=False, seed=1002),
 }
 
