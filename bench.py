@@ -142,8 +142,9 @@ def module_ops(hawq, torch, steps, warmup):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    # (a forward is ~1 ms: a few dozen steps end before clocks and caches have settled and read ~3 % low)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="resnet50_int8_b128", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-images", type=int, default=256, help="images in the CPU-oracle baseline sample (0: skip)")
     ap.add_argument("--report", default=None, help="optional file for the per-layer table (JSON)")
