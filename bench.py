@@ -93,7 +93,6 @@ def conv_sweep(hawq, torch, wl, np):
         ops = 2.0 * N * P * Q * K * R * S * C
         return dict(N=N, H=H, W=W, C=C, K=K, R=R, stride=stride, bits=bits, us=round(us, 2), tops=round(ops / us / 1e6, 1),
                     frac_mfma_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
-    loop_peak = hawq.hawq_probe_mfma_peak()      # TOP/s of a register-only INT8 MFMA loop on this device
     rows = []
     for N in (1, 128):
         rows.append(dict(config="single 3x3 layer", **run(N, 56, 56, 64, 64, 3, 3, 1, 1, 8, 1000)))
@@ -101,6 +100,7 @@ def conv_sweep(hawq, torch, wl, np):
         for name, N, H, W, C, K, R, S, stride, pad in wl.int4_sweep_shapes(batch):
             for bits in (4, 8):
                 rows.append(dict(config="sweep " + name, **run(N, H, W, C, K, R, S, stride, pad, bits, 1001)))
+    loop_peak = hawq.hawq_probe_mfma_peak(20000)   # TOP/s of a register-only INT8 MFMA loop on this device (now warm)
     for r in rows:
         r["frac_mfma_loop_peak"] = round(r["tops"] / loop_peak, 4)
     return {"workload": "single-layer configurations (event-timed launches include ~2 us of launch overhead)",
@@ -220,7 +220,7 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
-    loop_peak = hawq.hawq_probe_mfma_peak()
+    loop_peak = hawq.hawq_probe_mfma_peak(20000)
     # per-launch device times (HIP events recorded by the library on the same stream), median of a few passes
     reps = max(3, min(10, args.steps))
     per = np.array([hn.hawq_forward_resnet_timed(x, N, logits, ws, stream) for _ in range(reps)])
