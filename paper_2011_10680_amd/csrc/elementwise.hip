@@ -278,60 +278,74 @@ pool_sum_kernel(const int64_t units, const int H, const int W, const int C, cons
     }
 }
 
+// patch of output pixels per thread (measured at 128 x 35 x 35 x 288 INT32: 4x4 73.8 us, 4x8 76.8, 8x4 77.4, 8x8 78.2;
+// one row of eight, the previous form, 117.6 us)
+#define POOL_QT 4
+#define POOL_PT 4
 // fast path for the Inception pooling branch: 3x3 / stride 1 / pad 1 on INT32 (or unsigned 8-bit) data, C % 4 == 0.  One
-// thread = 4 channels of 8 adjacent output pixels of a row: it adds the three in-image rows of the 10 input columns under
-// them once (column sums, 30 loads) and every output is the sum of three adjacent column sums -- 3.75 loads per output
-// instead of 9, which is what the vector-memory path, not HBM, limits in the general kernel.
-template <bool X32>
+// thread = 4 channels of a QT-wide, PT-high patch of output pixels.  It walks the PT + 2 input rows under the patch once:
+// per row QT + 2 loads and the QT horizontal three-sums; an output row is the sum of the last three rows' horizontal sums
+// (kept in a ring of three).  (PT + 2)(QT + 2) loads for PT QT outputs -- 2.25 per output at 4 x 4 instead of 9, which is
+// what the vector-memory path, not HBM, limits in the general kernel.
+template <bool X32, int QT, int PT>
 __global__ void __launch_bounds__(256)
 pool_sum3x3_kernel(const int64_t units, const int H, const int W, const int C, const int y_dt, const void *__restrict__ x,
                    const int32_t *__restrict__ b, const uint8_t *__restrict__ c, const int lo, const int hi, void *__restrict__ y) {
-    constexpr int QT = 8;
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= units) return;
-    const int cg = C / 4, qb = (W + QT - 1) / QT;
+    const int cg = C / 4, qb = (W + QT - 1) / QT, pb = (H + PT - 1) / PT;
     const int k0 = (int)(u % cg) * 4;
     int64_t t = u / cg;
     const int q0 = (int)(t % qb) * QT; t /= qb;
-    const int p = (int)(t % H);
-    const int n = (int)(t / H);
-    int32_t col[QT + 2][4];
-#pragma unroll
-    for (int j = 0; j < QT + 2; ++j) col[j][0] = col[j][1] = col[j][2] = col[j][3] = 0;
-#pragma unroll
-    for (int r = 0; r < 3; ++r) {
-        const int ih = p - 1 + r;
-        if (ih < 0 || ih >= H) continue;
-#pragma unroll
-        for (int j = 0; j < QT + 2; ++j) {
-            const int iw = q0 - 1 + j;
-            if (iw < 0 || iw >= W) continue;
-            const int64_t e = (((int64_t)n * H + ih) * W + iw) * C + k0;
-            if (X32) {
-                const v4i v = *(const v4i *)((const int32_t *)x + e);
-                col[j][0] += v[0]; col[j][1] += v[1]; col[j][2] += v[2]; col[j][3] += v[3];
-            } else {
-                const uint32_t v = *(const uint32_t *)((const uint8_t *)x + e);
-                col[j][0] += v & 0xff; col[j][1] += (v >> 8) & 0xff; col[j][2] += (v >> 16) & 0xff; col[j][3] += v >> 24;
-            }
-        }
-    }
+    const int p0 = (int)(t % pb) * PT;
+    const int n = (int)(t / pb);
     int32_t bb[4] = {0, 0, 0, 0}, cc[4] = {1, 1, 1, 1};
     if (b != nullptr)
         for (int j = 0; j < 4; ++j) { bb[j] = b[k0 + j]; cc[j] = c[k0 + j]; }
+    int32_t hs[3][QT][4];   // horizontal three-sums of the last three input rows
+    static_for<0, PT + 2>([&](auto rc) {
+        constexpr int rr = decltype(rc)::value;
+        constexpr int slot = rr % 3;
+        const int ih = p0 - 1 + rr;
+        int32_t v[QT + 2][4];
 #pragma unroll
-    for (int i = 0; i < QT; ++i) {
-        if (q0 + i >= W) break;
-        int32_t out[4];
-        for (int j = 0; j < 4; ++j) {
-            const int32_t sum = col[i][j] + col[i + 1][j] + col[i + 2][j];
-            out[j] = b != nullptr ? clamp64(rq64(sum, bb[j], cc[j]), lo, hi) : sum;
+        for (int j = 0; j < QT + 2; ++j) {
+            const int iw = q0 - 1 + j;
+            v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0;
+            if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+            const int64_t e = (((int64_t)n * H + ih) * W + iw) * C + k0;
+            if (X32) {
+                const v4i w4 = *(const v4i *)((const int32_t *)x + e);
+                v[j][0] = w4[0]; v[j][1] = w4[1]; v[j][2] = w4[2]; v[j][3] = w4[3];
+            } else {
+                const uint32_t w1 = *(const uint32_t *)((const uint8_t *)x + e);
+                v[j][0] = w1 & 0xff; v[j][1] = (w1 >> 8) & 0xff; v[j][2] = (w1 >> 16) & 0xff; v[j][3] = w1 >> 24;
+            }
         }
-        const int64_t o = (((int64_t)n * H + p) * W + q0 + i) * C + k0;
-        if (y_dt == HAWQ_S32) *(v4i *)((int32_t *)y + o) = (v4i){out[0], out[1], out[2], out[3]};
-        else if (is4(y_dt)) *(uint16_t *)((uint8_t *)y + (o >> 1)) = (uint16_t)((out[0] & 0xf) | ((out[1] & 0xf) << 4) | ((out[2] & 0xf) << 8) | ((out[3] & 0xf) << 12));
-        else ((uint32_t *)y)[o >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
-    }
+#pragma unroll
+        for (int i = 0; i < QT; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) hs[slot][i][j] = v[i][j] + v[i + 1][j] + v[i + 2][j];
+        if constexpr (rr >= 2) {
+            const int p = p0 + rr - 2;
+            if (p < H) {
+#pragma unroll
+                for (int i = 0; i < QT; ++i) {
+                    if (q0 + i >= W) break;
+                    int32_t out[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int32_t sum = hs[0][i][j] + hs[1][i][j] + hs[2][i][j];
+                        out[j] = b != nullptr ? clamp64(rq64(sum, bb[j], cc[j]), lo, hi) : sum;
+                    }
+                    const int64_t o = (((int64_t)n * H + p) * W + q0 + i) * C + k0;
+                    if (y_dt == HAWQ_S32) *(v4i *)((int32_t *)y + o) = (v4i){out[0], out[1], out[2], out[3]};
+                    else if (is4(y_dt)) *(uint16_t *)((uint8_t *)y + (o >> 1)) = (uint16_t)((out[0] & 0xf) | ((out[1] & 0xf) << 4) | ((out[2] & 0xf) << 8) | ((out[3] & 0xf) << 12));
+                    else ((uint32_t *)y)[o >> 2] = (out[0] & 0xff) | ((out[1] & 0xff) << 8) | ((out[2] & 0xff) << 16) | ((uint32_t)out[3] << 24);
+                }
+            }
+        }
+    });
 }
 
 hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, int sw, int ph, int pw, int x_dt, int y_dt,
@@ -340,12 +354,13 @@ hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, in
     const bool any4 = is4(x_dt) || is4(y_dt);
     if (R == 3 && S == 3 && sh == 1 && sw == 1 && ph == 1 && pw == 1 && C % 4 == 0 && (x_dt == HAWQ_S32 || x_dt == HAWQ_U8) &&
         (((uintptr_t)x | (uintptr_t)y) & 15) == 0) {
-        const int64_t units = (int64_t)N * H * ((W + 7) / 8) * (C / 4);
+        constexpr int QT = POOL_QT, PT = POOL_PT;
+        const int64_t units = (int64_t)N * ((H + PT - 1) / PT) * ((W + QT - 1) / QT) * (C / 4);
         if (units == 0) return HAWQ_OK;
         const int64_t blocks = (units + 255) / 256;
         if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
-        if (x_dt == HAWQ_S32) pool_sum3x3_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
-        else pool_sum3x3_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
+        if (x_dt == HAWQ_S32) pool_sum3x3_kernel<true, QT, PT><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
+        else pool_sum3x3_kernel<false, QT, PT><<<(uint32_t)blocks, 256, 0, s>>>(units, H, W, C, y_dt, x, b, c, lo, hi, y);
         return check_launch();
     }
     const int per = (C % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15) == 0) ? 4 : (any4 ? 2 : 1);
