@@ -70,7 +70,8 @@ def profiled_traffic(workload):
 def conv_sweep(hawq, torch, wl, np):
     """Single-layer configurations: the 56x56x64 3x3 layer (batch 1 as specified, batch 128 as a throughput companion) and
     the ResNet18-shaped 3x3 / strided / 1x1 sweep in INT4 and in INT8 (batch 8 as specified, and batch 128), seeded inputs
-    resident in HBM, median of 20 HIP-event timed launches after 5 warm-ups.  TOPS = 2 N P Q K R S C / t (logical MACs)."""
+    resident in HBM (weights as given and as the blocked copy of hawq_conv_block_weights), median of 20 HIP-event timed
+    launches after 5 warm-ups.  TOPS = 2 N P Q K R S C / t (logical MACs)."""
     def run(N, H, W, C, K, R, S, stride, pad, bits, seed):
         case = wl.conv_case(seed=seed, N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=bits)
         x_dt, w_dt = (hawq.U8, hawq.S8) if bits == 8 else (hawq.U4, hawq.S4)
@@ -81,6 +82,11 @@ def conv_sweep(hawq, torch, wl, np):
         dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         x, w, bias, b, c = dev(case["x"]), dev(case["w"]), dev(case["bias"]), dev(case["b"]), dev(case["c"])
         y = torch.empty((N, P, Q, K if bits == 8 else K // 2), dtype=torch.uint8, device="cuda")
+        nb = hawq.hawq_conv_blocked_weights_bytes(d)     # the weights also in the blocked order, made once outside the timing
+        if nb:
+            wb = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            hawq.hawq_conv_block_weights(d, w, wb)
+            d.w_blocked = wb.data_ptr()
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
         for _ in range(5):
             hawq.hawq_conv2d_int(d, x, w, bias, b, c, None, None, None, y)

@@ -70,6 +70,9 @@ typedef struct {
                                       Used by the overflow bound; HAWQ_U8 data with x_hi <= 127 (the
                                       post-ReLU 8-bit range of the workloads) runs on the signed INT8
                                       matrix cores, larger values take a slower exact kernel.   */
+    const void *w_blocked;         /* optional (NULL: none): device copy of the same weights made by
+                                      hawq_conv_block_weights; the implicit-GEMM kernel then reads it instead of w
+                                      (whole cache lines per fetch).  w is still required: other kernels read it. */
 } hawq_conv_desc;
 
 /*
@@ -113,6 +116,18 @@ hawq_status hawq_conv2d_dual_int(const hawq_conv_desc *desc, const void *x, cons
                                  const int32_t *b, const uint8_t *c, const hawq_conv_desc *desc_s, const void *xs,
                                  const void *ws, const int32_t *bias_s, const int32_t *b_s, const uint8_t *c_s, void *y,
                                  void *stream);
+
+/*
+ * Blocked copy of a layer's weights for hawq_conv2d_int / hawq_conv2d_dual_int (hawq_conv_desc::w_blocked): the
+ * [K][R*S*C] byte matrix cut into [ceil(K/64)][row bytes / 64][64 channels][64 bytes] blocks, rows past K zero, so that
+ * one reduction step of a 64- or 128-channel tile is contiguous memory.  Same integers, another order: results do not
+ * change.  hawq_conv_blocked_weights_bytes: size of the copy, 0 if the layer has none (8-bit weights need C % 64 == 0,
+ * packed 4-bit weights C % 128 == 0).  hawq_conv_block_weights: device to device, asynchronous on `stream`; w and
+ * w_blocked 16-byte aligned device pointers; HAWQ_ERR_UNSUPPORTED if the layer has no blocked form.  Call once per
+ * layer, outside the timed path.
+ */
+size_t hawq_conv_blocked_weights_bytes(const hawq_conv_desc *desc);
+hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, void *w_blocked, void *stream);
 
 /*
  * Quantised fully connected layer / GEMM -- the matrix-multiply form of Section 3.1:

@@ -23,7 +23,7 @@ class HawqError(RuntimeError):
 class ConvDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
-                 "x_dtype", "w_dtype", "y_dtype", "res_dtype", "relu", "y_lo", "y_hi", "x_hi")]
+                 "x_dtype", "w_dtype", "y_dtype", "res_dtype", "relu", "y_lo", "y_hi", "x_hi")] + [("w_blocked", ctypes.c_void_p)]
 
 
 class LayerParams(ctypes.Structure):
@@ -97,6 +97,10 @@ def load_library():
     lib.hawq_tune_set_tile.argtypes = [i32]
     lib.hawq_net_split_first.restype = i32
     lib.hawq_net_split_first.argtypes = [vp, i32]
+    lib.hawq_conv_blocked_weights_bytes.restype = ctypes.c_size_t
+    lib.hawq_conv_blocked_weights_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+    lib.hawq_conv_block_weights.restype = ctypes.c_int
+    lib.hawq_conv_block_weights.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
     lib.hawq_probe_mfma_peak.restype = ctypes.c_int
     lib.hawq_probe_mfma_peak.argtypes = [i32, ctypes.POINTER(ctypes.c_double)]
     lib.hawq_tune_set_split.restype = None
@@ -180,6 +184,15 @@ def hawq_concat_dyadic(n_pixels, branches, y_dt, y_lo, y_hi, y, stream=None):
 
 def hawq_tune_set_tile(tile):
     load_library().hawq_tune_set_tile(int(tile))
+
+
+def hawq_conv_blocked_weights_bytes(desc):
+    return int(load_library().hawq_conv_blocked_weights_bytes(ctypes.byref(desc)))
+
+
+def hawq_conv_block_weights(desc, w, w_blocked, stream=None):
+    _check(load_library().hawq_conv_block_weights(ctypes.byref(desc), _p(w), _p(w_blocked), _stream(stream)),
+           "hawq_conv_block_weights")
 
 
 def hawq_probe_mfma_peak(iters=4000):

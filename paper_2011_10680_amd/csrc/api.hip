@@ -86,7 +86,8 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     a.res = (const uint8_t *)residual; a.res_b = residual ? res_b : nullptr; a.res_c = residual ? res_c : nullptr;
     a.y = (uint8_t *)y;
     a.xs = nullptr; a.ws = nullptr; a.bias_s = nullptr; a.b_s = nullptr; a.c_s = nullptr;
-    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.w_t = nullptr; a.ws_t = nullptr; a.dual16 = 0;
+    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.ws_t = nullptr; a.dual16 = 0;
+    a.w_t = (d->w_blocked != nullptr && ((uintptr_t)d->w_blocked & 15) == 0) ? d->w_blocked : nullptr;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.P = (int32_t)P; a.Q = (int32_t)Q; a.M = (int32_t)M;
@@ -129,6 +130,7 @@ hawq_status make_dual_args(const hawq_conv_desc *d, const void *x, const void *w
     if (t.R != 1 || t.S != 1 || t.pad_h != 0 || t.pad_w != 0) return HAWQ_ERR_SHAPE;
     if (t.N != a.N || t.P != a.P || t.Q != a.Q || t.K != a.K) return HAWQ_ERR_SHAPE;
     a.xs = t.x; a.ws = t.w; a.bias_s = t.bias; a.b_s = t.b; a.c_s = t.c;
+    a.ws_t = t.w_t;      // (the shortcut's blocked weights, if its descriptor names them)
     a.Hs = t.H; a.Ws = t.W; a.Cs = t.C; a.stride_sh = t.stride_h; a.stride_sw = t.stride_w; a.xs_dt = t.x_dt; a.ws_dt = t.w_dt;
     return HAWQ_OK;
 }
@@ -143,6 +145,22 @@ hawq_status dispatch_conv_dual(const ConvArgs &a, int x_hi, int xs_hi, hipStream
 }  // namespace hawq
 
 extern "C" {
+
+size_t hawq_conv_blocked_weights_bytes(const hawq_conv_desc *desc) {
+    if (!desc || desc->K <= 0 || desc->R <= 0 || desc->S <= 0 || desc->C <= 0) return 0;
+    const bool four = hawq::is4(desc->w_dtype);
+    if (desc->C % (four ? 128 : 64) != 0) return 0;
+    const int64_t row = hawq::tensor_bytes((int64_t)desc->R * desc->S * desc->C, desc->w_dtype);
+    return (size_t)((desc->K + 63) / 64) * (size_t)row * 64;
+}
+
+hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, void *w_blocked, void *stream) {
+    if (!desc || !w || !w_blocked) return HAWQ_ERR_NULL;
+    if (hawq_conv_blocked_weights_bytes(desc) == 0) return HAWQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)w | (uintptr_t)w_blocked) & 15) return HAWQ_ERR_UNSUPPORTED;
+    const int64_t row = hawq::tensor_bytes((int64_t)desc->R * desc->S * desc->C, desc->w_dtype);
+    return hawq::launch_block_weights(w, w_blocked, desc->K, row, (hipStream_t)stream);
+}
 
 hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias, const int32_t *b,
                             const uint8_t *c, const void *residual, const int32_t *res_b, const uint8_t *res_c, void *y,

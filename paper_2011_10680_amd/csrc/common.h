@@ -165,6 +165,9 @@ hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, in
 hawq_status launch_concat_branch(int64_t n_pixels, int K, int Kt, int off, int q_dt, int y_dt, const void *q, const int32_t *b,
                                  const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
 
+// [K][row bytes] weights -> the implicit-GEMM kernel's blocked order (ConvArgs::w_t); row a multiple of 64
+hawq_status launch_block_weights(const void *w, void *w_blocked, int K, int64_t row, hipStream_t s);
+
 inline hawq_status check_launch() { return hipGetLastError() == hipSuccess ? HAWQ_OK : HAWQ_ERR_DEVICE; }
 
 }  // namespace hawq

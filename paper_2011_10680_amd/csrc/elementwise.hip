@@ -417,4 +417,29 @@ hawq_status launch_concat_branch(int64_t n_pixels, int K, int Kt, int off, int q
     return check_launch();
 }
 
+// ---- weights into the blocked order of the implicit-GEMM kernel: one thread per 16-byte chunk of the copy ----
+__global__ void __launch_bounds__(256)
+block_weights_kernel(const uint8_t *__restrict__ w, uint8_t *__restrict__ out, const int K, const int64_t row, const int64_t chunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= chunks) return;
+    const int64_t steps = row / 64;
+    const int ch = (int)(i & 3);
+    const int kk = (int)((i >> 2) & 63);
+    const int64_t blk = i >> 8;                  // (k / 64) * steps + step
+    const int64_t st = blk % steps;
+    const int k = (int)(blk / steps) * 64 + kk;
+    v4i v = {0, 0, 0, 0};
+    if (k < K) v = *(const v4i *)(w + (int64_t)k * row + st * 64 + ch * 16);
+    *(v4i *)(out + i * 16) = v;
+}
+
+hawq_status launch_block_weights(const void *w, void *w_blocked, int K, int64_t row, hipStream_t s) {
+    const int64_t chunks = (int64_t)((K + 63) / 64) * (row / 64) * 256;
+    if (chunks == 0) return HAWQ_OK;
+    const int64_t blocks = (chunks + 255) / 256;
+    if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
+    block_weights_kernel<<<(uint32_t)blocks, 256, 0, s>>>((const uint8_t *)w, (uint8_t *)w_blocked, K, row, chunks);
+    return check_launch();
+}
+
 }  // namespace hawq

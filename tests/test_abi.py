@@ -86,6 +86,25 @@ def test_conv_argument_validation_on_host(lib):
     assert lib.hawq_status_string(5).decode().lower().startswith("int32")
 
 
+def test_blocked_weight_copy_size_and_validation_on_host(lib):
+    """Size of the blocked copy (whole 64-channel blocks of 64-byte pieces) and the cases with none; the copy call fails
+    before any launch on null pointers, layers without a blocked form and misaligned pointers."""
+    import paper_2011_10680_amd as hawq
+    size = lambda **kw: lib.hawq_conv_blocked_weights_bytes(ctypes.byref(_desc(**kw)))
+    assert size(C=64, K=100) == 128 * 9 * 64
+    assert size(C=256, K=64, R=1, S=1, pad_h=0, pad_w=0) == 64 * 256
+    assert size(C=96) == 0 and size(C=64, x_dtype=hawq.U4, w_dtype=hawq.S4) == 0
+    assert size(C=128, K=65, x_dtype=hawq.U4, w_dtype=hawq.S4) == 128 * 9 * 64
+    assert lib.hawq_conv_blocked_weights_bytes(None) == 0
+    P = ctypes.c_void_p(4096)
+    d = _desc()
+    assert lib.hawq_conv_block_weights(ctypes.byref(d), None, P, None) == 1
+    assert lib.hawq_conv_block_weights(ctypes.byref(d), P, None, None) == 1
+    assert lib.hawq_conv_block_weights(None, P, P, None) == 1
+    assert lib.hawq_conv_block_weights(ctypes.byref(_desc(C=96)), P, P, None) == 6
+    assert lib.hawq_conv_block_weights(ctypes.byref(d), ctypes.c_void_p(4100), P, None) == 6
+
+
 def test_dual_conv_argument_validation_on_host(lib):
     import paper_2011_10680_amd as hawq
     P = ctypes.c_void_p(4096)

@@ -375,3 +375,39 @@ def test_gemm_fc_shape(hawq):
     want = oracle.gemm_int(x, w, bias, None, None, M=M, N=N, K=K, x_dt=oracle.U8, w_dt=oracle.S8, y_dt=oracle.S32)
     assert_same(y.cpu().numpy(), want)
     assert np.array_equal(want.astype(np.int64), x.astype(np.int64) @ w.astype(np.int64).T + bias)
+
+
+@pytest.mark.parametrize("shape", [(3, 14, 14, 256, 200, 3, 3, 1, 1, 8), (2, 28, 28, 128, 128, 3, 3, 2, 1, 8), (5, 9, 9, 1024, 96, 1, 1, 1, 0, 8),
+                                   (12, 28, 28, 128, 128, 3, 3, 1, 1, 4), (4, 14, 14, 256, 72, 3, 3, 1, 1, 4)])
+def test_blocked_weight_copy_gives_the_same_bits(hawq, shape):
+    """hawq_conv_block_weights + hawq_conv_desc::w_blocked: the implicit-GEMM kernel reads the blocked copy (ragged channel
+    tiles: rows past K are zero blocks), every other kernel ignores it.  Same output as without, and as the oracle."""
+    import torch
+    from gpu_util import run_conv_gpu, assert_same, to_dev
+    N, H, W, C, K, R, S, stride, pad, bits = shape
+    case = _scale_c(wl.conv_case(seed=sum(shape), N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride=stride, pad=pad, bits=bits), bits)
+    x_dt, w_dt = (hawq.U8, hawq.S8) if bits == 8 else (hawq.U4, hawq.S4)
+    y_hi = 127 if bits == 8 else 15
+    ref, want = run_conv_gpu(case, x_dt, w_dt, x_dt, y_hi=y_hi, x_hi=127 if bits == 8 else 0)
+    assert_same(ref, want, "plain weights %r" % (shape,))
+    d = hawq.ConvDesc(N=N, H=H, W=W, C=C, K=K, R=R, S=S, stride_h=stride, stride_w=stride, pad_h=pad, pad_w=pad, x_dtype=x_dt,
+                      w_dtype=w_dt, y_dtype=x_dt, res_dtype=hawq.U8, relu=1, y_lo=0, y_hi=y_hi, x_hi=127 if bits == 8 else 0)
+    nb = hawq.hawq_conv_blocked_weights_bytes(d)
+    row = R * S * C * bits // 8
+    assert nb == ((K + 63) // 64) * 64 * row
+    w = to_dev(case["w"])
+    wb = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda")
+    hawq.hawq_conv_block_weights(d, w, wb)
+    torch.cuda.synchronize()
+    # the copy against its definition: block (k / 64, step) holds 64 rows x 64 bytes
+    wh = case["w"].reshape(K, row).view(np.uint8) if case["w"].dtype != np.uint8 else case["w"].reshape(K, row)
+    blk = wb.cpu().numpy().reshape((K + 63) // 64, row // 64, 64, 64)
+    full = np.zeros((((K + 63) // 64) * 64, row), dtype=np.uint8)
+    full[:K] = wh
+    assert np.array_equal(blk, full.reshape(-1, 64, row // 64, 64).transpose(0, 2, 1, 3))
+    d.w_blocked = wb.data_ptr()
+    P, Q = case["P"], case["Q"]
+    y = torch.full((N, P, Q, K if bits == 8 else K // 2), 0x5A, dtype=torch.uint8, device="cuda")
+    hawq.hawq_conv2d_int(d, to_dev(case["x"]), w, to_dev(case["bias"]), to_dev(case["b"]), to_dev(case["c"]), None, None, None, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().reshape(-1), np.asarray(want).reshape(-1).view(np.uint8))
