@@ -536,6 +536,30 @@ conv_pws_dual_kernel(const ConvArgs a, const int n_ct, const int n_seq, const in
     const int PQ = a.P * a.Q;
     const int d_row = lane >> 2;
     const int d_chunk = (lane & 3) ^ ((d_row >> 2) & 3);
+    // Where a lane's shortcut fetch reads (image, row, column of its output pixel) is found by division once, for the wave's
+    // first group; successive calls of issue() are one sequence stride (32 n_seq pixels) apart, so the byte offset then
+    // advances by wave-uniform increments with two carries -- no division in the loop.
+    const int step_px = 32 * n_seq;
+    const int dn = step_px / PQ, drem = step_px - dn * PQ, dp = drem / a.Q, dq = drem - dp * a.Q;
+    const uint32_t row_b = (uint32_t)(a.stride_sh * a.Ws * a.Cs), col_b = (uint32_t)(a.stride_sw * a.Cs);
+    const uint32_t inc_q = (uint32_t)dq * col_b, inc_p = (uint32_t)dp * row_b;
+    const uint32_t inc_n = (uint32_t)dn * (uint32_t)(a.Hs * a.Ws * a.Cs);
+    const uint32_t wrap_q = row_b - (uint32_t)a.Q * col_b;                              // next row, first column
+    const uint32_t wrap_p = (uint32_t)(a.Hs * a.Ws * a.Cs) - (uint32_t)a.P * row_b;     // next image, first row
+    int s_p[DW], s_q[DW];
+    uint32_t s_off[DW];
+#pragma unroll
+    for (int j = 0; j < DW; ++j) {
+        const int inst = wave + 4 * j;
+        const int kc = inst >> 1, h = inst & 1;
+        const int mi = seq * 32 + h * 16 + d_row;
+        const int n = mi / PQ, pq = mi - n * PQ;
+        s_p[j] = pq / a.Q;
+        s_q[j] = pq - s_p[j] * a.Q;
+        s_off[j] = (uint32_t)(((n * a.Hs + s_p[j] * a.stride_sh) * a.Ws + s_q[j] * a.stride_sw) * a.Cs) +
+                   (uint32_t)((kc - KC1) * 64 + d_chunk * 16);
+    }
+    // (calls must come in the order of the walk below: grp = seq, seq + n_seq, seq + 2 n_seq, ...)
     auto issue = [&](int grp, uint8_t *xs) {
         const int64_t mbase = (int64_t)grp * 32;
 #pragma unroll
@@ -545,15 +569,14 @@ conv_pws_dual_kernel(const ConvArgs a, const int n_ct, const int n_seq, const in
             const bool main_branch = kc < KC1;      // wave-uniform
             const int64_t m = mbase + h * 16 + d_row;
             uint32_t off = kInvalid;
-            if (grp < n_groups && m < a.M) {
-                if (main_branch) {
-                    off = (uint32_t)m * (uint32_t)a.C + kc * 64 + d_chunk * 16;
-                } else {
-                    const int mi = (int)m;
-                    const int n = mi / PQ, pq = mi - n * PQ;
-                    const int p = pq / a.Q, q = pq - p * a.Q;
-                    off = (uint32_t)(((n * a.Hs + p * a.stride_sh) * a.Ws + q * a.stride_sw) * a.Cs) + (kc - KC1) * 64 + d_chunk * 16;
-                }
+            if (grp < n_groups && m < a.M)
+                off = main_branch ? (uint32_t)m * (uint32_t)a.C + kc * 64 + d_chunk * 16 : s_off[j];
+            if (!main_branch) {
+                s_q[j] += dq;
+                s_off[j] += inc_q + inc_p + inc_n;
+                if (s_q[j] >= a.Q) { s_q[j] -= a.Q; s_p[j] += 1; s_off[j] += wrap_q; }
+                s_p[j] += dp;
+                if (s_p[j] >= a.P) { s_p[j] -= a.P; s_off[j] += wrap_p; }
             }
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 (void *)(main_branch ? a.x : a.xs), 0,
