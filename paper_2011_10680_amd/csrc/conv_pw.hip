@@ -559,6 +559,8 @@ conv_pws_dual_kernel(const ConvArgs a, const int n_ct, const int n_seq, const in
         s_off[j] = (uint32_t)(((n * a.Hs + s_p[j] * a.stride_sh) * a.Ws + s_q[j] * a.stride_sw) * a.Cs) +
                    (uint32_t)((kc - KC1) * 64 + d_chunk * 16);
     }
+    const __amdgpu_buffer_rsrc_t rsrc_xm = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.N * a.H * a.W * a.C), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_xs = __builtin_amdgcn_make_buffer_rsrc((void *)a.xs, 0, (int)((int64_t)a.N * a.Hs * a.Ws * a.Cs), 0x00020000);
     // (calls must come in the order of the walk below: grp = seq, seq + n_seq, seq + 2 n_seq, ...)
     auto issue = [&](int grp, uint8_t *xs) {
         const int64_t mbase = (int64_t)grp * 32;
@@ -568,20 +570,20 @@ conv_pws_dual_kernel(const ConvArgs a, const int n_ct, const int n_seq, const in
             const int kc = inst >> 1, h = inst & 1;
             const bool main_branch = kc < KC1;      // wave-uniform
             const int64_t m = mbase + h * 16 + d_row;
-            uint32_t off = kInvalid;
-            if (grp < n_groups && m < a.M)
-                off = main_branch ? (uint32_t)m * (uint32_t)a.C + kc * 64 + d_chunk * 16 : s_off[j];
-            if (!main_branch) {
+            const bool ok = grp < n_groups && m < a.M;
+            auto *dst = (__attribute__((address_space(3))) void *)(xs + inst * 1024);
+            if (main_branch) {                      // a scalar branch: each side names its own descriptor
+                const uint32_t off = ok ? (uint32_t)m * (uint32_t)a.C + kc * 64 + d_chunk * 16 : kInvalid;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_xm, dst, 16, (int)off, 0, 0, 0);
+            } else {
+                const uint32_t off = ok ? s_off[j] : kInvalid;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_xs, dst, 16, (int)off, 0, 0, 0);
                 s_q[j] += dq;
                 s_off[j] += inc_q + inc_p + inc_n;
                 if (s_q[j] >= a.Q) { s_q[j] -= a.Q; s_p[j] += 1; s_off[j] += wrap_q; }
                 s_p[j] += dp;
                 if (s_p[j] >= a.P) { s_p[j] -= a.P; s_off[j] += wrap_p; }
             }
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(main_branch ? a.x : a.xs), 0,
-                main_branch ? (int)((int64_t)a.N * a.H * a.W * a.C) : (int)((int64_t)a.N * a.Hs * a.Ws * a.Cs), 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)(xs + inst * 1024), 16, (int)off, 0, 0, 0);
         }
     };
     const bool slow_epilogue = wide || a.y_dt == HAWQ_S4;
