@@ -236,7 +236,7 @@ def main():
     for s in range(nsteps):
         macs, nbytes = hn.step_cost(N, s)
         o = hn.step_output(N, s)
-        rows.append(dict(step=s, name=o["name"], ms=float(step_ms[s]), gmac=macs / 1e9, mbytes=nbytes / 1e6,
+        rows.append(dict(step=s, name=o["name"], dims="%d,%d,%d,%d" % o["dims"], ms=float(step_ms[s]), gmac=macs / 1e9, mbytes=nbytes / 1e6,
                          tops=2 * macs / (step_ms[s] * 1e-3) / 1e12 if macs else 0.0,
                          gbs=nbytes / (step_ms[s] * 1e-3) / 1e9))
     total_macs = sum(r["gmac"] for r in rows) * 1e9
