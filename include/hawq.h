@@ -28,7 +28,11 @@
  *    the operand ranges (HAWQ_ERR_OVERFLOW); within that bound the caller's bias must
  *    keep |acc + bias| < 2^31.
  *  - Errors are return codes; argument validation happens on the host before any launch
- *    (so it can be exercised without a GPU).  On error nothing has been enqueued.
+ *    (so it can be exercised without a GPU): a call that fails validation has enqueued nothing.
+ *    The entry points that issue several launches (hawq_concat_dyadic: one per branch;
+ *    hawq_forward_resnet: one per layer) validate everything they can first; should a later
+ *    launch itself fail (HAWQ_ERR_DEVICE), the launches already issued stay enqueued, the
+ *    streams are still joined, and the outputs are undefined.
  */
 #ifndef HAWQ_H
 #define HAWQ_H
@@ -134,6 +138,10 @@ hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, v
  *   y[m,n] = epilogue( sum_k x[m,k] * w[n,k] + bias[n] ),   x [M,Kdim], w [N,Kdim], y [M,N]
  * with the epilogue of hawq_conv2d_int (no residual).  b == c == NULL with y_dt == HAWQ_S32
  * returns the raw INT32 logits of the last layer.
+ * HAWQ_U8 activations are taken over the type's whole range 0..255 (exact for every byte value).  The INT8 matrix
+ * instruction reads signed bytes, so a caller whose unsigned activations are known to stay within 0..127 (the post-ReLU
+ * range of the 8-bit layers) may pass the same buffer as HAWQ_S8: same bytes, same result, and the request can take the
+ * fastest matrix-core form.
  */
 hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int32_t w_dt, int32_t y_dt, const void *x,
                           const void *w, const int32_t *bias, const int32_t *b, const uint8_t *c, int32_t relu,
@@ -311,8 +319,9 @@ hawq_status hawq_forward_resnet_timed(const hawq_net *net, const void *x, int32_
 hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, double *macs, double *bytes);
 
 /* Measurement hook for tile-shape sweeps: 0 = the built-in heuristic (default), 1..3 = force one of the
- * matrix-core kernel's workgroup tiles (128x128, 64x128, 64x64 channels x pixels) for every later call
- * in this process.  Results are identical for every setting. */
+ * matrix-core kernel's workgroup tiles (128x128 as four waves, 64x128, 64x64 channels x pixels) for every
+ * later call in this process; any other value is taken as 0.  Process-wide state: set it only from a
+ * single-threaded measurement program.  Results are identical for every setting. */
 void hawq_tune_set_tile(int32_t tile);
 
 /* Measurement hook for the batch split of hawq_forward_resnet: 0 = the built-in rule (default), -1 = never split,

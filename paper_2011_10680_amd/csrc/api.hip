@@ -192,7 +192,7 @@ hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int3
     d.stride_h = d.stride_w = 1; d.pad_h = d.pad_w = 0;
     d.x_dtype = x_dt; d.w_dtype = w_dt; d.y_dtype = y_dt; d.res_dtype = HAWQ_U8;
     d.relu = relu; d.y_lo = y_lo; d.y_hi = y_hi;
-    d.x_hi = (x_dt == HAWQ_U8) ? 127 : 0;   // unsigned 8-bit activations are the post-ReLU range 0..127
+    d.x_hi = 0;   // the type's whole range: HAWQ_U8 rows may hold 0..255 (they then take an exact kernel off the signed matrix cores)
     ConvArgs a;
     int x_hi;
     hawq_status st = make_conv_args(&d, x, w, bias, b, c, nullptr, nullptr, nullptr, y, true, a, x_hi);

@@ -148,7 +148,7 @@ hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);
 bool conv_pws_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s);
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
-// bias corrected for the -128 input offset by the host (see net.cpp)
+// bias corrected for the -128 input offset by the host (see net.hip)
 hawq_status launch_conv_stem(const ConvArgs &a, hipStream_t s);
 // conv1 fused with the 3x3/2 max pool: writes only the pooled tensor (U8 or packed U4)
 hawq_status launch_conv_stem_pool(const ConvArgs &a, int pool_y_dt, int pool_lo, int pool_hi, void *pool_y, hipStream_t s);

@@ -591,6 +591,9 @@ bool conv_mfma_eligible(const ConvArgs &a, int x_hi) {
     }
     if (((uintptr_t)a.x | (uintptr_t)a.w) & 15) return false;
     if ((int64_t)a.R * a.S * (a.C / (conv_mfma_packed(a) ? 128 : 64)) + 16 > kMaxSteps) return false;   // the per-step address table is in LDS
+    // the pipeline's padded K-steps present the weight offset 2^30 and rely on it lying outside the weights (so that they
+    // read as zeros): the weight matrix, also in its blocked order (channels rounded up to 64), must end below it
+    if ((int64_t)((a.K + 63) / 64 * 64) * a.R * a.S * (is4(a.w_dt) ? a.C / 2 : a.C) >= ((int64_t)1 << 30)) return false;
     return true;
 }
 
@@ -601,6 +604,7 @@ bool conv_mfma_dual_eligible(const ConvArgs &a, int x_hi, int xs_hi) {
     if (a.Cs % 64 != 0 || a.ws_dt != HAWQ_S8) return false;
     if (a.xs_dt == HAWQ_U8 ? xs_hi > 127 : a.xs_dt != HAWQ_S8) return false;
     if ((int64_t)a.R * a.S * (a.C / 64) + a.Cs / 64 + 16 > kMaxSteps) return false;
+    if ((int64_t)((a.K + 63) / 64 * 64) * a.Cs >= ((int64_t)1 << 30)) return false;   // (as above, for the shortcut's weights)
     // every array 16-byte aligned, whole 16-channel groups (the epilogue's vector form), 8-bit or unsigned 4-bit output
     uintptr_t al = (uintptr_t)a.xs | (uintptr_t)a.ws | (uintptr_t)a.y | (uintptr_t)a.bias | (uintptr_t)a.b | (uintptr_t)a.bias_s |
                    (uintptr_t)a.b_s | (uintptr_t)a.c | (uintptr_t)a.c_s;
@@ -662,7 +666,7 @@ static hawq_status launch_cfg(const ConvArgs &a, int vec, hipStream_t s, bool de
 }
 
 static int g_tile_override = 0;   // 0: heuristic; 1..3: force a tile shape (measurement hook)
-void set_tile_override(int t) { g_tile_override = t; }
+void set_tile_override(int t) { g_tile_override = (t >= 1 && t <= 3) ? t : 0; }
 int tile_override() { return g_tile_override; }
 
 hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
@@ -674,8 +678,6 @@ hawq_status launch_conv_mfma(const ConvArgs &a, hipStream_t s) {
     if (g_tile_override == 1) return launch_cfg<128, 128, 2, 2>(a, vec, s);
     if (g_tile_override == 2) return launch_cfg<64, 128, 1, 4>(a, vec, s);
     if (g_tile_override == 3) return launch_cfg<64, 64, 2, 2>(a, vec, s);
-    if (g_tile_override == 4) return launch_cfg<128, 128, 2, 4>(a, vec, s);
-    if (g_tile_override == 5) return launch_cfg<128, 128, 4, 2>(a, vec, s);
     // Measured on MI355X over the ResNet layer shapes: with at least 128 output channels the 128x128 tile
     // wins (operand reuse: a CU's vector-memory path delivers ~60 B/clk and its LDS accepts ~70 B/clk of
     // writes, which a 128x128x64 step of INT8 MFMA consumes in exactly the time it takes to multiply), in

@@ -8,9 +8,9 @@ namespace hawq {
 // ---- residual add (Section 3.3): y = clamp(rq(m) + rq(r)) ----
 __global__ void __launch_bounds__(256)
 residual_add_kernel(const int64_t units, const int K, const int per, const int m_dt, const int r_dt, const int y_dt,
-                    const void *__restrict__ m, const int32_t *__restrict__ m_b, const uint8_t *__restrict__ m_c,
-                    const void *__restrict__ r, const int32_t *__restrict__ r_b, const uint8_t *__restrict__ r_c,
-                    const int lo, const int hi, void *__restrict__ y) {
+                    const void *m, const int32_t *__restrict__ m_b, const uint8_t *__restrict__ m_c,
+                    const void *r, const int32_t *__restrict__ r_b, const uint8_t *__restrict__ r_c,
+                    const int lo, const int hi, void *y) {   // (m, r, y unqualified: y may alias m or r when the types match)
     const int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (u >= units) return;
     const int64_t e0 = u * per;
@@ -204,7 +204,8 @@ maxpool_generic_kernel(const int64_t units, const int per, const int H, const in
     }
     const int64_t oe = (((int64_t)n * P + p) * Q + q) * C + k0;
     if (is4(y_dt)) ((uint8_t *)y)[oe >> 1] = (uint8_t)((out[0] & 0xf) | ((out[1] & 0xf) << 4));
-    else ((uint8_t *)y)[oe] = (uint8_t)out[0];
+    else
+        for (int j = 0; j < per; ++j) ((uint8_t *)y)[oe + j] = (uint8_t)out[j];   // (per = 2 with a 4-bit input and an 8-bit output)
 }
 
 hawq_status launch_maxpool(int N, int H, int W, int C, int x_dt, int y_dt, const void *x, int lo, int hi, void *y,

@@ -377,6 +377,39 @@ def test_gemm_fc_shape(hawq):
     assert np.array_equal(want.astype(np.int64), x.astype(np.int64) @ w.astype(np.int64).T + bias)
 
 
+@pytest.mark.parametrize("M,N,K,requant", [(37, 1000, 2048, False), (130, 96, 512, True), (5, 64, 64, True)])
+def test_gemm_unsigned_bytes_over_the_whole_range(hawq, M, N, K, requant):
+    """HAWQ_U8 rows holding every byte value 0..255 (the matrix instruction reads signed bytes: values above 127 must not
+    be read as negative), raw INT32 and requantised outputs; and the same 0..127 data passed as HAWQ_S8 and as HAWQ_U8."""
+    import torch
+    from gpu_util import to_dev, assert_same
+    g = np.random.default_rng(M + N + K)
+    x = g.integers(0, 256, size=(M, K), dtype=np.uint8)
+    n = min(256, K)
+    x[0, :n] = np.arange(256 - n, 256, dtype=np.uint8)
+    x[-1] = 255
+    w = g.integers(-127, 128, size=(N, K)).astype(np.int8)
+    bias = g.integers(-(1 << 15), 1 << 15, size=N).astype(np.int32)
+    b = g.integers(1 << 14, 1 << 15, size=N).astype(np.int32)
+    c = np.full(N, 15 + int(np.ceil(np.log2(K * 40.0))), dtype=np.uint8)
+    for x_np, x_dt in ((x, hawq.U8), ((x >> 1), hawq.U8), ((x >> 1), hawq.S8)):
+        if requant:
+            y = torch.full((M, N), 0x5A, dtype=torch.uint8, device="cuda")
+            hawq.hawq_gemm_int(M, N, K, x_dt, hawq.S8, hawq.U8, to_dev(x_np), to_dev(w), to_dev(bias), to_dev(b), to_dev(c), 1, 0, 127, y)
+            want = oracle.gemm_int(x_np.view(np.int8) if x_dt == hawq.S8 else x_np, w, bias, b, c, M=M, N=N, K=K, x_dt=x_dt,
+                                   w_dt=oracle.S8, y_dt=oracle.U8, relu=1, y_lo=0, y_hi=127)
+        else:
+            y = torch.full((M, N), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            hawq.hawq_gemm_int(M, N, K, x_dt, hawq.S8, hawq.S32, to_dev(x_np), to_dev(w), to_dev(bias), None, None, 0, 0, 0, y)
+            want = oracle.gemm_int(x_np.view(np.int8) if x_dt == hawq.S8 else x_np, w, bias, None, None, M=M, N=N, K=K, x_dt=x_dt,
+                                   w_dt=oracle.S8, y_dt=oracle.S32)
+            assert np.array_equal(want.astype(np.int64), x_np.astype(np.int64) @ w.astype(np.int64).T + bias)
+        torch.cuda.synchronize()
+        assert_same(y.cpu().numpy(), want, "x_dt %d" % x_dt)
+    if requant:
+        assert 0.02 < np.mean(want > 0) and np.mean(want == 127) < 0.5
+
+
 @pytest.mark.parametrize("shape", [(3, 14, 14, 256, 200, 3, 3, 1, 1, 8), (2, 28, 28, 128, 128, 3, 3, 2, 1, 8), (5, 9, 9, 1024, 96, 1, 1, 1, 0, 8),
                                    (12, 28, 28, 128, 128, 3, 3, 1, 1, 4), (4, 14, 14, 256, 72, 3, 3, 1, 1, 4)])
 def test_blocked_weight_copy_gives_the_same_bits(hawq, shape):

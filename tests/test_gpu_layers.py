@@ -75,7 +75,9 @@ def test_avgpool(hawq, N, H, W, C, x_dt, y_dt):
 
 
 @pytest.mark.parametrize("N,H,W,C,x_dt,y_dt,hi", [(3, 112, 112, 64, 0, 0, 127), (2, 112, 112, 64, 0, 2, 15), (2, 9, 7, 10, 0, 0, 127),
-                                                   (1, 8, 8, 6, 1, 1, 127), (1, 10, 10, 8, 2, 2, 15)])
+                                                   (1, 8, 8, 6, 1, 1, 127), (1, 10, 10, 8, 2, 2, 15),
+                                                   # 4-bit input, 8-bit output: a thread owns two channels and stores both
+                                                   (1, 10, 10, 8, 2, 0, 127), (2, 7, 9, 6, 3, 1, 127), (1, 9, 9, 10, 3, 3, 7)])
 def test_maxpool(hawq, N, H, W, C, x_dt, y_dt, hi):
     import torch
     from gpu_util import to_dev, out_shape, assert_same
@@ -86,7 +88,7 @@ def test_maxpool(hawq, N, H, W, C, x_dt, y_dt, hi):
         x = g.integers(-128, 128, size=(N, H, W, C)).astype(np.int8)
     else:
         x = wl.pack_nibbles(g.integers(0, 16, size=(N, H, W, C)))
-    lo = -128 if y_dt == 1 else 0
+    lo = {1: -128, 3: -8}.get(y_dt, 0)
     P, Q = (H - 1) // 2 + 1, (W - 1) // 2 + 1
     y = torch.zeros(out_shape((N, P, Q, C), y_dt), dtype=torch.int8 if y_dt == 1 else torch.uint8, device="cuda")
     hawq.hawq_maxpool_int(N, H, W, C, x_dt, y_dt, to_dev(x), lo, hi, y)

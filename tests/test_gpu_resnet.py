@@ -84,11 +84,12 @@ def test_fused_stem_with_wide_parameters_and_odd_sizes(hawq, image_hw, N):
 
 @pytest.mark.parametrize("arch,batch,mixed,seed,int32_sc", [(18, 64, False, 1002, True), (50, 128, False, 1003, True), (50, 256, True, 1004, False),
                                                             (18, 64, False, 1002, False), (50, 128, False, 1003, False)])
-def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed, int32_sc):
+def test_full_size_configs_whole_batch_against_oracle(hawq, arch, batch, mixed, seed, int32_sc):
     """The network configurations at their full batch, in the launch configuration the benchmark times
-    (reused workspace slots).  The oracle computes a sample of images one by one (images are independent, so
-    a row of the batched logits must equal the single-image result); on top of that: run-to-run identical
-    bits, and the same image gives the same logits wherever it sits in the batch."""
+    (reused workspace slots, the batch as two parts on two streams where the library's rule says so).  The oracle
+    computes every image of the batch (in chunks, to bound its memory) and all batch x 1000 INT32 logits must be
+    equal.  On top of that: run-to-run identical bits, and the same image gives the same logits wherever it sits
+    in the batch."""
     import torch
     bits = wl.draw_bits(arch, 4000 + arch) if mixed else None
     net = wl.make_resnet(arch, seed=seed, bits=bits, int32_shortcut=int32_sc)   # the benchmark's workloads: both transition forms
@@ -107,12 +108,16 @@ def test_full_size_configs_sampled_against_oracle(hawq, arch, batch, mixed, seed
     torch.cuda.synchronize()
     assert np.array_equal(logits.cpu().numpy(), got), "two runs differ"
     assert np.array_equal(got[0], got[batch - 1]), "same image, different logits at another batch position"
-    sample = sorted({0, 1, batch // 2 - 1, batch // 2, batch - 2})
-    want = onet.forward(net, x[sample])
-    for j, i in enumerate(sample):
-        assert np.array_equal(got[i], want[j]), "image %d of the full batch differs from the oracle" % i
-    assert len({got[i].tobytes() for i in range(batch - 1)}) == batch - 1   # distinct images, distinct logits
     hn.close()
+    chunk = 32
+    for i0 in range(0, batch, chunk):
+        want = onet.forward(net, x[i0:i0 + chunk])
+        if not np.array_equal(got[i0:i0 + chunk], want):
+            bad = np.argwhere(got[i0:i0 + chunk] != want)
+            raise AssertionError("image %d of the full batch differs from the oracle (%d logits in images %d..%d differ)" % (
+                i0 + bad[0][0], len(bad), i0, i0 + chunk - 1))
+        print("images %d..%d of %d equal the oracle" % (i0, min(batch, i0 + chunk) - 1, batch), flush=True)
+    assert len({got[i].tobytes() for i in range(batch - 1)}) == batch - 1   # distinct images, distinct logits
 
 
 @pytest.mark.parametrize("arch,N,first,hw", [(18, 13, 5, 64), (50, 6, 4, 64), (18, 9, 8, 64),
