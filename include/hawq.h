@@ -307,6 +307,21 @@ hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, i
                                 size_t workspace_bytes, void *stream);
 
 /*
+ * The same forward for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Identical to hawq_forward_resnet except that the workspace is
+ * a fixed array of hawq_noalloc_workspace_limit() bytes (64 MiB) inside the library's device code, one per GPU, held
+ * until the process ends; x and logits are still the caller's device buffers.  The call allocates nothing (no
+ * hipMalloc / hipFree, no allocating library routine).  hawq_net_workspace_bytes(net, N) must not exceed the limit --
+ * HAWQ_ERR_WORKSPACE otherwise (ResNet50 at 224x224 fits up to a batch of about 28, ResNet18 about 100).
+ * Every call on a GPU uses that GPU's one array (its contents are whatever the last call left; the forward reads
+ * nothing it has not written): calls that overlap in time on one GPU -- from different streams, networks or
+ * threads -- race.  Serialise them, e.g. by issuing them on one stream.  A network with kept activations may use it
+ * too; hawq_net_step_output's offsets are then relative to the array, which the caller cannot read.
+ */
+size_t hawq_noalloc_workspace_limit(void);
+hawq_status hawq_forward_resnet_noalloc(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *stream);
+
+/*
  * Same forward with a pair of HIP events around every step, recorded on `stream`; on return the
  * stream has been synchronised and step_ms[i] (host array, hawq_net_num_steps entries) holds the
  * device time of step i in milliseconds.  For measurement only.

@@ -91,6 +91,10 @@ def load_library():
     lib.hawq_net_step_cost.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.hawq_forward_resnet.restype = ctypes.c_int
     lib.hawq_forward_resnet.argtypes = [vp, vp, i32, vp, vp, sz, vp]
+    lib.hawq_forward_resnet_noalloc.restype = ctypes.c_int
+    lib.hawq_forward_resnet_noalloc.argtypes = [vp, vp, i32, vp, vp]
+    lib.hawq_noalloc_workspace_limit.restype = sz
+    lib.hawq_noalloc_workspace_limit.argtypes = []
     lib.hawq_forward_resnet_timed.restype = ctypes.c_int
     lib.hawq_forward_resnet_timed.argtypes = [vp, vp, i32, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.hawq_tune_set_tile.restype = None
@@ -207,6 +211,10 @@ def hawq_tune_set_split(n_first):
     load_library().hawq_tune_set_split(int(n_first))
 
 
+def hawq_noalloc_workspace_limit():
+    return int(load_library().hawq_noalloc_workspace_limit())
+
+
 def hawq_net_num_layers(arch):
     return load_library().hawq_net_num_layers(arch)
 
@@ -287,6 +295,10 @@ class HawqNet:
         _check(load_library().hawq_forward_resnet(self._h, _p(x), N, _p(logits), _p(workspace),
                                                   workspace.numel() * workspace.element_size(), _stream(stream)),
                "hawq_forward_resnet")
+
+    def hawq_forward_resnet_noalloc(self, x, N, logits, stream=None):
+        _check(load_library().hawq_forward_resnet_noalloc(self._h, _p(x), N, _p(logits), _stream(stream)),
+               "hawq_forward_resnet_noalloc")
 
     def hawq_forward_resnet_timed(self, x, N, logits, workspace, stream=None):
         ms = (ctypes.c_float * self.num_steps())()

@@ -4,10 +4,18 @@
 // Host code only; the kernels live in the other translation units.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
 #include "common.h"
+
+// Workspace of hawq_forward_resnet_noalloc: a fixed array in device memory that belongs to the library's code object (one
+// copy per GPU the library is loaded on, held until the process ends).  In host code this name is only a handle for
+// hipGetSymbolAddress -- never an address a kernel could use; the per-device address is resolved once (scratch_base below)
+// and that pointer is what reaches the kernels, exactly as a caller's workspace pointer does.
+#define HAWQ_NOALLOC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[HAWQ_NOALLOC_SCRATCH_BYTES];
 
 namespace hawq {
 hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w, const int32_t *bias, const int32_t *b,
@@ -112,6 +120,23 @@ struct Step {
 };
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device address of `scratch` on the current device, resolved on first use per device (hawq_net_create does it for the
+// device the network is created on, so the forward itself normally finds it cached).  nullptr if a HIP call fails.
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+void *scratch_base() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 }  // namespace
 
@@ -365,6 +390,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     }
     memcpy(&host[off_pb], pool_b, 4 * (size_t)c_last);
     memcpy(&host[off_pc], pool_c, (size_t)c_last);
+    if (scratch_base() == nullptr) return fail(HAWQ_ERR_DEVICE);   // (address of the fixed workspace on this device, for hawq_forward_resnet_noalloc)
     if (hipMalloc(&net->arena, total) != hipSuccess) return fail(HAWQ_ERR_DEVICE);
     if (hipMemcpy(net->arena, host.data(), total, hipMemcpyHostToDevice) != hipSuccess) return fail(HAWQ_ERR_DEVICE);
     // second stream (default priority) and the events that order it against the caller's stream
@@ -798,6 +824,17 @@ void hawq_tune_set_split(int32_t n_first) { g_split_override = n_first; }
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream) {
     return run_forward(net, x, N, logits, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+size_t hawq_noalloc_workspace_limit(void) { return (size_t)HAWQ_NOALLOC_SCRATCH_BYTES; }
+
+hawq_status hawq_forward_resnet_noalloc(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *stream) {
+    if (!net || !x || !logits) return HAWQ_ERR_NULL;
+    if (N <= 0) return HAWQ_ERR_SHAPE;
+    if (hawq_net_workspace_bytes(net, N) > (size_t)HAWQ_NOALLOC_SCRATCH_BYTES) return HAWQ_ERR_WORKSPACE;
+    void *ws = scratch_base();
+    if (ws == nullptr) return HAWQ_ERR_DEVICE;
+    return run_forward(net, x, N, logits, ws, (size_t)HAWQ_NOALLOC_SCRATCH_BYTES, (hipStream_t)stream, nullptr);
 }
 
 hawq_status hawq_forward_resnet_timed(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
