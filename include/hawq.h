@@ -77,6 +77,9 @@ typedef struct {
     const void *w_blocked;         /* optional (NULL: none): device copy of the same weights made by
                                       hawq_conv_block_weights; the implicit-GEMM kernel then reads it instead of w
                                       (whole cache lines per fetch).  w is still required: other kernels read it. */
+    const void *w_fragments;       /* optional (NULL: none): device copy of the same weights made by
+                                      hawq_conv_fragment_weights; a 3x3 / stride 1 / pad 1 layer with 128 or 256 input
+                                      channels then runs on the kernel that keeps its pixels in LDS and streams these. */
 } hawq_conv_desc;
 
 /*
@@ -132,6 +135,37 @@ hawq_status hawq_conv2d_dual_int(const hawq_conv_desc *desc, const void *x, cons
  */
 size_t hawq_conv_blocked_weights_bytes(const hawq_conv_desc *desc);
 hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, void *w_blocked, void *stream);
+
+/*
+ * Copy of a layer's weights in matrix-instruction fragment order: [ceil(K/32)][R*S*C/64][2][64 lanes][16 bytes], i.e. for
+ * every group of 32 output channels and every 64-byte reduction step the two 1 KB operand fragments exactly as the 64
+ * lanes of a wave hold them (channels past K zero).  A wave then loads its weights with fully coalesced reads straight
+ * into registers.  Same integers, another order: results do not change.  8-bit weights with C % 64 == 0 only
+ * (hawq_conv_fragment_weights_bytes returns 0 otherwise, hawq_conv_fragment_weights HAWQ_ERR_UNSUPPORTED).
+ * Device to device, asynchronous on `stream`, 16-byte aligned pointers; call once per layer, outside the timed path.
+ */
+size_t hawq_conv_fragment_weights_bytes(const hawq_conv_desc *desc);
+hawq_status hawq_conv_fragment_weights(const hawq_conv_desc *desc, const void *w, void *w_fragments, void *stream);
+
+/*
+ * Tail of a bottleneck block in one launch -- Figure 2 / Section 3.3: the block's 3x3 convolution, its requantisation,
+ * the 1x1 convolution that restores the channel count, its requantisation, the dyadic-rescaled shortcut, ReLU / clamp:
+ *   h = clamp( relu2?( rq(conv3x3(x, w2) + bias2, b2, c2) ), lo2, hi2 )                    (desc2: y_dtype, relu, y_lo, y_hi)
+ *   y = clamp( relu3?( rq(conv1x1(h, w3) + bias3, b3, c3) + rq(residual, res_b, res_c) ), lo3, hi3 )     (desc3)
+ * -- the very integers of hawq_conv2d_int(desc2) followed by hawq_conv2d_int(desc3, residual), but the tensor h between
+ * them stays inside the compute unit (INT32 accumulators in registers, h in LDS) and is never written to memory.
+ * desc2: 3x3, stride 1, pad 1, C -> K = C channels, 8-bit operands within the signed range (HAWQ_S8, or HAWQ_U8 with
+ * x_hi <= 127), y_dtype HAWQ_U8 / HAWQ_S8 with the clamp inside -128..127.  desc3: 1x1, stride 1, no padding, same N, H,
+ * W, C = desc2.K, x_dtype = desc2.y_dtype, y_dtype and res_dtype HAWQ_U8 / HAWQ_S8.  w2_fragments / w3_fragments: the two
+ * layers' weights as made by hawq_conv_fragment_weights.  residual [N,H,W,desc3.K] is required.  All pointers device
+ * memory, 16-byte aligned tensors.  Shapes served: C = 128 with image width <= 28 and desc3.K a multiple of 128 up to 512;
+ * C = 256 with width <= 14 and desc3.K a multiple of 256 up to 1024 (the stage-2 and stage-3 blocks of ResNet50);
+ * anything else valid returns HAWQ_ERR_UNSUPPORTED (run the two layers separately).
+ */
+hawq_status hawq_bottleneck_tail_int(const hawq_conv_desc *desc2, const void *x, const void *w2_fragments, const int32_t *bias2,
+                                     const int32_t *b2, const uint8_t *c2, const hawq_conv_desc *desc3, const void *w3_fragments,
+                                     const int32_t *bias3, const int32_t *b3, const uint8_t *c3, const void *residual,
+                                     const int32_t *res_b, const uint8_t *res_c, void *y, void *stream);
 
 /*
  * Quantised fully connected layer / GEMM -- the matrix-multiply form of Section 3.1:

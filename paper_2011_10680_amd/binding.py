@@ -23,7 +23,7 @@ class HawqError(RuntimeError):
 class ConvDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w",
-                 "x_dtype", "w_dtype", "y_dtype", "res_dtype", "relu", "y_lo", "y_hi", "x_hi")] + [("w_blocked", ctypes.c_void_p)]
+                 "x_dtype", "w_dtype", "y_dtype", "res_dtype", "relu", "y_lo", "y_hi", "x_hi")] + [("w_blocked", ctypes.c_void_p), ("w_fragments", ctypes.c_void_p)]
 
 
 class LayerParams(ctypes.Structure):
@@ -105,6 +105,12 @@ def load_library():
     lib.hawq_conv_blocked_weights_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
     lib.hawq_conv_block_weights.restype = ctypes.c_int
     lib.hawq_conv_block_weights.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+    lib.hawq_conv_fragment_weights_bytes.restype = ctypes.c_size_t
+    lib.hawq_conv_fragment_weights_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+    lib.hawq_conv_fragment_weights.restype = ctypes.c_int
+    lib.hawq_conv_fragment_weights.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+    lib.hawq_bottleneck_tail_int.restype = ctypes.c_int
+    lib.hawq_bottleneck_tail_int.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 5 + [ctypes.POINTER(ConvDesc)] + [vp] * 9
     lib.hawq_probe_mfma_peak.restype = ctypes.c_int
     lib.hawq_probe_mfma_peak.argtypes = [i32, ctypes.POINTER(ctypes.c_double)]
     lib.hawq_tune_set_split.restype = None
@@ -197,6 +203,22 @@ def hawq_conv_blocked_weights_bytes(desc):
 def hawq_conv_block_weights(desc, w, w_blocked, stream=None):
     _check(load_library().hawq_conv_block_weights(ctypes.byref(desc), _p(w), _p(w_blocked), _stream(stream)),
            "hawq_conv_block_weights")
+
+
+def hawq_conv_fragment_weights_bytes(desc):
+    return int(load_library().hawq_conv_fragment_weights_bytes(ctypes.byref(desc)))
+
+
+def hawq_conv_fragment_weights(desc, w, w_fragments, stream=None):
+    _check(load_library().hawq_conv_fragment_weights(ctypes.byref(desc), _p(w), _p(w_fragments), _stream(stream)),
+           "hawq_conv_fragment_weights")
+
+
+def hawq_bottleneck_tail_int(desc2, x, w2_fragments, bias2, b2, c2, desc3, w3_fragments, bias3, b3, c3, residual, res_b, res_c, y,
+                             stream=None):
+    _check(load_library().hawq_bottleneck_tail_int(ctypes.byref(desc2), _p(x), _p(w2_fragments), _p(bias2), _p(b2), _p(c2),
+                                                    ctypes.byref(desc3), _p(w3_fragments), _p(bias3), _p(b3), _p(c3), _p(residual),
+                                                    _p(res_b), _p(res_c), _p(y), _stream(stream)), "hawq_bottleneck_tail_int")
 
 
 def hawq_probe_mfma_peak(iters=4000):

@@ -88,6 +88,7 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     a.xs = nullptr; a.ws = nullptr; a.bias_s = nullptr; a.b_s = nullptr; a.c_s = nullptr;
     a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.ws_t = nullptr; a.dual16 = 0;
     a.w_t = (d->w_blocked != nullptr && ((uintptr_t)d->w_blocked & 15) == 0) ? d->w_blocked : nullptr;
+    a.w_f = (d->w_fragments != nullptr && ((uintptr_t)d->w_fragments & 15) == 0) ? d->w_fragments : nullptr;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
     a.stride_h = d->stride_h; a.stride_w = d->stride_w; a.pad_h = d->pad_h; a.pad_w = d->pad_w;
     a.P = (int32_t)P; a.Q = (int32_t)Q; a.M = (int32_t)M;
@@ -101,11 +102,44 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     return HAWQ_OK;
 }
 
+// The resident-pixel kernel's view of a validated 3x3 layer a1 (weights a1.w_f) and, when a2 is given, of the 1x1 layer
+// that consumes its output in the same launch (weights w2f; a2's x / y-of-a1 pointers are not used).
+bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *w2f, RpArgs &r) {
+    if (a1.R != 3 || a1.S != 3 || a1.stride_h != 1 || a1.stride_w != 1 || a1.pad_h != 1 || a1.pad_w != 1) return false;
+    if (a1.w_dt != HAWQ_S8 || a1.w_f == nullptr || a1.b == nullptr || a1.xs != nullptr) return false;
+    if (a1.x_dt == HAWQ_U8 ? x_hi > 127 : a1.x_dt != HAWQ_S8) return false;
+    if (a1.y_dt != HAWQ_U8 && a1.y_dt != HAWQ_S8) return false;
+    if ((uintptr_t)a1.x & 15) return false;
+    r = RpArgs{};
+    r.x = a1.x; r.N = a1.N; r.H = a1.H; r.W = a1.W; r.C = a1.C; r.M = a1.M;
+    r.w1f = (const uint8_t *)a1.w_f; r.bias1 = a1.bias; r.b1 = a1.b; r.c1 = a1.c; r.K1 = a1.K; r.lo1 = a1.lo; r.hi1 = a1.hi;
+    if (a2 == nullptr) {
+        if (a1.res != nullptr && a1.res_dt != HAWQ_U8 && a1.res_dt != HAWQ_S8) return false;
+        if (((uintptr_t)a1.y | (uintptr_t)a1.res) & 15) return false;
+        r.res = a1.res; r.res_b = a1.res_b; r.res_c = a1.res_c; r.res_dt = a1.res_dt; r.y = a1.y;
+        return conv_rp_shape_ok(r, false);
+    }
+    // the intermediate tensor becomes the signed matrix operand of the second convolution
+    if (a1.res != nullptr || a1.lo < -128 || a1.hi > 127) return false;
+    if (a2->R != 1 || a2->S != 1 || a2->stride_h != 1 || a2->stride_w != 1 || a2->pad_h != 0 || a2->pad_w != 0) return false;
+    if (a2->N != a1.N || a2->H != a1.H || a2->W != a1.W || a2->C != a1.K || a2->x_dt != a1.y_dt || a2->w_dt != HAWQ_S8) return false;
+    if (a2->b == nullptr || a2->res == nullptr || a2->xs != nullptr || w2f == nullptr) return false;
+    if ((a2->y_dt != HAWQ_U8 && a2->y_dt != HAWQ_S8) || (a2->res_dt != HAWQ_U8 && a2->res_dt != HAWQ_S8)) return false;
+    if (((uintptr_t)a2->y | (uintptr_t)a2->res | (uintptr_t)w2f) & 15) return false;
+    r.res = a2->res; r.res_b = a2->res_b; r.res_c = a2->res_c; r.res_dt = a2->res_dt; r.y = a2->y;
+    r.w2f = (const uint8_t *)w2f; r.bias2 = a2->bias; r.b2 = a2->b; r.c2 = a2->c; r.K2 = a2->K; r.lo2 = a2->lo; r.hi2 = a2->hi;
+    return conv_rp_shape_ok(r, true);
+}
+
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     if (conv_pw_eligible(a, x_hi)) return launch_conv_pw(a, s);
     if (tile_override() == 0 && conv_pws_eligible(a, x_hi)) return launch_conv_pws(a, s);
     if (tile_override() == 0 && conv3x3_c64_eligible(a, x_hi)) return launch_conv3x3_c64(a, s);
+    if (tile_override() == 0 && a.w_f != nullptr) {
+        RpArgs r;
+        if (make_rp_args(a, x_hi, nullptr, nullptr, r)) return launch_conv_rp(r, false, s);
+    }
     if (conv_mfma_eligible(a, x_hi)) return launch_conv_mfma(a, s);
     return launch_conv_direct(a, s);
 }
@@ -160,6 +194,48 @@ hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, v
     if (((uintptr_t)w | (uintptr_t)w_blocked) & 15) return HAWQ_ERR_UNSUPPORTED;
     const int64_t row = hawq::tensor_bytes((int64_t)desc->R * desc->S * desc->C, desc->w_dtype);
     return hawq::launch_block_weights(w, w_blocked, desc->K, row, (hipStream_t)stream);
+}
+
+size_t hawq_conv_fragment_weights_bytes(const hawq_conv_desc *desc) {
+    if (!desc || desc->K <= 0 || desc->R <= 0 || desc->S <= 0 || desc->C <= 0) return 0;
+    if (desc->w_dtype != HAWQ_S8 || desc->C % 64 != 0) return 0;
+    return (size_t)((desc->K + 31) / 32) * 32 * (size_t)desc->R * desc->S * desc->C;
+}
+
+hawq_status hawq_conv_fragment_weights(const hawq_conv_desc *desc, const void *w, void *w_fragments, void *stream) {
+    if (!desc || !w || !w_fragments) return HAWQ_ERR_NULL;
+    const size_t bytes = hawq_conv_fragment_weights_bytes(desc);
+    if (bytes == 0 || bytes >= (size_t)kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)w | (uintptr_t)w_fragments) & 15) return HAWQ_ERR_UNSUPPORTED;
+    return hawq::launch_fragment_weights(w, w_fragments, desc->K, (int64_t)desc->R * desc->S * desc->C, (hipStream_t)stream);
+}
+
+hawq_status hawq_bottleneck_tail_int(const hawq_conv_desc *desc2, const void *x, const void *w2_fragments, const int32_t *bias2,
+                                     const int32_t *b2, const uint8_t *c2, const hawq_conv_desc *desc3, const void *w3_fragments,
+                                     const int32_t *bias3, const int32_t *b3, const uint8_t *c3, const void *residual,
+                                     const int32_t *res_b, const uint8_t *res_c, void *y, void *stream) {
+    if (!desc2 || !desc3 || !b2 || !c2 || !b3 || !c3 || !residual || !w2_fragments || !w3_fragments) return HAWQ_ERR_NULL;
+    // each layer on its own terms (types, clamp, overflow bound, sizes); the weights are given in fragment order only, and
+    // the intermediate tensor has no address: stand-ins that pass the pointer checks and are never dereferenced
+    ConvArgs a1, a2;
+    int x_hi, h_hi;
+    hawq_conv_desc d2 = *desc2, d3 = *desc3;
+    d2.w_blocked = nullptr; d2.w_fragments = w2_fragments; d3.w_blocked = nullptr; d3.w_fragments = nullptr;
+    hawq_status st = make_conv_args(&d2, x, w2_fragments, bias2, b2, c2, nullptr, nullptr, nullptr, y, true, a1, x_hi);
+    if (st != HAWQ_OK) return st;
+    // the second layer reads the first one's clamped output: that bounds its activations
+    const int lo1 = a1.lo, hi1 = a1.hi;
+    if (d3.x_dtype == HAWQ_U8 || d3.x_dtype == HAWQ_S8) {
+        const int m = (-lo1 > hi1 ? -lo1 : hi1);
+        d3.x_hi = m < 1 ? 1 : (m > (d3.x_dtype == HAWQ_U8 ? 255 : 128) ? 0 : m);
+    }
+    st = make_conv_args(&d3, x, w3_fragments, bias3, b3, c3, residual, res_b, res_c, y, true, a2, h_hi);
+    if (st != HAWQ_OK) return st;
+    if (((uintptr_t)w2_fragments) & 15) return HAWQ_ERR_UNSUPPORTED;
+    RpArgs r;
+    if (!make_rp_args(a1, x_hi, &a2, w3_fragments, r)) return HAWQ_ERR_UNSUPPORTED;
+    if (a1.M == 0) return HAWQ_OK;
+    return launch_conv_rp(r, true, (hipStream_t)stream);
 }
 
 hawq_status hawq_conv2d_int(const hawq_conv_desc *desc, const void *x, const void *w, const int32_t *bias, const int32_t *b,

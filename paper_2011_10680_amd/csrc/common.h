@@ -43,12 +43,38 @@ struct ConvArgs {
     // implicit-GEMM kernel -- [ceil(K/64)][row bytes / 64][64 channels][64 bytes], i.e. the [K][R*S*C] byte matrix cut
     // into 64-channel x 64-byte blocks, rows past K zero -- so that one K-step of a channel tile is contiguous memory
     const void *w_t, *ws_t;
+    // w_f (optional): the weights in MFMA fragment order for the resident-pixel 3x3 kernel (launch_fragment_weights)
+    const void *w_f;
     // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
     // meant for a launch that is alone (small tiles with a deep LDS ring when there are few tiles) are not chosen
     int32_t corun;
     // dual16 (two-convolution form, set by the network plan from host data): every (b, c) and (b_s, c_s) is in the narrow
     // evaluation's range and |rq(acc + bias, b, c)| of the main branch cannot exceed 32767 for any input
     int32_t dual16;
+};
+
+// Arguments of the resident-pixel 3x3 kernel (conv_rp.hip), with or without the fused 1x1 that ends a bottleneck block.
+struct RpArgs {
+    const uint8_t *x;        // input [N,H,W,C], 8-bit (signed operand range)
+    int32_t N, H, W, C;
+    int32_t M;               // N*H*W pixels (the 3x3 convolution is stride 1, pad 1: as many output pixels)
+    // stage 1: 3x3, C -> K1
+    const uint8_t *w1f;      // weights in MFMA fragment order (launch_fragment_weights)
+    const int32_t *bias1, *b1;
+    const uint8_t *c1;
+    int32_t K1, lo1, hi1;    // clamp with ReLU folded in
+    // shortcut and output of the stage that stores to memory (stage 1 alone, or stage 2 when fused): [M][K] 8-bit
+    const uint8_t *res;      // nullptr: none (plain form only; the fused form requires one)
+    const int32_t *res_b;
+    const uint8_t *res_c;
+    int32_t res_dt;          // HAWQ_U8 | HAWQ_S8
+    uint8_t *y;
+    // stage 2 (fused form): 1x1, K1 -> K2
+    const uint8_t *w2f;
+    const int32_t *bias2, *b2;
+    const uint8_t *c2;
+    int32_t K2, lo2, hi2;
+    int32_t kg;              // plain form: stage-1 channels per workgroup (set by the launcher)
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }
@@ -164,6 +190,14 @@ hawq_status launch_pool_sum(int N, int H, int W, int C, int R, int S, int sh, in
                             const void *x, const int32_t *b, const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
 hawq_status launch_concat_branch(int64_t n_pixels, int K, int Kt, int off, int q_dt, int y_dt, const void *q, const int32_t *b,
                                  const uint8_t *c, int lo, int hi, void *y, hipStream_t s);
+
+// resident-pixel 3x3 (+ fused 1x1) kernel: shape test and launch (operand types / alignment are the caller's to check)
+bool conv_rp_shape_ok(const RpArgs &a, bool fused);
+// RpArgs from a validated 3x3 layer (and, fused, the 1x1 layer that follows it); false if types, alignment or shape do not fit
+bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *w2f, RpArgs &r);
+hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s);
+// [K][row bytes] weights -> MFMA fragment order for that kernel; row a multiple of 64; out: ceil(K/32) * row * 32 bytes
+hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, hipStream_t s);
 
 // [K][row bytes] weights -> the implicit-GEMM kernel's blocked order (ConvArgs::w_t); row a multiple of 64
 hawq_status launch_block_weights(const void *w, void *w_blocked, int K, int64_t row, hipStream_t s);

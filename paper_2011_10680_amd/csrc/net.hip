@@ -115,6 +115,11 @@ struct Step {
     const int32_t *bias = nullptr, *b = nullptr, *res_b = nullptr;
     const uint8_t *c = nullptr, *res_c = nullptr;
     double macs_per_image = 0, bytes_per_image = 0, bytes_fixed = 0;
+    const uint8_t *w_f = nullptr; // the weights in MFMA fragment order (resident-pixel 3x3 kernel and its fused 1x1), or null
+    // A bottleneck's 3x3 convolution and the 1x1 convolution + shortcut that follows it as one launch (the tensor between
+    // them is never stored): the 3x3 step launches nothing (tail_next = index of the 1x1 step), the 1x1 step launches both
+    // (tail_prev = index of the 3x3 step).
+    int tail_next = -1, tail_prev = -1;
     bool fused_pool = false;      // conv1 step: the max pool is computed in the same kernel (writes the pool's tensor)
     bool skip = false;            // max-pool step when conv1 has absorbed it: nothing to launch
 };
@@ -165,6 +170,8 @@ void assign_slots(hawq_net *net) {
         if (st.res >= 0) T[st.res].last_use = (int)s;
         // a transition step that is carried out at its block's last convolution reads its input there
         if (st.pair_ds >= 0 && net->steps[st.pair_ds].in >= 0) T[net->steps[st.pair_ds].in].last_use = (int)s;
+        // likewise the input of a 3x3 convolution that runs inside its successor's launch
+        if (st.tail_prev >= 0 && net->steps[st.tail_prev].in >= 0) T[net->steps[st.tail_prev].in].last_use = (int)s;
     }
     std::vector<int> owner;  // slot -> tensor currently in it (-1 free)
     auto &sb = net->slot_bytes_per_image;
@@ -327,11 +334,19 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto cont_dt = [&](int i) { return is8(i) ? HAWQ_U8 : HAWQ_U4; };     // container of the tensor layer i reads
 
     // ---- parameter arena layout ----
-    struct Off { size_t w, wt, bias, b, c, rb, rc; };
+    struct Off { size_t w, wt, wf, bias, b, c, rb, rc; };
     // row of the [K][R*S*C] weight matrix in bytes as stored, and whether a blocked copy is made for the implicit-GEMM
     // kernel (64-byte K-steps: 8-bit form with C % 64 == 0, packed 4-bit form with C % 128 == 0)
     auto wrow = [&](int i) { return (int64_t)tensor_bytes((int64_t)L[i].R * L[i].S * L[i].C, is8(i) ? HAWQ_S8 : HAWQ_S4); };
     auto blocked = [&](int i) { return !L[i].is_stem && L[i].C % (is8(i) ? 64 : 128) == 0; };
+    // fragment-ordered copy: the 3x3 / 1 / 1 layers the resident-pixel kernel takes (128 or 256 input channels, 8-bit form)
+    // and the 1x1 layer that follows such a layer in a bottleneck (it may run fused behind it)
+    auto rp3x3 = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && is8(i) && (L[i].C == 128 || L[i].C == 256) && L[i].K % L[i].C == 0; };
+    auto fragmented = [&](int i) {
+        if (L[i].is_stem || L[i].is_fc) return false;
+        if (rp3x3(i)) return true;
+        return i > 0 && L[i].R == 1 && L[i].has_residual && is8(i) && rp3x3(i - 1) && L[i - 1].block == L[i].block && L[i].C == L[i - 1].K;
+    };
     std::vector<Off> off(nl);
     size_t total = 0;
     auto take = [&](size_t bytes) { size_t o = total; total = align_up(total + bytes, 256); return o; };
@@ -339,6 +354,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
         off[i].w = take((size_t)tensor_bytes(nw, is8(i) ? HAWQ_S8 : HAWQ_S4));
         off[i].wt = blocked(i) ? take((size_t)((L[i].K + 63) / 64) * (size_t)wrow(i) * 64) : 0;
+        off[i].wf = fragmented(i) ? take((size_t)((L[i].K + 31) / 32) * (size_t)wrow(i) * 32) : 0;
         off[i].bias = take(4 * (size_t)L[i].K);
         off[i].b = take(4 * (size_t)L[i].K);
         off[i].c = take((size_t)L[i].K);
@@ -367,6 +383,20 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             for (int k = 0; k < L[i].K; ++k)
                 for (int64_t st = 0; st < nsteps; ++st)
                     memcpy(dst + (((int64_t)(k >> 6) * nsteps + st) * 64 + (k & 63)) * 64, src + k * row + st * 64, 64);
+        }
+        if (fragmented(i)) {   // [K][row] -> [K/32][row/64][2][64 lanes][16]: see launch_fragment_weights for the order
+            const int64_t row = wrow(i), nsteps = row / 64;
+            const uint8_t *src = &host[off[i].w];
+            uint8_t *dst = &host[off[i].wf];
+            for (int g = 0; g < (L[i].K + 31) / 32; ++g)
+                for (int64_t st = 0; st < nsteps; ++st)
+                    for (int kk = 0; kk < 2; ++kk)
+                        for (int lane = 0; lane < 64; ++lane) {
+                            const int rho = lane & 31, khalf = lane >> 5;
+                            const int k = g * 32 + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
+                            uint8_t *d = dst + ((((int64_t)g * nsteps + st) * 2 + kk) * 64 + lane) * 16;
+                            if (k < L[i].K) memcpy(d, src + k * row + st * 64 + (kk * 2 + khalf) * 16, 16);
+                        }
         }
         memcpy(&host[off[i].bias], lp[i].bias, 4 * (size_t)L[i].K);
         if (!L[i].is_fc) {
@@ -450,6 +480,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         d.x_hi = in_hi;
         st.w = A + off[i].w; st.bias = (const int32_t *)(A + off[i].bias);
         st.w_t = blocked(i) ? A + off[i].wt : nullptr;
+        st.w_f = fragmented(i) ? A + off[i].wf : nullptr;
         st.b = (const int32_t *)(A + off[i].b); st.c = A + off[i].c;
         if (res_t >= 0) { st.res_b = (const int32_t *)(A + off[i].rb); st.res_c = A + off[i].rc; }
         st.out = new_tensor(L[i].P, L[i].Q, L[i].K, d.y_dtype);
@@ -564,6 +595,21 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             ds_step = (int)net->steps.size() - 1;
         }
         t = conv_step(last, u, u_dt, act_hi(u_bits), sc, sc_dt, out_bits, out_dt, false, true);
+        if (ds_step < 0 && !net->keep && mids.size() == 2) {
+            // bottleneck with an identity shortcut: 3x3 and the closing 1x1 + shortcut as one launch where the
+            // resident-pixel kernel takes the shapes and every tensor involved is in 8-bit form
+            const int s3 = (int)net->steps.size() - 1, s2 = s3 - 1;
+            Step &c2 = net->steps[s2], &c3 = net->steps[s3];
+            RpArgs probe{};
+            probe.C = c2.desc.C; probe.K1 = c2.desc.K; probe.K2 = c3.desc.K; probe.H = c2.desc.H; probe.W = c2.desc.W; probe.M = 1;
+            const bool types = c2.desc.x_dtype == HAWQ_U8 && c2.desc.y_dtype == HAWQ_U8 && c3.desc.y_dtype == HAWQ_U8 &&
+                               c3.desc.res_dtype == HAWQ_U8 && c2.desc.x_hi <= 127;
+            if (c2.w_f && c3.w_f && types && c2.desc.R == 3 && c3.desc.R == 1 && conv_rp_shape_ok(probe, true)) {
+                c2.tail_next = s3;
+                c3.tail_prev = s2;
+                net->tensors[c2.out].elems_per_image = 0;   // never stored
+            }
+        }
         if (ds_step >= 0 && !net->keep && is8(last) && is8(ds)) {
             net->steps[ds_step].pair_last = (int)net->steps.size() - 1;
             net->steps.back().pair_ds = ds_step;
@@ -658,6 +704,15 @@ hawq_status hawq_net_step_cost(const hawq_net *net, int32_t N, int32_t step, dou
     // a transition / last convolution pair that runs as one launch: all the work and the traffic it still needs (both
     // inputs, both parameter sets, the block output) are reported on the last convolution's step
     if (st.pair_last >= 0 && pair_runs_fused(net, N, step)) { *macs = 0; *bytes = 0; }
+    // a 3x3 convolution that runs inside the launch of the 1x1 that follows it: work and traffic (the 3x3's input, the
+    // shortcut, the block output, both weight sets) are reported on that step; the tensor in between moves no bytes
+    if (st.tail_next >= 0) { *macs = 0; *bytes = 0; }
+    if (st.tail_prev >= 0) {
+        const Step &p = net->steps[st.tail_prev];
+        const double px = (double)st.desc.H * st.desc.W;
+        *macs += p.macs_per_image * N;
+        *bytes = (px * p.desc.C + 2.0 * px * st.desc.K) * N + st.bytes_fixed + p.bytes_fixed;
+    }
     if (st.pair_ds >= 0 && pair_runs_fused(net, N, st.pair_ds)) {
         const Step &d = net->steps[st.pair_ds];
         const hawq_conv_desc &c = st.desc, &e = d.desc;
@@ -722,6 +777,28 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                 continue;
             }
         }
+        if (st.kind == STEP_CONV && st.tail_next >= 0) {   // runs inside the next step's launch
+            if (ev && hipEventRecord(ev[2 * s + 1], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+            continue;
+        }
+        if (st.kind == STEP_CONV && st.tail_prev >= 0) {
+            const Step &p = net->steps[st.tail_prev];
+            hawq_conv_desc d2 = p.desc, d3 = st.desc;
+            d2.N = N; d3.N = N;
+            ConvArgs a1, a2;
+            int x_hi, h_hi;
+            rc = make_conv_args(&d2, tptr(p.in), p.w, p.bias, p.b, p.c, nullptr, nullptr, nullptr, tptr(st.out), true, a1, x_hi);
+            if (rc == HAWQ_OK)
+                rc = make_conv_args(&d3, tptr(p.in), st.w, st.bias, st.b, st.c, tptr(st.res), st.res_b, st.res_c, tptr(st.out), true, a2, h_hi);
+            if (rc != HAWQ_OK) return rc;
+            a1.w_f = p.w_f;
+            RpArgs r;
+            if (!make_rp_args(a1, x_hi, &a2, st.w_f, r)) return HAWQ_ERR_UNSUPPORTED;   // (the plan checked shapes and types)
+            rc = launch_conv_rp(r, true, stream);
+            if (rc != HAWQ_OK) return rc;
+            if (ev && hipEventRecord(ev[2 * s + 1], stream) != hipSuccess) return HAWQ_ERR_DEVICE;
+            continue;
+        }
         const uint8_t *in = st.in >= 0 ? tptr(st.in) : (const uint8_t *)x;
         uint8_t *outp = st.out >= 0 ? tptr(st.out) : (uint8_t *)logits;
         switch (st.kind) {
@@ -738,6 +815,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                                 outp, true, a, x_hi);
             a.corun = n_parts > 1;
             a.w_t = st.w_t;
+            a.w_f = st.w_f;
             if (rc == HAWQ_OK) {
                 if (st.kind == STEP_STEM && st.fused_pool && conv_stem_eligible(a)) {
                     const Step &pool = net->steps[s + 1];
