@@ -115,6 +115,8 @@ def load_library():
     lib.hawq_probe_mfma_peak.argtypes = [i32, ctypes.POINTER(ctypes.c_double)]
     lib.hawq_tune_set_split.restype = None
     lib.hawq_tune_set_split.argtypes = [i32]
+    lib.hawq_tune_set_fusion.restype = None
+    lib.hawq_tune_set_fusion.argtypes = [i32]
     lib.hawq_status_string.restype = ctypes.c_char_p
     lib.hawq_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -235,6 +237,11 @@ def hawq_tune_set_split(n_first):
 
 def hawq_noalloc_workspace_limit():
     return int(load_library().hawq_noalloc_workspace_limit())
+
+
+def hawq_tune_set_fusion(mode):
+    """Measurement hook: 1 = later networks fuse bottleneck tails wherever the kernel applies, 0 = the plan's rule."""
+    load_library().hawq_tune_set_fusion(int(mode))
 
 
 def hawq_net_num_layers(arch):

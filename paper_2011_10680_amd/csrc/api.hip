@@ -178,6 +178,11 @@ hawq_status dispatch_conv_dual(const ConvArgs &a, int x_hi, int xs_hi, hipStream
 
 }  // namespace hawq
 
+#ifdef HAWQ_RP_TIMING
+static long long *g_rp_timing = nullptr;
+extern "C" void hawq_debug_set_rp_timing(void *p) { g_rp_timing = (long long *)p; }
+#endif
+
 extern "C" {
 
 size_t hawq_conv_blocked_weights_bytes(const hawq_conv_desc *desc) {
@@ -235,6 +240,9 @@ hawq_status hawq_bottleneck_tail_int(const hawq_conv_desc *desc2, const void *x,
     RpArgs r;
     if (!make_rp_args(a1, x_hi, &a2, w3_fragments, r)) return HAWQ_ERR_UNSUPPORTED;
     if (a1.M == 0) return HAWQ_OK;
+#ifdef HAWQ_RP_TIMING
+    r.timing = g_rp_timing;
+#endif
     return launch_conv_rp(r, true, (hipStream_t)stream);
 }
 

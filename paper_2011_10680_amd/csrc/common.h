@@ -74,7 +74,9 @@ struct RpArgs {
     const int32_t *bias2, *b2;
     const uint8_t *c2;
     int32_t K2, lo2, hi2;
-    int32_t kg;              // plain form: stage-1 channels per workgroup (set by the launcher)
+#ifdef HAWQ_RP_TIMING
+    long long *timing;       // measurement build only: [workgroup][wave][6] cycle stamps
+#endif
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }

@@ -40,43 +40,55 @@ __device__ __forceinline__ int rp_stage_chan(const int32_t *bias, const int32_t 
     return 0;
 }
 
-// Epilogue of one lane: pixels T0, T0 + 1 of its four (MFMA column tiles) x 16 consecutive channels.  pc / pr: the lane's
-// first channel's entries.  resw[tp]: the 16 shortcut bytes of pixel tp (only read when has_res).  Result: out[tp] = the
-// 16 output bytes.  (Two pixels per call: a channel's parameters are read once for both, and the intermediate values of
-// all four pixels at once would not fit the register budget next to the accumulators and the prefetched weights.)
-template <int T0>
-__device__ __forceinline__ void rp_epilogue(const v16i (&acc)[4], const RpChan *pc, const RpRes *pr, const bool has_res,
-                                            const bool res_signed, const uint32_t (&resw)[4][4], const int wide, const int lo_,
-                                            const int hi_, uint32_t (&out)[4][4]) {
-    if (wide) {   // exact general form: 64-bit products, shifts and clamp
+// Epilogue of one lane: NT (1 or 2) of its pixels (MFMA column tiles T0, T0 + 1) x 16 consecutive channels.  pc / pr: the
+// lane's first channel's entries.  resw[t]: the 16 shortcut bytes of pixel T0 + t (only read when has_res).  Result:
+// out[t] = the 16 output bytes.  (Two pixels per call: a channel's parameters are read once for both, and the
+// intermediate values of all pixels at once would not fit the register budget next to the accumulators and the
+// prefetched weights.)
+template <int NT>
+__device__ __forceinline__ void rp_epilogue(const v16i &acc0, const v16i &acc1, const RpChan *pc, const RpRes *pr, const bool has_res,
+                                            const bool res_signed, const uint32_t (&resw)[2][4], const int wide, const int lo_,
+                                            const int hi_, uint32_t (&out)[2][4]) {
+    if (wide) {
+        // Exact general form (64-bit products, shifts and clamp), written as a compact loop because it is cold: every round
+        // handles element 0 of the accumulators and the low shortcut byte, then rotates both by one element, and shifts the
+        // new output byte in from the top of the 128-bit result (after sixteen rounds everything is back in place).
         const uint32_t sgn = res_signed ? 0x80u : 0u;   // signed bytes: subtract 256 where bit 7 is set
+        v16i t0 = acc0, t1 = acc1;
+        uint32_t r0[4] = {resw[0][0], resw[0][1], resw[0][2], resw[0][3]};
+        uint32_t r1[4] = {resw[1][0], resw[1][1], resw[1][2], resw[1][3]};
+        uint32_t o0[4] = {0, 0, 0, 0}, o1[4] = {0, 0, 0, 0};
+#pragma unroll 1
+        for (int i = 0; i < 16; ++i) {
+            const RpChan p = pc[i];
+            const RpRes q = has_res ? pr[i] : RpRes{0, 1};   // (no shortcut: the bytes are zero and rq(0, 0, 1) = 0)
+            const uint32_t w0 = r0[0] & 0xff, w1 = r1[0] & 0xff;
+            const int64_t v0 = rq64(t0[0] + p.bias, p.b, p.c) + rq64((int32_t)w0 - (int32_t)((w0 & sgn) << 1), q.rb, q.rc);
+            const int64_t v1 = rq64(t1[0] + p.bias, p.b, p.c) + rq64((int32_t)w1 - (int32_t)((w1 & sgn) << 1), q.rb, q.rc);
+            const uint32_t b0 = (uint32_t)clamp64(v0, lo_, hi_) & 0xff, b1 = (uint32_t)clamp64(v1, lo_, hi_) & 0xff;
 #pragma unroll
-        for (int tp = T0; tp < T0 + 2; ++tp) {
-            uint32_t ow[4] = {0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const RpChan p = pc[i];
-                int64_t v = rq64(acc[tp][i] + p.bias, p.b, p.c);
-                // (no shortcut: the word is zero and so is its term -- rq(0, rb, rc) = 0 for rb < 2^31)
-                const uint32_t w = (resw[tp][i >> 2] >> (8 * (i & 3))) & 0xff;
-                const int32_t r = (int32_t)w - (int32_t)((w & sgn) << 1);
-                const RpRes q = has_res ? pr[i] : RpRes{0, 1};
-                v += rq64(r, q.rb, q.rc);
-                ow[i >> 2] |= (uint32_t)(clamp64(v, lo_, hi_) & 0xff) << (8 * (i & 3));
+            for (int j = 0; j < 3; ++j) {
+                o0[j] = (o0[j] >> 8) | (o0[j + 1] << 24); o1[j] = (o1[j] >> 8) | (o1[j + 1] << 24);
+                r0[j] = (r0[j] >> 8) | (r0[j + 1] << 24); r1[j] = (r1[j] >> 8) | (r1[j + 1] << 24);
             }
-            out[tp][0] = ow[0]; out[tp][1] = ow[1]; out[tp][2] = ow[2]; out[tp][3] = ow[3];
+            o0[3] = (o0[3] >> 8) | (b0 << 24); o1[3] = (o1[3] >> 8) | (b1 << 24);
+            r0[3] >>= 8; r1[3] >>= 8;
+            t0 = __builtin_shufflevector(t0, t0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 0);
+            t1 = __builtin_shufflevector(t1, t1, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 0);
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { out[0][j] = o0[j]; out[1][j] = o1[j]; }
         return;
     }
     int32_t lo = lo_, hi = hi_;
     asm volatile("" : "+v"(lo), "+v"(hi));   // in vector registers: the clamp is then one three-operand median
-    int32_t y[4][16];   // (only rows T0, T0 + 1 are used)
+    int32_t y[2][16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int32_t bs = pc[i].bs;
         const int64_t Rs = pc[i].Rs;
-#pragma unroll
-        for (int tp = T0; tp < T0 + 2; ++tp) y[tp][i] = (int32_t)(((int64_t)acc[tp][i] * (int64_t)bs + Rs) >> 32);
+        y[0][i] = (int32_t)(((int64_t)acc0[i] * (int64_t)bs + Rs) >> 32);
+        if (NT == 2) y[1][i] = (int32_t)(((int64_t)acc1[i] * (int64_t)bs + Rs) >> 32);
     }
     if (has_res) {
         auto add_res = [&](auto sc) {
@@ -86,10 +98,10 @@ __device__ __forceinline__ void rp_epilogue(const v16i (&acc)[4], const RpChan *
                 const RpRes p = pr[i];
                 const int32_t rr = (int32_t)(1u << ((p.rc - 1) & 31));
 #pragma unroll
-                for (int tp = T0; tp < T0 + 2; ++tp) {
-                    const int32_t r = S ? __builtin_amdgcn_sbfe((int32_t)resw[tp][i >> 2], 8 * (i & 3), 8)
-                                        : (int32_t)__builtin_amdgcn_ubfe(resw[tp][i >> 2], 8 * (i & 3), 8);
-                    y[tp][i] += (__mul24(r, p.rb) + rr) >> p.rc;
+                for (int t = 0; t < NT; ++t) {
+                    const int32_t r = S ? __builtin_amdgcn_sbfe((int32_t)resw[t][i >> 2], 8 * (i & 3), 8)
+                                        : (int32_t)__builtin_amdgcn_ubfe(resw[t][i >> 2], 8 * (i & 3), 8);
+                    y[t][i] += (__mul24(r, p.rb) + rr) >> p.rc;
                 }
             }
         };
@@ -97,138 +109,94 @@ __device__ __forceinline__ void rp_epilogue(const v16i (&acc)[4], const RpChan *
         else add_res(std::false_type{});
     }
 #pragma unroll
-    for (int tp = T0; tp < T0 + 2; ++tp) {
+    for (int t = 0; t < NT; ++t) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            int32_t t;
-            asm("v_med3_i32 %0, %1, %2, %3" : "=v"(t) : "v"(y[tp][i]), "v"(lo), "v"(hi));
-            y[tp][i] = t;
+            int32_t v;
+            asm("v_med3_i32 %0, %1, %2, %3" : "=v"(v) : "v"(y[t][i]), "v"(lo), "v"(hi));
+            y[t][i] = v;
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {   // low bytes of 4 values -> one dword
-            const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 1], (uint32_t)y[tp][4 * q], 0x0c0c0400u);
-            const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[tp][4 * q + 3], (uint32_t)y[tp][4 * q + 2], 0x04000c0cu);
-            out[tp][q] = t0 | t1;
+            const uint32_t t0 = __builtin_amdgcn_perm((uint32_t)y[t][4 * q + 1], (uint32_t)y[t][4 * q], 0x0c0c0400u);
+            const uint32_t t1 = __builtin_amdgcn_perm((uint32_t)y[t][4 * q + 3], (uint32_t)y[t][4 * q + 2], 0x04000c0cu);
+            out[t][q] = t0 | t1;
         }
     }
+    if (NT == 1) out[1][0] = out[1][1] = out[1][2] = out[1][3] = 0;   // (every element written on every path keeps the array in registers)
 }
 
-// CCH: input channels / 64 of the 3x3 convolution.  WC x WP = 8 waves: WC along channels (32 each per pass), WP along
-// pixels (128 each).  WMAX: largest image width the static LDS patch is sized for.  FUSED: second phase (1x1 on the
-// requantised tile, K1 == 64 CCH channels wide, + shortcut).  Without it a workgroup computes `kg` channels of the 3x3
-// convolution's output (grid: tiles x K1 / kg) and its epilogue stores to memory (optionally adding a shortcut).
-template <int CCH, int WC, int WP, int WMAX, bool FUSED>
+// CCH: input channels / 64 of the 3x3 convolution.  WC x WP = 8 waves: WC along channels (32 each), WP along pixels
+// (32 TP each: TP MFMA column tiles per wave).  WMAX: largest image width the static LDS patch is sized for.  FUSED:
+// second phase (1x1 on the requantised tile, K1 == 64 CCH == 32 WC channels wide, + shortcut).  Without it a workgroup
+// computes 32 WC channels of the 3x3 convolution's output (grid: tiles x K1 / (32 WC)) and its epilogue stores to memory
+// (optionally adding a shortcut).
+template <int CCH, int WC, int WP, int TP, int WMAX, bool FUSED>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 conv_rp_kernel(const RpArgs a) {
     static_assert(WC * WP == 8, "eight waves");
-    static_assert(CCH >= 2, "the double-buffered fragment registers assume an even number of K-steps per filter row");
+    static_assert(!FUSED || 32 * WC == 64 * CCH, "fused: the workgroup owns every channel of the intermediate tile");
     constexpr int T = 512;
-    constexpr int BP = 128 * WP;              // output pixels per tile
+    constexpr int WPX = 32 * TP;              // pixels per wave
+    constexpr int BP = WPX * WP;              // output pixels per tile
     constexpr int C = 64 * CCH;
+    constexpr int KG = 32 * WC;               // stage-1 channels of a workgroup
     constexpr int PITCH = C + 16;             // bytes per LDS row (patch and, fused, the intermediate tile: K1 == C)
-    constexpr int ROWS = BP + 2 * WMAX + 2;   // patch rows; row ROWS is the row of zeros
+    constexpr int ROWS = (BP + 2 * WMAX + 2 + 15) / 16 * 16;   // patch rows (rounded up); rows ROWS .. ROWS + 15 hold zeros
     constexpr int S1 = 9 * CCH;               // K-steps of the 3x3 convolution
     constexpr int S2 = CCH;                   // K-steps of the fused 1x1 convolution (K1 / 64)
-    constexpr int NCH1 = FUSED ? C : 512;     // stage-1 channels a workgroup can own
     constexpr int NCH2 = FUSED ? 4 * C : 1;   // stage-2 channels (at most)
-    __shared__ __attribute__((aligned(16))) uint8_t patch[(ROWS + 1) * PITCH];
+    __shared__ __attribute__((aligned(16))) uint8_t patch[(ROWS + 16) * PITCH];
     __shared__ __attribute__((aligned(16))) uint8_t tile[FUSED ? BP * PITCH : 16];
-    __shared__ RpChan par1[NCH1];
+    __shared__ RpChan par1[KG];
     __shared__ RpChan par2[NCH2];
-    __shared__ RpRes pres[FUSED ? NCH2 : NCH1];
+    __shared__ RpRes pres[FUSED ? NCH2 : KG];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = wave % WC, wp = wave / WC;
     const int rho = lane & 31, khalf = lane >> 5;
+#ifdef HAWQ_RP_TIMING
+    long long tstamp[6] = {0, 0, 0, 0, 0, 0};
+#define RP_STAMP(i) tstamp[i] = (long long)__builtin_readcyclecounter()
+#define RP_STAMP_OUT() do { if (a.timing && lane == 0) { for (int q_ = 0; q_ < 6; ++q_) a.timing[((long long)blockIdx.x * 8 + wave) * 6 + q_] = tstamp[q_]; } } while (0)
+#else
+#define RP_STAMP(i) do { } while (0)
+#define RP_STAMP_OUT() do { } while (0)
+#endif
+    RP_STAMP(0);
 
-    const int ncg = FUSED ? 1 : a.K1 / a.kg;                        // channel groups (workgroups per tile)
+    const int ncg = FUSED ? 1 : a.K1 / KG;                           // channel groups (workgroups per tile)
     const uint32_t L = xcd_remap(blockIdx.x, gridDim.x);
     const int tile_i = (int)(L / (uint32_t)ncg), cg = (int)(L % (uint32_t)ncg);
     const int m0 = tile_i * BP;
-    const int W = a.W, H = a.H, HW = a.H * a.W;
-    const int kg = FUSED ? C : a.kg;                                 // stage-1 channels of this workgroup
-    const int kbase1 = cg * kg;
-    const int npass1 = kg / (32 * WC);
+    const int W = a.W;
+    const int kbase1 = cg * KG;
+    const bool has_res1 = !FUSED && a.res != nullptr;
 
-    // ---- patch: flat input pixels m0 - W - 1 ... m0 + BP + W of every channel, one contiguous range of memory ----
-    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.M * C), 0x00020000);
+    // ---- prologue: every global load of it is issued before the first one is waited for ----
+    // patch: flat input pixels m0 - W - 1 ... m0 + BP + W of every channel, one contiguous range of memory
+    constexpr int CPR = C / 16;                                  // 16-byte chunks per pixel
+    constexpr int NIT = (ROWS * CPR + T - 1) / T;
+    const int nchunk = (BP + 2 * W + 2) * CPR;
+    v4i pv[NIT];
     {
-        constexpr int CPR = C / 16;                                  // 16-byte chunks per pixel
-        constexpr int NIT = (ROWS * CPR + T - 1) / T;
-        const int nchunk = (BP + 2 * W + 2) * CPR;
+        const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.M * C), 0x00020000);
         const int64_t src0 = ((int64_t)m0 - W - 1) * C;
-        v4i v[NIT];
 #pragma unroll
         for (int j = 0; j < NIT; ++j) {
             const int i = tid + j * T;
             // outside the tensor (before the first or after the last pixel) the offset is out of range: zeros
             const int64_t o = src0 + (int64_t)i * 16;
             const uint32_t off = (i < nchunk && o >= 0) ? (uint32_t)o : 0x80000000u;
-            v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < NIT; ++j) {
-            const int i = tid + j * T;
-            if (i < nchunk) *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 16) = v[j];
-        }
-        if (tid < CPR) *(v4i *)(patch + ROWS * PITCH + tid * 16) = (v4i){0, 0, 0, 0};
-    }
-    // ---- per-channel parameters ----
-    int wide = 0;
-    const bool has_res1 = !FUSED && a.res != nullptr;
-    for (int i = tid; i < kg; i += T) {
-        RpChan p;
-        wide |= rp_stage_chan(a.bias1, a.b1, a.c1, kbase1 + i, p);
-        par1[i] = p;
-        if (has_res1) {
-            RpRes q;
-            q.rb = a.res_b[kbase1 + i]; q.rc = a.res_c[kbase1 + i];
-            if (q.rc > 31 || q.rb >= (1 << 22)) wide = 1;
-            pres[i] = q;
+            pv[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)off, 0, 0);
         }
     }
-    if constexpr (FUSED) {
-        for (int i = tid; i < a.K2; i += T) {
-            RpChan p;
-            wide |= rp_stage_chan(a.bias2, a.b2, a.c2, i, p);
-            par2[i] = p;
-            RpRes q;
-            q.rb = a.res_b[i]; q.rc = a.res_c[i];
-            if (q.rc > 31 || q.rb >= (1 << 22)) wide = 1;
-            pres[i] = q;
-        }
-    }
-
-    // ---- the lane's four pixels: LDS row offsets, and which of the nine taps lie inside the image ----
-    int base[4];
-    uint32_t vmask[4];
-    uint32_t yoff[4];   // byte offset of the pixel's first channel in the tensor this launch stores (out of range: no such pixel)
-    const int Ky = FUSED ? a.K2 : a.K1;
-#pragma unroll
-    for (int tp = 0; tp < 4; ++tp) {
-        const int p = wp * 128 + tp * 32 + rho;
-        const int64_t m = (int64_t)m0 + p;
-        const bool pvalid = m < a.M;
-        yoff[tp] = pvalid ? (uint32_t)(m * Ky) : 0x80000000u;
-        const int rem = pvalid ? (int)(m % HW) : 0;
-        const int yy = rem / W, xx = rem - yy * W;
-        uint32_t mask = 0;
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-#pragma unroll
-            for (int s = 0; s < 3; ++s)
-                if (pvalid && (unsigned)(yy + r - 1) < (unsigned)H && (unsigned)(xx + s - 1) < (unsigned)W) mask |= 1u << (r * 3 + s);
-        vmask[tp] = mask;
-        base[tp] = p * PITCH + khalf * 16;
-    }
-    const int zaddr = ROWS * PITCH + khalf * 16;
-
-    // ---- weight stream of this wave: channel groups  (kbase1 / 32) + wc * npass1 + pass,  K-steps in order ----
+    // weight stream of this wave: channel group  kbase1 / 32 + wc,  K-steps in order, three steps ahead
     const int G1 = (a.K1 + 31) / 32;
     __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w1f, 0, (int)((int64_t)G1 * S1 * 2048), 0x00020000);
     const int lane16 = lane * 16;
-    int woff = __builtin_amdgcn_readfirstlane((kbase1 / 32 + wc * npass1) * S1 * 2048);   // byte offset of the next K-step to fetch
+    int woff = __builtin_amdgcn_readfirstlane((kbase1 / 32 + wc) * S1 * 2048);   // byte offset of the next K-step to fetch
     v4i af[3][2];
 #pragma unroll
     for (int d = 0; d < 3; ++d) {
@@ -236,112 +204,189 @@ conv_rp_kernel(const RpArgs a) {
         af[d][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
         woff += 2048;
     }
-
-    wide = __syncthreads_or(wide);   // patch and parameters are in LDS
-
-    v16i acc[4];
-    v4i bf[2][2][4];   // [buffer][half of the K-step][pixel tile]
-    int sel[4];
-    // row offsets of tap (r, s) for the lane's four pixels (the zero row where the tap is outside the image)
-    auto set_tap = [&](int r, int s) {
-        const int tapoff = (r * W + s) * PITCH;
-        const int bit = r * 3 + s;
+    // per-channel parameters: thread i stages channel i of stage 1 and channels i, i + 512, ... of stage 2
+    constexpr int NP2 = FUSED ? (NCH2 + T - 1) / T : 0;
+    int32_t q1b = 0, q1c = 1, q1bias = 0, q1rb = 0, q1rc = 1;
+    int32_t q2b[NP2 + 1], q2c[NP2 + 1], q2bias[NP2 + 1], q2rb[NP2 + 1], q2rc[NP2 + 1];
+    if (tid < KG) {
+        q1b = a.b1[kbase1 + tid]; q1c = a.c1[kbase1 + tid]; q1bias = a.bias1[kbase1 + tid];
+        if (has_res1) { q1rb = a.res_b[kbase1 + tid]; q1rc = a.res_c[kbase1 + tid]; }
+    }
+    if constexpr (FUSED) {
 #pragma unroll
-        for (int tp = 0; tp < 4; ++tp) sel[tp] = ((vmask[tp] >> bit) & 1u) ? base[tp] + tapoff : zaddr;
-    };
-    auto read_b1 = [&](auto bufc, auto ccc) {
-        constexpr int buf = decltype(bufc)::value, cc = decltype(ccc)::value;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp) bf[buf][kk][tp] = *(const v4i *)(patch + sel[tp] + cc * 64 + kk * 32);
-    };
-    auto mfma8 = [&](auto bufc, const v4i(&aw)[2]) {
-        constexpr int buf = decltype(bufc)::value;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp) acc[tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aw[kk], bf[buf][kk][tp], acc[tp], 0, 0, 0);
-    };
-    using B0 = std::integral_constant<int, 0>;
-    using B1 = std::integral_constant<int, 1>;
-
-    // y of the stage whose epilogue stores to memory
-    const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)((int64_t)a.M * Ky), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)(a.res ? a.res : a.x), 0, a.res ? (int)((int64_t)a.M * Ky) : 0, 0x00020000);
-    const bool res_signed = a.res_dt == HAWQ_S8;
-    uint32_t resw[4][4] = {};
-    auto load_res = [&](int ch) {   // the lane's 16 shortcut bytes of each of its pixels, channels ch .. ch + 15
-#pragma unroll
-        for (int tp = 0; tp < 4; ++tp) {
-            // (an out-of-range pixel stays out of range: the tensors are below 2 GiB, ch below 2^16)
-            const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
-            resw[tp][0] = (uint32_t)t[0]; resw[tp][1] = (uint32_t)t[1]; resw[tp][2] = (uint32_t)t[2]; resw[tp][3] = (uint32_t)t[3];
-        }
-    };
-    auto store_y = [&](int ch, const uint32_t (&o)[4][4]) {
-#pragma unroll
-        for (int tp = 0; tp < 4; ++tp) {
-            __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)o[tp][0], (int)o[tp][1], (int)o[tp][2], (int)o[tp][3]}, rsrc_y, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
-        }
-    };
-
-    // ================= phase 1: the 3x3 convolution =================
-    if (has_res1) load_res(kbase1 + wc * npass1 * 32 + khalf * 16);
-    for (int it = 0; it < 3 * npass1; ++it) {
-        const int r = it % 3, pass = it / 3;
-        if (r == 0) {
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[tp][i] = 0;
-            // (the pixel fragments of a pass's first step are not prefetched across the previous pass's epilogue: the
-            // epilogue needs the registers)
-            set_tap(0, 0);
-            read_b1(B0{}, std::integral_constant<int, 0>{});
-        }
-        // one filter row: taps (r, 0..2) x CCH channel chunks; the pixel fragments of step i + 1 are read while step i
-        // is multiplied, the weight fragments of step i + 3 are requested as soon as step i has issued
-        static_for<0, 3 * CCH>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            constexpr int slot = i % 3;
-            constexpr int cur = i % 2, nxt = (i + 1) % 2;
-            constexpr int jn = i + 1;                              // the step to prefetch pixel fragments for
-            if constexpr (jn < 3 * CCH) {
-                if constexpr (jn % CCH == 0) set_tap(r, jn / CCH);
-                read_b1(std::integral_constant<int, nxt>{}, std::integral_constant<int, jn % CCH>{});
-            } else if (r != 2) {
-                set_tap(r + 1, 0);
-                read_b1(std::integral_constant<int, nxt>{}, std::integral_constant<int, 0>{});
-            }
-            mfma8(std::integral_constant<int, cur>{}, af[slot]);
-            af[slot][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
-            af[slot][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
-            woff += 2048;
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        if (r == 2) {
-            const int chl = (wc * npass1 + pass) * 32 + khalf * 16;   // the lane's first channel within the workgroup's range
-            uint32_t o[4][4];
-            __builtin_amdgcn_sched_barrier(0);
-            rp_epilogue<0>(acc, par1 + chl, pres + chl, has_res1, res_signed, resw, wide, a.lo1, a.hi1, o);
-            __builtin_amdgcn_sched_barrier(0);
-            rp_epilogue<2>(acc, par1 + chl, pres + chl, has_res1, res_signed, resw, wide, a.lo1, a.hi1, o);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (FUSED) {
-#pragma unroll
-                for (int tp = 0; tp < 4; ++tp)
-                    *(v4i *)(tile + (wp * 128 + tp * 32 + rho) * PITCH + chl) = (v4i){(int)o[tp][0], (int)o[tp][1], (int)o[tp][2], (int)o[tp][3]};
-            } else {
-                if (has_res1 && pass + 1 < npass1) load_res(kbase1 + chl + 32);
-                store_y(kbase1 + chl, o);
-            }
+        for (int j = 0; j < NP2; ++j) {
+            const int k = tid + j * T;
+            const bool ok = k < a.K2;
+            q2b[j] = ok ? a.b2[k] : 0; q2c[j] = ok ? a.c2[k] : 1; q2bias[j] = ok ? a.bias2[k] : 0;
+            q2rb[j] = ok ? a.res_b[k] : 0; q2rc[j] = ok ? a.res_c[k] : 1;
         }
     }
 
-    // ================= phase 2: 1x1 on the requantised tile, + shortcut =================
+    // ---- the lane's pixels: LDS row offsets, and which of the nine taps lie inside the image ----
+    // A tap outside the image reads zeros: its lane is redirected to one of sixteen rows of zeros, the one congruent to the
+    // row it would have read (mod 16) -- the sixteen lanes of an LDS access then still fall into sixteen different banks.
+    int base[TP];
+    uint32_t vmask[TP];
+    uint32_t yoff[TP];   // byte offset of the pixel's first channel in the tensor this launch stores (out of range: no such pixel)
+    const int Ky = FUSED ? a.K2 : a.K1;
+    {
+        const int H = a.H, HW = a.H * a.W;
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            const int p = wp * WPX + tp * 32 + rho;
+            const int64_t m = (int64_t)m0 + p;
+            const bool pvalid = m < a.M;
+            yoff[tp] = pvalid ? (uint32_t)(m * Ky) : 0x80000000u;
+            const int rem = pvalid ? (int)(m % HW) : 0;
+            const int yy = rem / W, xx = rem - yy * W;
+            uint32_t mask = 0;
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    if (pvalid && (unsigned)(yy + r - 1) < (unsigned)H && (unsigned)(xx + s - 1) < (unsigned)W) mask |= 1u << (r * 3 + s);
+            vmask[tp] = mask;
+            base[tp] = p * PITCH + khalf * 16;
+        }
+    }
+
+    // ---- LDS: patch, rows of zeros, parameters ----
+#pragma unroll
+    for (int j = 0; j < NIT; ++j) {
+        const int i = tid + j * T;
+        if (i < nchunk) *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 16) = pv[j];
+    }
+    for (int i = tid; i < 16 * CPR; i += T) *(v4i *)(patch + (ROWS + i / CPR) * PITCH + (i % CPR) * 16) = (v4i){0, 0, 0, 0};
+    int wide = 0;
+    auto stage = [&](int32_t bias, int32_t b, int32_t c, RpChan &o) {
+        o.b = b; o.c = c; o.bias = bias; o.bs = 0; o.Rs = 0;
+        if (c > 32 || ((int64_t)b >> (c - 1)) != 0) { wide = 1; return; }
+        const int64_t R = (int64_t)bias * (int64_t)b + ((int64_t)1 << (c - 1));
+        o.bs = (int32_t)((uint32_t)b << (32 - c));
+        o.Rs = (int64_t)((uint64_t)R << (32 - c));
+    };
+    if (tid < KG) {
+        RpChan p;
+        stage(q1bias, q1b, q1c, p);
+        par1[tid] = p;
+        if (has_res1) {
+            if (q1rc > 31 || q1rb >= (1 << 22)) wide = 1;
+            pres[tid] = RpRes{q1rb, q1rc};
+        }
+    }
     if constexpr (FUSED) {
-        const int npass2 = a.K2 / (32 * WC);
+#pragma unroll
+        for (int j = 0; j < NP2; ++j) {
+            const int k = tid + j * T;
+            if (k < a.K2) {
+                RpChan p;
+                stage(q2bias[j], q2b[j], q2c[j], p);
+                par2[k] = p;
+                if (q2rc[j] > 31 || q2rb[j] >= (1 << 22)) wide = 1;
+                pres[k] = RpRes{q2rb[j], q2rc[j]};
+            }
+        }
+    }
+    wide = __syncthreads_or(wide);   // patch and parameters are in LDS
+    RP_STAMP(1);
+
+    v16i acc[TP];
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[tp][i] = 0;
+    v4i bf[2][TP];   // pixel fragments: [buffer][pixel tile], one half K-step (32 reduction elements) each
+    int sel[TP];
+    // row offsets of tap (r, s) for the lane's pixels
+    auto set_tap = [&](int r, int s) {
+        const int shift = r * W + s;
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            const int p = wp * WPX + tp * 32 + rho;
+            sel[tp] = ((vmask[tp] >> (r * 3 + s)) & 1u) ? base[tp] + shift * PITCH : (ROWS + ((p + shift) & 15)) * PITCH + khalf * 16;
+        }
+    };
+    auto mfma_row = [&](auto bufc, const v4i &aw) {
+        constexpr int buf = decltype(bufc)::value;
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) acc[tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aw, bf[buf][tp], acc[tp], 0, 0, 0);
+    };
+
+    const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)((int64_t)a.M * Ky), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)(a.res ? a.res : a.x), 0, a.res ? (int)((int64_t)a.M * Ky) : 0, 0x00020000);
+    const bool res_signed = a.res_dt == HAWQ_S8;
+    // The lane's shortcut bytes, fetched a whole pass of the second convolution ahead of their use: two buffers where the
+    // registers allow it (RB = 2), else one, refilled right after the epilogue that read it.
+    constexpr int RB = (FUSED && TP <= 4) ? 2 : 1;
+    uint32_t resw[RB][TP + 1][4] = {};   // (one spare row: the last epilogue call of an odd TP reads a pair)
+    auto load_res = [&](auto bc, int ch) {   // 16 shortcut bytes of each of the lane's pixels, channels ch .. ch + 15
+        constexpr int rb = decltype(bc)::value;
+#pragma unroll
+        for (int tp = 0; tp < TP; ++tp) {
+            // (an out-of-range pixel stays out of range: the tensors are below 2 GiB, ch below 2^16)
+            const v4i t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_r, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
+            resw[rb][tp][0] = (uint32_t)t[0]; resw[rb][tp][1] = (uint32_t)t[1]; resw[rb][tp][2] = (uint32_t)t[2]; resw[rb][tp][3] = (uint32_t)t[3];
+        }
+    };
+    using R0 = std::integral_constant<int, 0>;
+    // epilogue of all the lane's pixels, two at a time; `put(tp, bytes)` stores one pixel's 16 bytes
+    auto epilogue = [&](auto bc, const RpChan *pc, const RpRes *pr, bool has_res, int lo, int hi, auto put) {
+        constexpr int rb = decltype(bc)::value;
+        static_for<0, (TP + 1) / 2>([&](auto jc) {
+            constexpr int t0 = 2 * decltype(jc)::value;
+            constexpr int nt = t0 + 1 < TP ? 2 : 1;
+            const uint32_t rw[2][4] = {{resw[rb][t0][0], resw[rb][t0][1], resw[rb][t0][2], resw[rb][t0][3]},
+                                       {resw[rb][t0 + 1][0], resw[rb][t0 + 1][1], resw[rb][t0 + 1][2], resw[rb][t0 + 1][3]}};
+            uint32_t o[2][4];
+            rp_epilogue<nt>(acc[t0], acc[nt == 2 ? t0 + 1 : t0], pc, pr, has_res, res_signed, rw, wide, lo, hi, o);
+            put(std::integral_constant<int, t0>{}, o[0]);
+            if constexpr (nt == 2) put(std::integral_constant<int, t0 + 1>{}, o[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ================= phase 1: the 3x3 convolution, 9 CCH K-steps, fully unrolled =================
+    // Half-step h (32 reduction elements) = K-step h / 2, half h % 2.  While half-step h is multiplied, the pixel fragments
+    // of half-step h + 1 are read into the other buffer; the weight fragments of K-step t + 3 are requested as soon as
+    // K-step t has issued.
+    const int chl = wc * 32 + khalf * 16;   // the lane's first channel within the workgroup's range
+    if (has_res1) load_res(R0{}, kbase1 + chl);
+    set_tap(0, 0);
+#pragma unroll
+    for (int tp = 0; tp < TP; ++tp) bf[0][tp] = *(const v4i *)(patch + sel[tp]);
+    static_for<0, 2 * S1>([&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+        constexpr int t = h / 2, kk = h % 2;
+        constexpr int hn = h + 1, tn = hn / 2, kn = hn % 2;          // the half-step to prefetch
+        if constexpr (hn < 2 * S1) {
+            if constexpr (kn == 0 && tn % CCH == 0) set_tap((tn / CCH) / 3, (tn / CCH) % 3);
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) bf[hn % 2][tp] = *(const v4i *)(patch + sel[tp] + (tn % CCH) * 64 + kn * 32);
+        }
+        mfma_row(std::integral_constant<int, h % 2>{}, af[t % 3][kk]);
+        if constexpr (kk == 1) {
+            if constexpr (t + 3 < S1) {
+                af[t % 3][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
+                af[t % 3][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
+                woff += 2048;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    RP_STAMP(2);
+
+    auto put_y = [&](int ch) {
+        return [&, ch](auto tpc, const uint32_t (&o)[4]) {
+            constexpr int tp = decltype(tpc)::value;
+            __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]}, rsrc_y, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
+        };
+    };
+    if constexpr (!FUSED) {
+        epilogue(R0{}, par1 + chl, pres + chl, has_res1, a.lo1, a.hi1, put_y(kbase1 + chl));
+    } else {
+        // ================= phase 2: 1x1 on the requantised tile, + shortcut =================
+        // the second convolution's first weights and shortcut bytes travel while the first one's epilogue runs
+        const int npass2 = a.K2 / KG;
         const int G2 = a.K2 / 32;
         rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w2f, 0, (int)((int64_t)G2 * S2 * 2048), 0x00020000);
         woff = __builtin_amdgcn_readfirstlane(wc * npass2 * S2 * 2048);
@@ -352,48 +397,70 @@ conv_rp_kernel(const RpArgs a) {
             ag[d][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
             woff += 2048;
         }
-        load_res(wc * npass2 * 32 + khalf * 16);
+        __builtin_amdgcn_sched_barrier(0);
+        epilogue(R0{}, par1 + chl, pres, false, a.lo1, a.hi1, [&](auto tpc, const uint32_t (&o)[4]) {
+            constexpr int tp = decltype(tpc)::value;
+            *(v4i *)(tile + (wp * WPX + tp * 32 + rho) * PITCH + chl) = (v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]};
+        });
+        const int ch0 = wc * npass2 * 32 + khalf * 16;   // the lane's first channel of pass 0
+        load_res(R0{}, ch0);
         __syncthreads();   // every wave's part of the tile is written
-        auto read_b2 = [&](auto bufc, auto stc) {
-            constexpr int buf = decltype(bufc)::value, st = decltype(stc)::value;
+        RP_STAMP(3);
+        // Phase 2 alternates a short burst of MFMAs with a long integer epilogue.  Waves w and w + 4 share a SIMD and leave
+        // the barrier together; delaying one of them by about one burst makes its MFMAs fall into the other's epilogue
+        // instead of both queueing for the matrix pipe and then for the vector ALU.
+        if (wave >= 4) __builtin_amdgcn_s_sleep(TP * S2 * 2 * 32 / 64);
+        // one pass: 32 output channels per wave; `bc`: which shortcut buffer this pass reads
+        auto pass2 = [&](auto bc, int pass) {
+            constexpr int rb = decltype(bc)::value;
+            // with two buffers the next pass's shortcut bytes are requested before this pass's MFMAs
+            if (RB == 2 && pass + 1 < npass2) load_res(std::integral_constant<int, (rb + 1) % RB>{}, ch0 + (pass + 1) * 32);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int tp = 0; tp < 4; ++tp) bf[buf][kk][tp] = *(const v4i *)(tile + base[tp] + st * 64 + kk * 32);
-        };
-        for (int pass = 0; pass < npass2; ++pass) {
-#pragma unroll
-            for (int tp = 0; tp < 4; ++tp)
+            for (int tp = 0; tp < TP; ++tp)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[tp][i] = 0;
-            read_b2(B0{}, std::integral_constant<int, 0>{});
-            static_for<0, S2>([&](auto ic) {
-                constexpr int i = decltype(ic)::value;
-                constexpr int cur = i % 2, nxt = (i + 1) % 2;
-                if constexpr (i + 1 < S2) read_b2(std::integral_constant<int, nxt>{}, std::integral_constant<int, i + 1>{});
-                mfma8(std::integral_constant<int, cur>{}, ag[i]);
-                ag[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
-                ag[i][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
-                woff += 2048;
+#pragma unroll
+            for (int tp = 0; tp < TP; ++tp) bf[0][tp] = *(const v4i *)(tile + base[tp]);
+            static_for<0, 2 * S2>([&](auto hc) {
+                constexpr int h = decltype(hc)::value;
+                constexpr int t = h / 2, kk = h % 2;
+                constexpr int hn = h + 1, tn = hn / 2, kn = hn % 2;
+                if constexpr (hn < 2 * S2) {
+#pragma unroll
+                    for (int tp = 0; tp < TP; ++tp) bf[hn % 2][tp] = *(const v4i *)(tile + base[tp] + tn * 64 + kn * 32);
+                }
+#ifndef HAWQ_RP_ABL_NO_P2_MFMA
+                mfma_row(std::integral_constant<int, h % 2>{}, ag[t][kk]);
+#else
+                asm volatile("" :: "v"(ag[t][kk]), "v"(bf[h % 2][0]), "v"(bf[h % 2][TP - 1]));
+#endif
+                if constexpr (kk == 1) {   // the same K-step of the next pass (past the last pass: out of range, zeros, unused)
+                    ag[t][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
+                    ag[t][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
+                    woff += 2048;
+                }
                 __builtin_amdgcn_sched_barrier(0);
             });
-            const int ch = (wc * npass2 + pass) * 32 + khalf * 16;
-            uint32_t o[4][4];
-            __builtin_amdgcn_sched_barrier(0);
-            rp_epilogue<0>(acc, par2 + ch, pres + ch, true, res_signed, resw, wide, a.lo2, a.hi2, o);
-            __builtin_amdgcn_sched_barrier(0);
-            rp_epilogue<2>(acc, par2 + ch, pres + ch, true, res_signed, resw, wide, a.lo2, a.hi2, o);
-            __builtin_amdgcn_sched_barrier(0);
-            if (pass + 1 < npass2) load_res(ch + 32);
-            store_y(ch, o);
+            const int ch = ch0 + pass * 32;
+            epilogue(bc, par2 + ch, pres + ch, true, a.lo2, a.hi2, put_y(ch));
+            if (RB == 1 && pass + 1 < npass2) load_res(R0{}, ch + 32);
+            if (pass == 0) RP_STAMP(4);
+        };
+        for (int pass = 0; pass < npass2; pass += 2) {
+            pass2(R0{}, pass);
+            if (pass + 1 < npass2) pass2(std::integral_constant<int, 1 % RB>{}, pass + 1);
         }
     }
+    RP_STAMP(5);
+    RP_STAMP_OUT();
 }
 
 // ---- host side ----
 
-// Which instantiation serves the request; 0 = none.  C = 128: tiles of 256 pixels (4 waves along channels x 2 along
-// pixels), image widths up to 28; C = 256: tiles of 128 pixels (8 x 1), widths up to 14 (fused) or 28 (plain).
+// Which instantiation serves the request; 0 = none.  C = 128: tiles of 448 pixels (4 waves along channels x 2 along
+// pixels x 7 MFMA column tiles), image widths up to 28; C = 256: tiles of 128 pixels (8 x 1 x 4), widths up to 14 (fused)
+// or 28 (plain).  (A 28 x 28 layer at batch 128 has 100352 pixels: 224 tiles of 448 keep every tile in one round on 256
+// compute units, where 392 tiles of 256 need two.)
 static int rp_variant(const RpArgs &a, bool fused) {
     if (a.C % 64 != 0 || a.M <= 0 || a.H <= 0 || a.W <= 0) return 0;
     const int cch = a.C / 64;
@@ -410,16 +477,22 @@ static int rp_variant(const RpArgs &a, bool fused) {
 
 bool conv_rp_shape_ok(const RpArgs &a, bool fused) { return rp_variant(a, fused) != 0; }
 
-hawq_status launch_conv_rp(const RpArgs &a_in, bool fused, hipStream_t s) {
-    RpArgs a = a_in;
+hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s) {
     const int v = rp_variant(a, fused);
     if (v == 0) return HAWQ_ERR_UNSUPPORTED;
     auto tiles = [&](int bp) { return (uint32_t)(((int64_t)a.M + bp - 1) / bp); };
+    // small problems: narrower tiles put more compute units to work
     switch (v) {
-    case 1: a.kg = a.C; conv_rp_kernel<2, 4, 2, 28, true><<<tiles(256), 512, 0, s>>>(a); break;
-    case 2: a.kg = a.C; conv_rp_kernel<4, 8, 1, 14, true><<<tiles(128), 512, 0, s>>>(a); break;
-    case 3: a.kg = 128; conv_rp_kernel<2, 4, 2, 28, false><<<tiles(256) * (uint32_t)(a.K1 / a.kg), 512, 0, s>>>(a); break;
-    default: a.kg = 256; conv_rp_kernel<4, 8, 1, 28, false><<<tiles(128) * (uint32_t)(a.K1 / a.kg), 512, 0, s>>>(a); break;
+    case 1:
+        if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, true><<<tiles(448), 512, 0, s>>>(a);
+        else conv_rp_kernel<2, 4, 2, 4, 28, true><<<tiles(256), 512, 0, s>>>(a);
+        break;
+    case 2: conv_rp_kernel<4, 8, 1, 4, 14, true><<<tiles(128), 512, 0, s>>>(a); break;
+    case 3:
+        if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        else conv_rp_kernel<2, 4, 2, 4, 28, false><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        break;
+    default: conv_rp_kernel<4, 8, 1, 4, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a); break;
     }
     return check_launch();
 }

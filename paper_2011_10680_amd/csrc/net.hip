@@ -228,6 +228,7 @@ size_t workspace_one_part(const hawq_net *net, int N) { return slot_offset(net, 
 // gaps (measured 5 % on ResNet50 at batch 128 with equal parts; nothing at batch 64, a loss with three or four parts).
 // Returns the size of the first part, 0 for no split.
 int g_split_override = 0;   // 0: rule below; -1: never split; n > 0: first part of n images (measurement hook)
+int g_fuse_tails = 0;       // networks created from now on: 0 = the plan's rule for fused bottleneck tails, 1 = wherever the kernel applies, -1 = nowhere
 int split_first_part(const hawq_net *net, int N) {
     if (net->keep || !net->aux_stream) return 0;
     if (g_split_override < 0) return 0;
@@ -604,7 +605,12 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             probe.C = c2.desc.C; probe.K1 = c2.desc.K; probe.K2 = c3.desc.K; probe.H = c2.desc.H; probe.W = c2.desc.W; probe.M = 1;
             const bool types = c2.desc.x_dtype == HAWQ_U8 && c2.desc.y_dtype == HAWQ_U8 && c3.desc.y_dtype == HAWQ_U8 &&
                                c3.desc.res_dtype == HAWQ_U8 && c2.desc.x_hi <= 127;
-            if (c2.w_f && c3.w_f && types && c2.desc.R == 3 && c3.desc.R == 1 && conv_rp_shape_ok(probe, true)) {
+            // Measured on MI355X at batch 128 (ResNet50 stage 2 / stage 3 shapes): one launch 65 / 39 us, two launches
+            // (resident-pixel 3x3, then the streaming 1x1) 55 / 38 us -- the second convolution's integer epilogue binds, and
+            // in the fused kernel it runs at two waves per SIMD on the tiles' compute units only.  The plan therefore keeps
+            // two launches unless told otherwise (hawq_tune_set_fusion).
+            const bool want = g_fuse_tails > 0;
+            if (want && c2.w_f && c3.w_f && types && c2.desc.R == 3 && c3.desc.R == 1 && conv_rp_shape_ok(probe, true)) {
                 c2.tail_next = s3;
                 c3.tail_prev = s2;
                 net->tensors[c2.out].elems_per_image = 0;   // never stored
@@ -898,6 +904,8 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
 // Measurement hook (not part of the documented interface): 0 = the library's rule, -1 = never split a batch, n = first part of n images.
 // Set it before sizing the workspace.
 void hawq_tune_set_split(int32_t n_first) { g_split_override = n_first; }
+
+void hawq_tune_set_fusion(int32_t mode) { g_fuse_tails = mode > 0 ? 1 : (mode < 0 ? -1 : 0); }
 
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream) {

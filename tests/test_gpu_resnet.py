@@ -201,3 +201,31 @@ def test_forward_captured_in_a_graph_replays_like_eager(hawq):
     finally:
         hawq.hawq_tune_set_split(0)
         hn.close()
+
+
+@pytest.mark.parametrize("N,hw,int32_sc", [(5, 224, True), (9, 112, False), (3, 64, True)])
+def test_fused_bottleneck_tails_in_the_network(hawq, N, hw, int32_sc):
+    """ResNet50 with the 3x3 -> 1x1 + shortcut tails of its identity blocks run as one launch each (the plan's rule keeps
+    them as two launches; the hook forces the fused form): fewer launches that do work, same logits as the oracle and as
+    the unfused plan."""
+    import torch
+    net = wl.make_resnet(50, seed=61, image_hw=hw, int32_shortcut=int32_sc)
+    x = wl.make_image_batch(62, N, image_hw=hw)
+    want = onet.forward(net, x)
+    outs, working = [], []
+    try:
+        for mode in (0, 1):
+            hawq.hawq_tune_set_fusion(mode)
+            hn = hawq.HawqNet(50, net["layers"], net["pool_b"], net["pool_c"], image_hw=hw)
+            ws = torch.full((hn.workspace_bytes(N),), 0x77, dtype=torch.uint8, device="cuda")
+            logits = torch.zeros((N, 1000), dtype=torch.int32, device="cuda")
+            hn.hawq_forward_resnet(torch.from_numpy(x).cuda(), N, logits, ws)
+            torch.cuda.synchronize()
+            outs.append(logits.cpu().numpy())
+            working.append(sum(hn.step_cost(N, s)[0] > 0 for s in range(hn.num_steps())))
+            hn.close()
+    finally:
+        hawq.hawq_tune_set_fusion(0)
+    assert np.array_equal(outs[0], want) and np.array_equal(outs[1], want)
+    # stage 2 (image side / 8 <= 28) and stage 3 (<= 14) identity blocks: 3 + 5 launches fewer at these image sizes
+    assert working[0] - working[1] == 8, working
