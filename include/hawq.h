@@ -172,10 +172,11 @@ hawq_status hawq_bottleneck_tail_int(const hawq_conv_desc *desc2, const void *x,
  *   y[m,n] = epilogue( sum_k x[m,k] * w[n,k] + bias[n] ),   x [M,Kdim], w [N,Kdim], y [M,N]
  * with the epilogue of hawq_conv2d_int (no residual).  b == c == NULL with y_dt == HAWQ_S32
  * returns the raw INT32 logits of the last layer.
- * HAWQ_U8 activations are taken over the type's whole range 0..255 (exact for every byte value).  The INT8 matrix
- * instruction reads signed bytes, so a caller whose unsigned activations are known to stay within 0..127 (the post-ReLU
- * range of the 8-bit layers) may pass the same buffer as HAWQ_S8: same bytes, same result, and the request can take the
- * fastest matrix-core form.
+ * HAWQ_U8 activations are taken over the type's whole range 0..255 (exact for every byte value).  With at most 512 rows and
+ * Kdim a multiple of 512 they run on the matrix cores all the same (the kernel multiplies x - 128 and corrects with
+ * 128 * sum(w), exact); other shapes with unsigned bytes take a slower exact kernel, and a caller whose unsigned
+ * activations are known to stay within 0..127 (the post-ReLU range of the 8-bit layers) may pass the same buffer as
+ * HAWQ_S8: same bytes, same result, every matrix-core form applies.
  */
 hawq_status hawq_gemm_int(int32_t M, int32_t N, int32_t Kdim, int32_t x_dt, int32_t w_dt, int32_t y_dt, const void *x,
                           const void *w, const int32_t *bias, const int32_t *b, const uint8_t *c, int32_t relu,

@@ -112,6 +112,7 @@ bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *
     if ((uintptr_t)a1.x & 15) return false;
     r = RpArgs{};
     r.x = a1.x; r.N = a1.N; r.H = a1.H; r.W = a1.W; r.C = a1.C; r.M = a1.M;
+    r.corun = a1.corun;
     r.w1f = (const uint8_t *)a1.w_f; r.bias1 = a1.bias; r.b1 = a1.b; r.c1 = a1.c; r.K1 = a1.K; r.lo1 = a1.lo; r.hi1 = a1.hi;
     if (a2 == nullptr) {
         if (a1.res != nullptr && a1.res_dt != HAWQ_U8 && a1.res_dt != HAWQ_S8) return false;
@@ -133,6 +134,7 @@ bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *
 
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
+    if (a.x_dt == HAWQ_U8 && x_hi > 127 && gemm_splitk_eligible(a)) return launch_gemm_splitk(a, x_hi, s);
     if (conv_pw_eligible(a, x_hi)) return launch_conv_pw(a, s);
     if (tile_override() == 0 && conv_pws_eligible(a, x_hi)) return launch_conv_pws(a, s);
     if (tile_override() == 0 && conv3x3_c64_eligible(a, x_hi)) return launch_conv3x3_c64(a, s);

@@ -74,6 +74,7 @@ struct RpArgs {
     const int32_t *bias2, *b2;
     const uint8_t *c2;
     int32_t K2, lo2, hi2;
+    int32_t corun;           // kernels of another stream share the chip (see ConvArgs::corun)
 #ifdef HAWQ_RP_TIMING
     long long *timing;       // measurement build only: [workgroup][wave][6] cycle stamps
 #endif
@@ -175,6 +176,9 @@ hawq_status launch_conv_pw(const ConvArgs &a, hipStream_t s);
 // same, for C = 256 with K >= 256 a multiple of 128: the activation stage is shared by a workgroup's four waves
 bool conv_pws_eligible(const ConvArgs &a, int x_hi);
 hawq_status launch_conv_pws(const ConvArgs &a, hipStream_t s);
+// few rows, long reduction (the fully connected layer): eight waves split the reduction, partial tiles meet in LDS
+bool gemm_splitk_eligible(const ConvArgs &a);
+hawq_status launch_gemm_splitk(const ConvArgs &a, int x_hi, hipStream_t s);
 // conv1 of the networks: 7x7/2 pad 3, C=3 -> 64, weights re-tiled to [64][8][8][4] and the
 // bias corrected for the -128 input offset by the host (see net.hip)
 hawq_status launch_conv_stem(const ConvArgs &a, hipStream_t s);

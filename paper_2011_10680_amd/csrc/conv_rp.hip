@@ -158,10 +158,13 @@ conv_rp_kernel(const RpArgs a) {
     const int rho = lane & 31, khalf = lane >> 5;
 #ifdef HAWQ_RP_TIMING
     long long tstamp[6] = {0, 0, 0, 0, 0, 0};
+    long long pstamp[4] = {0, 0, 0, 0};
 #define RP_STAMP(i) tstamp[i] = (long long)__builtin_readcyclecounter()
-#define RP_STAMP_OUT() do { if (a.timing && lane == 0) { for (int q_ = 0; q_ < 6; ++q_) a.timing[((long long)blockIdx.x * 8 + wave) * 6 + q_] = tstamp[q_]; } } while (0)
+#define RP_PSTAMP(i) pstamp[i] = (long long)__builtin_readcyclecounter()
+#define RP_STAMP_OUT() do { if (a.timing && lane == 0) { for (int q_ = 0; q_ < 6; ++q_) a.timing[((long long)blockIdx.x * 8 + wave) * 10 + q_] = tstamp[q_]; for (int q_ = 0; q_ < 4; ++q_) a.timing[((long long)blockIdx.x * 8 + wave) * 10 + 6 + q_] = pstamp[q_]; } } while (0)
 #else
 #define RP_STAMP(i) do { } while (0)
+#define RP_PSTAMP(i) do { } while (0)
 #define RP_STAMP_OUT() do { } while (0)
 #endif
     RP_STAMP(0);
@@ -222,6 +225,7 @@ conv_rp_kernel(const RpArgs a) {
         }
     }
 
+    RP_PSTAMP(0);
     // ---- the lane's pixels: LDS row offsets, and which of the nine taps lie inside the image ----
     // A tap outside the image reads zeros: its lane is redirected to one of sixteen rows of zeros, the one congruent to the
     // row it would have read (mod 16) -- the sixteen lanes of an LDS access then still fall into sixteen different banks.
@@ -251,11 +255,13 @@ conv_rp_kernel(const RpArgs a) {
     }
 
     // ---- LDS: patch, rows of zeros, parameters ----
+    RP_PSTAMP(1);
 #pragma unroll
     for (int j = 0; j < NIT; ++j) {
         const int i = tid + j * T;
         if (i < nchunk) *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 16) = pv[j];
     }
+    RP_PSTAMP(2);
     for (int i = tid; i < 16 * CPR; i += T) *(v4i *)(patch + (ROWS + i / CPR) * PITCH + (i % CPR) * 16) = (v4i){0, 0, 0, 0};
     int wide = 0;
     auto stage = [&](int32_t bias, int32_t b, int32_t c, RpChan &o) {
@@ -287,6 +293,7 @@ conv_rp_kernel(const RpArgs a) {
             }
         }
     }
+    RP_PSTAMP(3);
     wide = __syncthreads_or(wide);   // patch and parameters are in LDS
     RP_STAMP(1);
 
@@ -459,7 +466,7 @@ conv_rp_kernel(const RpArgs a) {
 
 // Which instantiation serves the request; 0 = none.  C = 128: tiles of 448 pixels (4 waves along channels x 2 along
 // pixels x 7 MFMA column tiles), image widths up to 28; C = 256: tiles of 128 pixels (8 x 1 x 4), widths up to 14 (fused)
-// or 28 (plain).  (A 28 x 28 layer at batch 128 has 100352 pixels: 224 tiles of 448 keep every tile in one round on 256
+// or 28 (plain); C = 512 (plain only): tiles of 64 pixels (8 x 1 x 2), widths up to 14.  (A 28 x 28 layer at batch 128 has 100352 pixels: 224 tiles of 448 keep every tile in one round on 256
 // compute units, where 392 tiles of 256 need two.)
 static int rp_variant(const RpArgs &a, bool fused) {
     if (a.C % 64 != 0 || a.M <= 0 || a.H <= 0 || a.W <= 0) return 0;
@@ -472,6 +479,7 @@ static int rp_variant(const RpArgs &a, bool fused) {
     }
     if (cch == 2 && a.W <= 28 && a.K1 % 128 == 0) return 3;
     if (cch == 4 && a.W <= 28 && a.K1 % 256 == 0) return 4;
+    if (cch == 8 && a.W <= 14 && a.K1 % 256 == 0) return 5;
     return 0;
 }
 
@@ -492,7 +500,15 @@ hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s) {
         if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
         else conv_rp_kernel<2, 4, 2, 4, 28, false><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
         break;
-    default: conv_rp_kernel<4, 8, 1, 4, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a); break;
+    case 4:
+        // few tiles and the chip to itself (14 x 14 at batch 64: 98 tiles): half the channels per workgroup, twice the
+        // workgroups (measured 15.7 -> see the launcher's notes; with another stream's kernels on the chip the larger
+        // workgroups are the better neighbours)
+        if (!a.corun && tiles(128) * (uint32_t)(a.K1 / 256) < 160) conv_rp_kernel<4, 4, 2, 2, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        else conv_rp_kernel<4, 8, 1, 4, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        break;
+    // 512 channels (7 x 7 images: few pixels, long reduction): 64-pixel tiles, so that pixel tiles x channel halves fill the chip
+    default: conv_rp_kernel<8, 8, 1, 2, 14, false><<<tiles(64) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a); break;
     }
     return check_launch();
 }

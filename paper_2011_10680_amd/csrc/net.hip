@@ -316,7 +316,10 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         auto packed_pays = [&](const LayerShape &l) {
             const bool pw = l.R == 1 && l.S == 1 && (l.C == 64 || l.C == 128 || (l.C == 256 && l.K <= 128));
             const bool c64 = l.R == 3 && l.S == 3 && l.C == 64 && l.K == 64 && l.stride == 1 && l.pad == 1;
-            const bool c128 = l.R == 3 && l.S == 3 && l.C % 128 == 0;   // packed LDS-DMA form of the implicit-GEMM kernel
+            // packed LDS-DMA form of the implicit-GEMM kernel -- unless the resident-pixel kernel takes the layer in 8-bit
+            // form (128 or 256 channels, stride 1, image width within its patch), which is faster than either packed form
+            const bool rp = l.R == 3 && l.S == 3 && l.stride == 1 && l.pad == 1 && (l.C == 128 || l.C == 256) && l.K % l.C == 0 && l.W <= 28;
+            const bool c128 = l.R == 3 && l.S == 3 && l.C % 128 == 0 && !rp;
             return pw || c64 || c128;
         };
         for (int i = 0; i < nl; ++i)
@@ -342,7 +345,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto blocked = [&](int i) { return !L[i].is_stem && L[i].C % (is8(i) ? 64 : 128) == 0; };
     // fragment-ordered copy: the 3x3 / 1 / 1 layers the resident-pixel kernel takes (128 or 256 input channels, 8-bit form)
     // and the 1x1 layer that follows such a layer in a bottleneck (it may run fused behind it)
-    auto rp3x3 = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && is8(i) && (L[i].C == 128 || L[i].C == 256) && L[i].K % L[i].C == 0; };
+    auto rp3x3 = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && is8(i) && (L[i].C == 128 || L[i].C == 256 || (L[i].C == 512 && L[i].W <= 14)) && L[i].K % L[i].C == 0; };
     auto fragmented = [&](int i) {
         if (L[i].is_stem || L[i].is_fc) return false;
         if (rp3x3(i)) return true;
@@ -798,6 +801,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                 rc = make_conv_args(&d3, tptr(p.in), st.w, st.bias, st.b, st.c, tptr(st.res), st.res_b, st.res_c, tptr(st.out), true, a2, h_hi);
             if (rc != HAWQ_OK) return rc;
             a1.w_f = p.w_f;
+            a1.corun = n_parts > 1;
             RpArgs r;
             if (!make_rp_args(a1, x_hi, &a2, st.w_f, r)) return HAWQ_ERR_UNSUPPORTED;   // (the plan checked shapes and types)
             rc = launch_conv_rp(r, true, stream);

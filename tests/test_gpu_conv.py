@@ -377,7 +377,8 @@ def test_gemm_fc_shape(hawq):
     assert np.array_equal(want.astype(np.int64), x.astype(np.int64) @ w.astype(np.int64).T + bias)
 
 
-@pytest.mark.parametrize("M,N,K,requant", [(37, 1000, 2048, False), (130, 96, 512, True), (5, 64, 64, True)])
+@pytest.mark.parametrize("M,N,K,requant", [(37, 1000, 2048, False), (130, 96, 512, True), (5, 64, 64, True), (300, 72, 1024, True),
+                                           (512, 40, 1536, False), (513, 64, 512, False)])
 def test_gemm_unsigned_bytes_over_the_whole_range(hawq, M, N, K, requant):
     """HAWQ_U8 rows holding every byte value 0..255 (the matrix instruction reads signed bytes: values above 127 must not
     be read as negative), raw INT32 and requantised outputs; and the same 0..127 data passed as HAWQ_S8 and as HAWQ_U8."""
