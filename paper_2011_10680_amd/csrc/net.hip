@@ -316,10 +316,10 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         auto packed_pays = [&](const LayerShape &l) {
             const bool pw = l.R == 1 && l.S == 1 && (l.C == 64 || l.C == 128 || (l.C == 256 && l.K <= 128));
             const bool c64 = l.R == 3 && l.S == 3 && l.C == 64 && l.K == 64 && l.stride == 1 && l.pad == 1;
-            // packed LDS-DMA form of the implicit-GEMM kernel -- unless the resident-pixel kernel takes the layer in 8-bit
-            // form (128 or 256 channels, stride 1, image width within its patch), which is faster than either packed form
-            const bool rp = l.R == 3 && l.S == 3 && l.stride == 1 && l.pad == 1 && (l.C == 128 || l.C == 256) && l.K % l.C == 0 && l.W <= 28;
-            const bool c128 = l.R == 3 && l.S == 3 && l.C % 128 == 0 && !rp;
+            // packed LDS-DMA form of the implicit-GEMM kernel.  (Running these layers in 8-bit form on the resident-pixel
+            // kernel instead was measured on the mixed network at batch 256: the 3x3 layer gains nothing there -- 45.7 against
+            // 46.2 us at 28x28 -- and its producer writes twice the bytes, 36 against 30 us.)
+            const bool c128 = l.R == 3 && l.S == 3 && l.C % 128 == 0;
             return pw || c64 || c128;
         };
         for (int i = 0; i < nl; ++i)
