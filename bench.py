@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--workload", default="resnet50_int8_b128", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-images", type=int, default=256, help="images in the CPU-oracle baseline sample (0: skip)")
     ap.add_argument("--report", default=None, help="optional file for the per-layer table (JSON)")
+    ap.add_argument("--bits-json", default=None,
+                    help="JSON file {group name: 4 | 8} replacing the workload's bit assignment (e.g. a selection written by "
+                         "`python -m paper_2011_10680_amd.bitselect_report`)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel 5 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -201,7 +204,10 @@ def main():
         bits = wl.draw_bits(arch, 4000 + arch)
     else:
         bits = None
-    net = wl.make_resnet(arch, seed=wk["seed"], bits=bits, int32_shortcut=wk.get("int32_shortcut", False))
+    if args.bits_json:
+        with open(args.bits_json) as f:
+            bits = {k: int(v) for k, v in json.load(f).items()}
+    net = wl.make_resnet(arch, seed=wk["seed"], bits=bits, int32_shortcut=wk.get("int32_shortcut", False) and not args.bits_json)
     x = torch.from_numpy(wl.make_image_batch(wk["seed"] + 1, N)).cuda()
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
     if args.single_stream:
@@ -275,10 +281,10 @@ def main():
         "metric": "resnet%d_int_only_images_per_sec" % arch, "value": N / (ms_per_step * 1e-3), "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8" if not wk["mixed"] else "int4/int8", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": N, "image": "3x224x224 uint8",
+        "dtype": "int8" if not any(l["bits"] == 4 for l in net["layers"]) else "int4/int8", "data": "synthetic",
+        "config": {"workload": args.workload + (" with --bits-json" if args.bits_json else ""), "batch": N, "image": "3x224x224 uint8",
                    "layers_int4": sum(l["bits"] == 4 for l in net["layers"]),
-                   "transition_blocks": "int32 both branches" if wk.get("int32_shortcut") else "stored int8 shortcut",
+                   "transition_blocks": "int32 both branches" if (wk.get("int32_shortcut") and not args.bits_json) else "stored int8 shortcut",
                    "batch_parts": "%d + %d images on two streams" % (first, N - first) if first else "one"},
         "tops": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
         "frac_int8_mfma_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / PEAK_INT8_TOPS,
