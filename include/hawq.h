@@ -78,8 +78,9 @@ typedef struct {
                                       hawq_conv_block_weights; the implicit-GEMM kernel then reads it instead of w
                                       (whole cache lines per fetch).  w is still required: other kernels read it. */
     const void *w_fragments;       /* optional (NULL: none): device copy of the same weights made by
-                                      hawq_conv_fragment_weights; a 3x3 / stride 1 / pad 1 layer with 128 or 256 input
-                                      channels then runs on the kernel that keeps its pixels in LDS and streams these. */
+                                      hawq_conv_fragment_weights; a 3x3 / stride 1 / pad 1 layer with 128, 256 or 512
+                                      input channels (8-bit or packed 4-bit operands) then runs on the kernel that keeps
+                                      its pixels in LDS and streams these. */
 } hawq_conv_desc;
 
 /*
@@ -140,8 +141,10 @@ hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, v
  * Copy of a layer's weights in matrix-instruction fragment order: [ceil(K/32)][R*S*C/64][2][64 lanes][16 bytes], i.e. for
  * every group of 32 output channels and every 64-byte reduction step the two 1 KB operand fragments exactly as the 64
  * lanes of a wave hold them (channels past K zero).  A wave then loads its weights with fully coalesced reads straight
- * into registers.  Same integers, another order: results do not change.  8-bit weights with C % 64 == 0 only
- * (hawq_conv_fragment_weights_bytes returns 0 otherwise, hawq_conv_fragment_weights HAWQ_ERR_UNSUPPORTED).
+ * into registers.  Same integers, another order: results do not change.  C % 64 == 0; packed 4-bit weights are expanded
+ * to signed bytes on the way (there is no 4-bit matrix instruction), even elements of every 32 before the odd ones -- the
+ * order in which the kernel splits the packed activations -- so the copy of a 4-bit layer has the size of an 8-bit one's.
+ * Otherwise hawq_conv_fragment_weights_bytes returns 0 and hawq_conv_fragment_weights HAWQ_ERR_UNSUPPORTED.
  * Device to device, asynchronous on `stream`, 16-byte aligned pointers; call once per layer, outside the timed path.
  */
 size_t hawq_conv_fragment_weights_bytes(const hawq_conv_desc *desc);

@@ -106,14 +106,22 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
 // that consumes its output in the same launch (weights w2f; a2's x / y-of-a1 pointers are not used).
 bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *w2f, RpArgs &r) {
     if (a1.R != 3 || a1.S != 3 || a1.stride_h != 1 || a1.stride_w != 1 || a1.pad_h != 1 || a1.pad_w != 1) return false;
-    if (a1.w_dt != HAWQ_S8 || a1.w_f == nullptr || a1.b == nullptr || a1.xs != nullptr) return false;
-    if (a1.x_dt == HAWQ_U8 ? x_hi > 127 : a1.x_dt != HAWQ_S8) return false;
-    if (a1.y_dt != HAWQ_U8 && a1.y_dt != HAWQ_S8) return false;
+    if (a1.w_f == nullptr || a1.b == nullptr || a1.xs != nullptr) return false;
     if ((uintptr_t)a1.x & 15) return false;
     r = RpArgs{};
-    r.x = a1.x; r.N = a1.N; r.H = a1.H; r.W = a1.W; r.C = a1.C; r.M = a1.M;
     r.corun = a1.corun;
+    r.x = a1.x; r.N = a1.N; r.H = a1.H; r.W = a1.W; r.C = a1.C; r.M = a1.M;
     r.w1f = (const uint8_t *)a1.w_f; r.bias1 = a1.bias; r.b1 = a1.b; r.c1 = a1.c; r.K1 = a1.K; r.lo1 = a1.lo; r.hi1 = a1.hi;
+    if (a1.x_dt == HAWQ_U4) {   // packed 4-bit operands: plain form, no shortcut, 8-bit or packed unsigned 4-bit output
+        if (a1.w_dt != HAWQ_S4 || a2 != nullptr || a1.res != nullptr) return false;
+        if (a1.y_dt != HAWQ_U8 && a1.y_dt != HAWQ_S8 && a1.y_dt != HAWQ_U4) return false;
+        if ((uintptr_t)a1.y & 15) return false;
+        r.pk = 1; r.y4 = a1.y_dt == HAWQ_U4; r.y = a1.y; r.res_dt = HAWQ_U8;
+        return conv_rp_shape_ok(r, false);
+    }
+    if (a1.w_dt != HAWQ_S8) return false;
+    if (a1.x_dt == HAWQ_U8 ? x_hi > 127 : a1.x_dt != HAWQ_S8) return false;
+    if (a1.y_dt != HAWQ_U8 && a1.y_dt != HAWQ_S8) return false;
     if (a2 == nullptr) {
         if (a1.res != nullptr && a1.res_dt != HAWQ_U8 && a1.res_dt != HAWQ_S8) return false;
         if (((uintptr_t)a1.y | (uintptr_t)a1.res) & 15) return false;
@@ -205,8 +213,8 @@ hawq_status hawq_conv_block_weights(const hawq_conv_desc *desc, const void *w, v
 
 size_t hawq_conv_fragment_weights_bytes(const hawq_conv_desc *desc) {
     if (!desc || desc->K <= 0 || desc->R <= 0 || desc->S <= 0 || desc->C <= 0) return 0;
-    if (desc->w_dtype != HAWQ_S8 || desc->C % 64 != 0) return 0;
-    return (size_t)((desc->K + 31) / 32) * 32 * (size_t)desc->R * desc->S * desc->C;
+    if ((desc->w_dtype != HAWQ_S4 && desc->w_dtype != HAWQ_S8) || desc->C % 64 != 0) return 0;
+    return (size_t)((desc->K + 31) / 32) * 32 * (size_t)desc->R * desc->S * desc->C;   // (4-bit weights are expanded to bytes)
 }
 
 hawq_status hawq_conv_fragment_weights(const hawq_conv_desc *desc, const void *w, void *w_fragments, void *stream) {
@@ -214,7 +222,8 @@ hawq_status hawq_conv_fragment_weights(const hawq_conv_desc *desc, const void *w
     const size_t bytes = hawq_conv_fragment_weights_bytes(desc);
     if (bytes == 0 || bytes >= (size_t)kMaxBytes) return HAWQ_ERR_UNSUPPORTED;
     if (((uintptr_t)w | (uintptr_t)w_fragments) & 15) return HAWQ_ERR_UNSUPPORTED;
-    return hawq::launch_fragment_weights(w, w_fragments, desc->K, (int64_t)desc->R * desc->S * desc->C, (hipStream_t)stream);
+    return hawq::launch_fragment_weights(w, w_fragments, desc->K, hawq::tensor_bytes((int64_t)desc->R * desc->S * desc->C, desc->w_dtype),
+                                         desc->w_dtype == HAWQ_S4, (hipStream_t)stream);
 }
 
 hawq_status hawq_bottleneck_tail_int(const hawq_conv_desc *desc2, const void *x, const void *w2_fragments, const int32_t *bias2,

@@ -55,7 +55,7 @@ struct ConvArgs {
 
 // Arguments of the resident-pixel 3x3 kernel (conv_rp.hip), with or without the fused 1x1 that ends a bottleneck block.
 struct RpArgs {
-    const uint8_t *x;        // input [N,H,W,C], 8-bit (signed operand range)
+    const uint8_t *x;        // input [N,H,W,C], 8-bit (signed operand range), or packed 4-bit when pk
     int32_t N, H, W, C;
     int32_t M;               // N*H*W pixels (the 3x3 convolution is stride 1, pad 1: as many output pixels)
     // stage 1: 3x3, C -> K1
@@ -75,6 +75,8 @@ struct RpArgs {
     const uint8_t *c2;
     int32_t K2, lo2, hi2;
     int32_t corun;           // kernels of another stream share the chip (see ConvArgs::corun)
+    int32_t pk;              // operands are packed 4-bit (unsigned activations, signed weights); plain form only, no shortcut
+    int32_t y4;              // pk: the output is packed unsigned 4-bit (else one byte per channel)
 #ifdef HAWQ_RP_TIMING
     long long *timing;       // measurement build only: [workgroup][wave][6] cycle stamps
 #endif
@@ -202,8 +204,9 @@ bool conv_rp_shape_ok(const RpArgs &a, bool fused);
 // RpArgs from a validated 3x3 layer (and, fused, the 1x1 layer that follows it); false if types, alignment or shape do not fit
 bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *w2f, RpArgs &r);
 hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s);
-// [K][row bytes] weights -> MFMA fragment order for that kernel; row a multiple of 64; out: ceil(K/32) * row * 32 bytes
-hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, hipStream_t s);
+// [K][row bytes] weights -> MFMA fragment order for that kernel (four: packed 4-bit rows, expanded to bytes on the way);
+// out: ceil(K/32) * 32 * (bytes of an expanded row)
+hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, bool four, hipStream_t s);
 
 // [K][row bytes] weights -> the implicit-GEMM kernel's blocked order (ConvArgs::w_t); row a multiple of 64
 hawq_status launch_block_weights(const void *w, void *w_blocked, int K, int64_t row, hipStream_t s);

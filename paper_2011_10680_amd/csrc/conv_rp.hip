@@ -131,10 +131,18 @@ __device__ __forceinline__ void rp_epilogue(const v16i &acc0, const v16i &acc1, 
 // second phase (1x1 on the requantised tile, K1 == 64 CCH == 32 WC channels wide, + shortcut).  Without it a workgroup
 // computes 32 WC channels of the 3x3 convolution's output (grid: tiles x K1 / (32 WC)) and its epilogue stores to memory
 // (optionally adding a shortcut).
-template <int CCH, int WC, int WP, int TP, int WMAX, bool FUSED>
+// PK: packed 4-bit operands (Section 3.5's storage: two elements per byte).  There is no 4-bit matrix instruction, so the
+// nibbles become bytes before the MFMA; here that happens at the edges only.  The patch fill splits every 16 packed bytes
+// (32 channels) into the 16 low-nibble bytes (even channels) and the 16 high-nibble bytes (odd channels) and writes them
+// as two adjacent 16-byte LDS chunks; the weight fragments were expanded once, on the way into the fragment copy, with
+// the same even / odd order (launch_fragment_weights), so both operands see the same permutation of the reduction
+// index.  The K loop is the 8-bit loop, instruction for instruction: a 4-bit layer costs what its 8-bit twin costs, minus
+// half the activation and output bytes.
+template <int CCH, int WC, int WP, int TP, int WMAX, bool FUSED, bool PK = false>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 conv_rp_kernel(const RpArgs a) {
     static_assert(WC * WP == 8, "eight waves");
+    static_assert(!(FUSED && PK), "the fused form takes 8-bit operands");
     static_assert(!FUSED || 32 * WC == 64 * CCH, "fused: the workgroup owns every channel of the intermediate tile");
     constexpr int T = 512;
     constexpr int WPX = 32 * TP;              // pixels per wave
@@ -179,13 +187,13 @@ conv_rp_kernel(const RpArgs a) {
 
     // ---- prologue: every global load of it is issued before the first one is waited for ----
     // patch: flat input pixels m0 - W - 1 ... m0 + BP + W of every channel, one contiguous range of memory
-    constexpr int CPR = C / 16;                                  // 16-byte chunks per pixel
+    constexpr int CPR = PK ? C / 32 : C / 16;                    // 16-byte chunks per pixel in memory
     constexpr int NIT = (ROWS * CPR + T - 1) / T;
     const int nchunk = (BP + 2 * W + 2) * CPR;
     v4i pv[NIT];
     {
-        const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.M * C), 0x00020000);
-        const int64_t src0 = ((int64_t)m0 - W - 1) * C;
+        const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((int64_t)a.M * CPR * 16), 0x00020000);
+        const int64_t src0 = ((int64_t)m0 - W - 1) * (CPR * 16);
 #pragma unroll
         for (int j = 0; j < NIT; ++j) {
             const int i = tid + j * T;
@@ -200,9 +208,10 @@ conv_rp_kernel(const RpArgs a) {
     __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void *)a.w1f, 0, (int)((int64_t)G1 * S1 * 2048), 0x00020000);
     const int lane16 = lane * 16;
     int woff = __builtin_amdgcn_readfirstlane((kbase1 / 32 + wc) * S1 * 2048);   // byte offset of the next K-step to fetch
-    v4i af[3][2];
+    constexpr int D = 3;            // K-steps the weight fragments are requested ahead
+    v4i af[D][2];
 #pragma unroll
-    for (int d = 0; d < 3; ++d) {
+    for (int d = 0; d < D; ++d) {
         af[d][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
         af[d][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
         woff += 2048;
@@ -233,6 +242,7 @@ conv_rp_kernel(const RpArgs a) {
     uint32_t vmask[TP];
     uint32_t yoff[TP];   // byte offset of the pixel's first channel in the tensor this launch stores (out of range: no such pixel)
     const int Ky = FUSED ? a.K2 : a.K1;
+    const int ysh = (PK && a.y4) ? 1 : 0;   // a packed 4-bit output holds two channels per byte
     {
         const int H = a.H, HW = a.H * a.W;
 #pragma unroll
@@ -240,7 +250,7 @@ conv_rp_kernel(const RpArgs a) {
             const int p = wp * WPX + tp * 32 + rho;
             const int64_t m = (int64_t)m0 + p;
             const bool pvalid = m < a.M;
-            yoff[tp] = pvalid ? (uint32_t)(m * Ky) : 0x80000000u;
+            yoff[tp] = pvalid ? (uint32_t)((m * Ky) >> ysh) : 0x80000000u;
             const int rem = pvalid ? (int)(m % HW) : 0;
             const int yy = rem / W, xx = rem - yy * W;
             uint32_t mask = 0;
@@ -259,10 +269,24 @@ conv_rp_kernel(const RpArgs a) {
 #pragma unroll
     for (int j = 0; j < NIT; ++j) {
         const int i = tid + j * T;
-        if (i < nchunk) *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 16) = pv[j];
+        if (i < nchunk) {
+            if constexpr (PK) {   // 16 packed bytes -> low nibbles (even channels), high nibbles (odd channels): two chunks
+                v4i lo, hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t u = (uint32_t)pv[j][e];
+                    lo[e] = (int)(u & 0x0F0F0F0Fu);
+                    hi[e] = (int)((u >> 4) & 0x0F0F0F0Fu);
+                }
+                *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 32) = lo;
+                *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 32 + 16) = hi;
+            } else {
+                *(v4i *)(patch + (i / CPR) * PITCH + (i % CPR) * 16) = pv[j];
+            }
+        }
     }
     RP_PSTAMP(2);
-    for (int i = tid; i < 16 * CPR; i += T) *(v4i *)(patch + (ROWS + i / CPR) * PITCH + (i % CPR) * 16) = (v4i){0, 0, 0, 0};
+    for (int i = tid; i < 16 * (C / 16); i += T) *(v4i *)(patch + (ROWS + i / (C / 16)) * PITCH + (i % (C / 16)) * 16) = (v4i){0, 0, 0, 0};
     int wide = 0;
     auto stage = [&](int32_t bias, int32_t b, int32_t c, RpChan &o) {
         o.b = b; o.c = c; o.bias = bias; o.bs = 0; o.Rs = 0;
@@ -319,7 +343,7 @@ conv_rp_kernel(const RpArgs a) {
         for (int tp = 0; tp < TP; ++tp) acc[tp] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aw, bf[buf][tp], acc[tp], 0, 0, 0);
     };
 
-    const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)((int64_t)a.M * Ky), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc((void *)a.y, 0, (int)(((int64_t)a.M * Ky) >> ysh), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_r = __builtin_amdgcn_make_buffer_rsrc((void *)(a.res ? a.res : a.x), 0, a.res ? (int)((int64_t)a.M * Ky) : 0, 0x00020000);
     const bool res_signed = a.res_dt == HAWQ_S8;
     // The lane's shortcut bytes, fetched a whole pass of the second convolution ahead of their use: two buffers where the
@@ -354,7 +378,7 @@ conv_rp_kernel(const RpArgs a) {
 
     // ================= phase 1: the 3x3 convolution, 9 CCH K-steps, fully unrolled =================
     // Half-step h (32 reduction elements) = K-step h / 2, half h % 2.  While half-step h is multiplied, the pixel fragments
-    // of half-step h + 1 are read into the other buffer; the weight fragments of K-step t + 3 are requested as soon as
+    // of half-step h + 1 are read into the other buffer; the weight fragments of K-step t + D are requested as soon as
     // K-step t has issued.
     const int chl = wc * 32 + khalf * 16;   // the lane's first channel within the workgroup's range
     if (has_res1) load_res(R0{}, kbase1 + chl);
@@ -370,11 +394,11 @@ conv_rp_kernel(const RpArgs a) {
 #pragma unroll
             for (int tp = 0; tp < TP; ++tp) bf[hn % 2][tp] = *(const v4i *)(patch + sel[tp] + (tn % CCH) * 64 + kn * 32);
         }
-        mfma_row(std::integral_constant<int, h % 2>{}, af[t % 3][kk]);
+        mfma_row(std::integral_constant<int, h % 2>{}, af[t % D][kk]);
         if constexpr (kk == 1) {
-            if constexpr (t + 3 < S1) {
-                af[t % 3][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
-                af[t % 3][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
+            if constexpr (t + D < S1) {
+                af[t % D][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
+                af[t % D][1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff + 1024, 0);
                 woff += 2048;
             }
         }
@@ -385,7 +409,14 @@ conv_rp_kernel(const RpArgs a) {
     auto put_y = [&](int ch) {
         return [&, ch](auto tpc, const uint32_t (&o)[4]) {
             constexpr int tp = decltype(tpc)::value;
-            __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]}, rsrc_y, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
+            if (PK && a.y4) {
+                // sixteen values 0..15, one per byte -> sixteen nibbles, even channel in the low nibble
+                auto nib = [](uint32_t d) { return (d & 0xfu) | ((d >> 4) & 0xf0u) | ((d >> 8) & 0xf00u) | ((d >> 12) & 0xf000u); };
+                const v2i w = {(int)(nib(o[0]) | (nib(o[1]) << 16)), (int)(nib(o[2]) | (nib(o[3]) << 16))};
+                __builtin_amdgcn_raw_buffer_store_b64(w, rsrc_y, (int)(yoff[tp] + (uint32_t)(ch >> 1)), 0, 0);
+            } else {
+                __builtin_amdgcn_raw_buffer_store_b128((v4i){(int)o[0], (int)o[1], (int)o[2], (int)o[3]}, rsrc_y, (int)(yoff[tp] + (uint32_t)ch), 0, 0);
+            }
         };
     };
     if constexpr (!FUSED) {
@@ -471,6 +502,7 @@ conv_rp_kernel(const RpArgs a) {
 static int rp_variant(const RpArgs &a, bool fused) {
     if (a.C % 64 != 0 || a.M <= 0 || a.H <= 0 || a.W <= 0) return 0;
     const int cch = a.C / 64;
+    if (a.pk && (fused || a.res != nullptr)) return 0;
     if (fused) {
         if (a.K1 != a.C || a.K2 > 4 * a.C) return 0;
         if (cch == 2 && a.W <= 28 && a.K2 % 128 == 0) return 1;
@@ -489,57 +521,90 @@ hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s) {
     const int v = rp_variant(a, fused);
     if (v == 0) return HAWQ_ERR_UNSUPPORTED;
     auto tiles = [&](int bp) { return (uint32_t)(((int64_t)a.M + bp - 1) / bp); };
-    // small problems: narrower tiles put more compute units to work
+    // few tiles and the chip to itself (14 x 14 at batch 64: 98 tiles of 128 pixels): half the channels per workgroup,
+    // twice the workgroups (14x14 256 -> 256 at batch 64: 15.7 -> 11.1 us); with another stream's kernels on the chip the
+    // larger workgroups are the better neighbours
+    const bool few = !a.corun && tiles(128) * (uint32_t)(a.K1 / 256) < 160;
     switch (v) {
-    case 1:
+    case 1:   // small problems: narrower tiles put more compute units to work
         if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, true><<<tiles(448), 512, 0, s>>>(a);
         else conv_rp_kernel<2, 4, 2, 4, 28, true><<<tiles(256), 512, 0, s>>>(a);
         break;
     case 2: conv_rp_kernel<4, 8, 1, 4, 14, true><<<tiles(128), 512, 0, s>>>(a); break;
     case 3:
-        if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
-        else conv_rp_kernel<2, 4, 2, 4, 28, false><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        if (a.pk) {
+            if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false, true><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            else conv_rp_kernel<2, 4, 2, 4, 28, false, true><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        } else {
+            if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            else conv_rp_kernel<2, 4, 2, 4, 28, false><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+        }
         break;
     case 4:
-        // few tiles and the chip to itself (14 x 14 at batch 64: 98 tiles): half the channels per workgroup, twice the
-        // workgroups (measured 15.7 -> see the launcher's notes; with another stream's kernels on the chip the larger
-        // workgroups are the better neighbours)
-        if (!a.corun && tiles(128) * (uint32_t)(a.K1 / 256) < 160) conv_rp_kernel<4, 4, 2, 2, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
-        else conv_rp_kernel<4, 8, 1, 4, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        if (a.pk) {
+            if (few) conv_rp_kernel<4, 4, 2, 2, 28, false, true><<<tiles(128) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            else conv_rp_kernel<4, 8, 1, 4, 28, false, true><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        } else {
+            if (few) conv_rp_kernel<4, 4, 2, 2, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            else conv_rp_kernel<4, 8, 1, 4, 28, false><<<tiles(128) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        }
         break;
     // 512 channels (7 x 7 images: few pixels, long reduction): 64-pixel tiles, so that pixel tiles x channel halves fill the chip
-    default: conv_rp_kernel<8, 8, 1, 2, 14, false><<<tiles(64) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a); break;
+    default:
+        if (a.pk) conv_rp_kernel<8, 8, 1, 2, 14, false, true><<<tiles(64) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        else conv_rp_kernel<8, 8, 1, 2, 14, false><<<tiles(64) * (uint32_t)(a.K1 / 256), 512, 0, s>>>(a);
+        break;
     }
     return check_launch();
 }
 
-// Fragment-ordered copy of a weight matrix [K][row bytes] (row = R*S*C, a multiple of 64):
+// Fragment-ordered copy of a weight matrix [K][row bytes] of signed bytes (row = R*S*C, a multiple of 64):
 //   out[g][t][kk][lane][16]  with  g = channel group of 32 (rows past K are zero), t = K-step of 64 bytes,
 //   lane = khalf * 32 + rho  holding bytes  t*64 + (kk*2 + khalf)*16 .. + 16  of channel
 //   32 g + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3)
 // -- the channel whose accumulator the 32x32x32 MFMA leaves in register (rho >> 3) * 4 + (rho & 3) of lane half
 // (rho >> 2) & 1, so that a lane ends up with 16 consecutive channels.
+// FOUR: the source rows are packed 4-bit (row bytes = R*S*C / 2, a multiple of 32) and are expanded to signed bytes on
+// the way: 16-byte chunk 2q of the expanded row holds the sign-extended low nibbles of packed bytes 16q .. 16q + 15 (the
+// even elements), chunk 2q + 1 their high nibbles (the odd elements) -- the order in which the kernel's patch fill
+// splits the packed activations.  The copy then has the size and the layout of an 8-bit layer's.
+template <bool FOUR>
 __global__ void __launch_bounds__(256) fragment_weights_kernel(const uint8_t *__restrict__ w, uint8_t *__restrict__ out, const int K,
                                                                const int64_t row, const int64_t chunks) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // index of a 16-byte chunk of the output
     if (i >= chunks) return;
     const int lane = (int)(i & 63), kk = (int)((i >> 6) & 1);
     const int64_t gt = i >> 7;
-    const int64_t steps = row / 64;
+    const int64_t steps = (FOUR ? 2 * row : row) / 64;
     const int64_t t = gt % steps, g = gt / steps;
     const int rho = lane & 31, khalf = lane >> 5;
     const int k = (int)g * 32 + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
     v4i v = {0, 0, 0, 0};
-    if (k < K) v = *(const v4i *)(w + (int64_t)k * row + t * 64 + (kk * 2 + khalf) * 16);
+    if (k < K) {
+        const int64_t ci = t * 4 + kk * 2 + khalf;   // 16-byte chunk of the (expanded) row
+        if (FOUR) {
+            const v4i p = *(const v4i *)(w + (int64_t)k * row + (ci >> 1) * 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t u = (uint32_t)p[e];
+                u = (ci & 1) ? (u >> 4) & 0x0F0F0F0Fu : u & 0x0F0F0F0Fu;
+                v[e] = (int)(u | ((u & 0x08080808u) * 0x1Eu));   // sign-extend each nibble to its byte
+            }
+        } else {
+            v = *(const v4i *)(w + (int64_t)k * row + ci * 16);
+        }
+    }
     *(v4i *)(out + i * 16) = v;
 }
 
-hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, hipStream_t s) {
-    const int64_t chunks = (int64_t)((K + 31) / 32) * (row / 64) * 128;
+// row: bytes of a weight row as stored (packed 4-bit when four)
+hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, bool four, hipStream_t s) {
+    const int64_t chunks = (int64_t)((K + 31) / 32) * ((four ? 2 * row : row) / 64) * 128;
     if (chunks == 0) return HAWQ_OK;
     const int64_t blocks = (chunks + 255) / 256;
     if (blocks > 0x7fffffff) return HAWQ_ERR_UNSUPPORTED;
-    fragment_weights_kernel<<<(uint32_t)blocks, 256, 0, s>>>((const uint8_t *)w, (uint8_t *)w_frag, K, row, chunks);
+    if (four) fragment_weights_kernel<true><<<(uint32_t)blocks, 256, 0, s>>>((const uint8_t *)w, (uint8_t *)w_frag, K, row, chunks);
+    else fragment_weights_kernel<false><<<(uint32_t)blocks, 256, 0, s>>>((const uint8_t *)w, (uint8_t *)w_frag, K, row, chunks);
     return check_launch();
 }
 

@@ -346,9 +346,11 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     // fragment-ordered copy: the 3x3 / 1 / 1 layers the resident-pixel kernel takes (128 or 256 input channels, 8-bit form)
     // and the 1x1 layer that follows such a layer in a bottleneck (it may run fused behind it)
     auto rp3x3 = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && is8(i) && (L[i].C == 128 || L[i].C == 256 || (L[i].C == 512 && L[i].W <= 14)) && L[i].K % L[i].C == 0; };
+    // ... and the same layers with packed 4-bit operands (the kernel's packed form)
+    auto rp3x3pk = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && !is8(i) && L[i].W <= 28 && (L[i].C == 128 || L[i].C == 256 || (L[i].C == 512 && L[i].W <= 14)) && L[i].K % L[i].C == 0; };
     auto fragmented = [&](int i) {
         if (L[i].is_stem || L[i].is_fc) return false;
-        if (rp3x3(i)) return true;
+        if (rp3x3(i) || rp3x3pk(i)) return true;
         return i > 0 && L[i].R == 1 && L[i].has_residual && is8(i) && rp3x3(i - 1) && L[i - 1].block == L[i].block && L[i].C == L[i - 1].K;
     };
     std::vector<Off> off(nl);
@@ -358,7 +360,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
         const int64_t nw = (int64_t)L[i].K * L[i].R * L[i].S * L[i].C;
         off[i].w = take((size_t)tensor_bytes(nw, is8(i) ? HAWQ_S8 : HAWQ_S4));
         off[i].wt = blocked(i) ? take((size_t)((L[i].K + 63) / 64) * (size_t)wrow(i) * 64) : 0;
-        off[i].wf = fragmented(i) ? take((size_t)((L[i].K + 31) / 32) * (size_t)wrow(i) * 32) : 0;
+        off[i].wf = fragmented(i) ? take((size_t)((L[i].K + 31) / 32) * 32 * (size_t)L[i].R * L[i].S * L[i].C) : 0;   // (always bytes: 4-bit weights are expanded)
         off[i].bias = take(4 * (size_t)L[i].K);
         off[i].b = take(4 * (size_t)L[i].K);
         off[i].c = take((size_t)L[i].K);
@@ -389,7 +391,8 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                     memcpy(dst + (((int64_t)(k >> 6) * nsteps + st) * 64 + (k & 63)) * 64, src + k * row + st * 64, 64);
         }
         if (fragmented(i)) {   // [K][row] -> [K/32][row/64][2][64 lanes][16]: see launch_fragment_weights for the order
-            const int64_t row = wrow(i), nsteps = row / 64;
+            const bool four = !is8(i);                 // packed rows: expanded to bytes, even elements of every 32 first
+            const int64_t rowp = wrow(i), nsteps = (four ? 2 * rowp : rowp) / 64;
             const uint8_t *src = &host[off[i].w];
             uint8_t *dst = &host[off[i].wf];
             for (int g = 0; g < (L[i].K + 31) / 32; ++g)
@@ -399,7 +402,14 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                             const int rho = lane & 31, khalf = lane >> 5;
                             const int k = g * 32 + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
                             uint8_t *d = dst + ((((int64_t)g * nsteps + st) * 2 + kk) * 64 + lane) * 16;
-                            if (k < L[i].K) memcpy(d, src + k * row + st * 64 + (kk * 2 + khalf) * 16, 16);
+                            if (k >= L[i].K) continue;
+                            const int64_t ci = st * 4 + kk * 2 + khalf;
+                            if (!four) { memcpy(d, src + k * rowp + ci * 16, 16); continue; }
+                            const uint8_t *p = src + k * rowp + (ci >> 1) * 16;
+                            for (int j = 0; j < 16; ++j) {
+                                const int v = (ci & 1) ? (p[j] >> 4) : (p[j] & 0xF);
+                                d[j] = (uint8_t)(int8_t)(v >= 8 ? v - 16 : v);
+                            }
                         }
         }
         memcpy(&host[off[i].bias], lp[i].bias, 4 * (size_t)L[i].K);

@@ -104,6 +104,52 @@ def test_conv3x3_with_fragment_weights(hawq, N, H, W, C, K, res, wide):
     assert 0.05 < np.mean(want > 0) and np.mean(want == 127) < 0.5
 
 
+# N, H, W, C, K, output type, wide parameters: packed 4-bit operands on the same kernel
+PACKED = [(3, 14, 14, 256, 256, "u4", False), (2, 28, 28, 128, 128, "u4", False), (1, 13, 11, 256, 512, "u8", False),
+          (9, 7, 7, 512, 512, "u4", False), (2, 9, 5, 128, 256, "u4", True), (40, 28, 28, 128, 128, "u4", False)]
+
+
+@pytest.mark.parametrize("N,H,W,C,K,ydt,wide", PACKED)
+def test_conv3x3_packed_4bit_with_fragment_weights(hawq, N, H, W, C, K, ydt, wide):
+    import torch
+    from gpu_util import to_dev, assert_same
+    case = wl.conv_case(seed=3 * N + H + W + C + K, N=N, H=H, W=W, C=C, K=K, R=3, S=3, stride=1, pad=1, bits=4)
+    kdim = 9 * C
+    sigma = math.sqrt(kdim * (15 * 15 / 3.0) * (7 * 8 / 3.0)) + 1
+    hi = 15 if ydt == "u4" else 127
+    c0 = int(math.floor(math.log2(1.5 * (1 << 14) / ((hi / 3.0) / sigma))))
+    g = np.random.default_rng(K + kdim)
+    case["c"] = (c0 + g.integers(0, 2, size=K)).astype(np.uint8)
+    case["bias"] = np.rint(sigma * g.uniform(-0.5, 0.5, size=K)).astype(np.int32)
+    case["x"][0, 0, 0, :8] = 0xFF          # nibble extremes: activations 15, weights -1 / -8 / 7 in both halves of a byte
+    case["w"][0, 0, 0, :8] = [0xFF, 0x88, 0x77, 0x8F, 0xF8, 0x78, 0x87, 0x00]
+    case["w_vals"][0, 0, 0, :16] = [-1, -1, -8, -8, 7, 7, -1, -8, -8, -1, -8, 7, 7, -8, 0, 0]
+    if wide:
+        case["b"] = (case["b"].astype(np.int64) << 13).astype(np.int32)
+        case["c"] = (case["c"].astype(np.int32) + 13).astype(np.uint8)
+    y_dt = hawq.U4 if ydt == "u4" else hawq.U8
+    d = hawq.ConvDesc(N=N, H=H, W=W, C=C, K=K, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, x_dtype=hawq.U4, w_dtype=hawq.S4,
+                      y_dtype=y_dt, res_dtype=hawq.U8, relu=1, y_lo=0, y_hi=hi, x_hi=0)
+    w = to_dev(case["w"])
+    nb = hawq.hawq_conv_fragment_weights_bytes(d)
+    assert nb == ((K + 31) // 32) * 32 * 9 * C        # 4-bit weights are expanded to bytes in the copy
+    wf = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda")
+    hawq.hawq_conv_fragment_weights(d, w, wf)
+    torch.cuda.synchronize()
+    # the copy's definition: signed bytes, of every 32 elements the 16 even ones first, then the 16 odd ones
+    wv = case["w_vals"].reshape(K, 9 * C // 32, 16, 2).transpose(0, 1, 3, 2).reshape(K, 9 * C).astype(np.int8)
+    assert np.array_equal(wf.cpu().numpy().reshape(-1), _frag_definition(wv, K, 9 * C).reshape(-1))
+    d.w_fragments = wf.data_ptr()
+    y = torch.full((N, H, W, K // 2 if ydt == "u4" else K), 0x5A, dtype=torch.uint8, device="cuda")
+    hawq.hawq_conv2d_int(d, to_dev(case["x"]), w, to_dev(case["bias"]), to_dev(case["b"]), to_dev(case["c"]), None, None, None, y)
+    torch.cuda.synchronize()
+    want = oracle.conv2d_int(case["x"], case["w"], case["bias"], case["b"], case["c"], N=N, H=H, W=W, C=C, K=K, R=3, S=3, stride=1,
+                             pad=1, x_dt=oracle.U4, w_dt=oracle.S4, y_dt=oracle.U4 if ydt == "u4" else oracle.U8, relu=1, y_lo=0, y_hi=hi)
+    assert_same(y.cpu().numpy(), want)
+    vals = oracle.unpack(want, oracle.U4) if ydt == "u4" else want.reshape(-1)
+    assert 0.05 < np.mean(vals > 0) and np.mean(vals == hi) < 0.5
+
+
 # N, H, W, C, K2, shortcut type, intermediate clamp, wide parameters
 TAIL = [(3, 14, 14, 256, 1024, "u8", 127, False), (2, 28, 28, 128, 512, "u8", 127, False), (1, 9, 11, 128, 256, "s8", 127, False),
         (2, 7, 13, 256, 512, "u8", 15, False), (1, 5, 5, 128, 128, "u8", 127, True), (4, 14, 14, 256, 256, "s8", 127, True),
