@@ -525,18 +525,21 @@ hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s) {
     // twice the workgroups (14x14 256 -> 256 at batch 64: 15.7 -> 11.1 us); with another stream's kernels on the chip the
     // larger workgroups are the better neighbours
     const bool few = !a.corun && tiles(128) * (uint32_t)(a.K1 / 256) < 160;
+    // 128 channels: 448-pixel tiles once they cover most of the chip in one round -- counting the other stream's twin launch
+    // when the forward runs as two half-batches (2 x 112 tiles then share the 256 compute units)
+    const bool wide_tiles = a.M >= 448 * (a.corun ? 80 : 160);
     switch (v) {
     case 1:   // small problems: narrower tiles put more compute units to work
-        if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, true><<<tiles(448), 512, 0, s>>>(a);
+        if (wide_tiles) conv_rp_kernel<2, 4, 2, 7, 28, true><<<tiles(448), 512, 0, s>>>(a);
         else conv_rp_kernel<2, 4, 2, 4, 28, true><<<tiles(256), 512, 0, s>>>(a);
         break;
     case 2: conv_rp_kernel<4, 8, 1, 4, 14, true><<<tiles(128), 512, 0, s>>>(a); break;
     case 3:
         if (a.pk) {
-            if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false, true><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            if (wide_tiles) conv_rp_kernel<2, 4, 2, 7, 28, false, true><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
             else conv_rp_kernel<2, 4, 2, 4, 28, false, true><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
         } else {
-            if (a.M >= 448 * 160) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
+            if (wide_tiles) conv_rp_kernel<2, 4, 2, 7, 28, false><<<tiles(448) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
             else conv_rp_kernel<2, 4, 2, 4, 28, false><<<tiles(256) * (uint32_t)(a.K1 / 128), 512, 0, s>>>(a);
         }
         break;
