@@ -52,19 +52,50 @@ def cpu_baseline(net, images):
     onet.forward(net, x)
     dt = time.perf_counter() - t0
     return dict(value=images / dt, unit="images/s", cores=cores, kind="oracle",
-                sample="%d images of the same network and input distribution, %.1f s" % (images, dt))
+                sample="%d images of the same network and input distribution, %.1f s" % (images, dt),
+                build="gcc " + " ".join(oracle.CFLAGS) + " (plain C loops, OpenMP over output pixels, no intrinsics, no BLAS)")
+
+
+def _profile_text(workload):
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "forward_%s.md" % workload)
+    try:
+        return open(path).read()
+    except OSError:
+        return None
 
 
 def profiled_traffic(workload):
     """HBM bytes one forward moved under rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel
     calibration), read from the committed summary of that profile; None if there is none for this workload."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "forward_%s.md" % workload)
-    try:
-        text = open(path).read()
-    except OSError:
+    text = _profile_text(workload)
+    if text is None:
         return None
     m = re.search(r"all kernels of one forward, scaled by the copy factors: read ([0-9.]+) MB, written ([0-9.]+) MB", text)
     return (float(m.group(1)) + float(m.group(2))) * 1e6 if m else None
+
+
+def profiled_dominant_kernel(workload):
+    """The kernel with the largest share of a forward in the committed rocprofv3 summary (one-stream run, kernel-trace
+    durations and counters): name, launches and microseconds per forward, its HBM and INT8-MFMA rates against the
+    published peaks and which of the two it is nearer to; None if there is no summary for this workload."""
+    text = _profile_text(workload)
+    if text is None or "## Derived per kernel" not in text:
+        return None
+    best = None
+    for line in text.split("## Derived per kernel", 1)[1].splitlines():
+        c = [x.strip() for x in line.strip().strip("|").split("|")]
+        if len(c) != 9 or not c[1].isdigit():
+            continue
+        row = dict(name=c[0].strip("`"), launches_per_forward=int(c[1]), us_per_forward=float(c[2]), hbm_mb=float(c[3]),
+                   hbm_gbs=float(c[4]), frac_hbm_peak=float(c[5]), tops=float(c[6]), frac_int8_mfma_peak=float(c[7]),
+                   mfma_pipe_busy=float(c[8]))
+        if best is None or row["us_per_forward"] > best["us_per_forward"]:
+            best = row
+    if best is not None:
+        best["bound"] = "mfma" if best["frac_int8_mfma_peak"] >= best["frac_hbm_peak"] else "hbm"
+        best["frac"] = max(best["frac_int8_mfma_peak"], best["frac_hbm_peak"])
+        best["source"] = "profiles/forward_%s.md" % workload
+    return best
 
 
 def conv_sweep(hawq, torch, wl, np):
@@ -87,6 +118,11 @@ def conv_sweep(hawq, torch, wl, np):
             wb = torch.empty(nb, dtype=torch.uint8, device="cuda")
             hawq.hawq_conv_block_weights(d, w, wb)
             d.w_blocked = wb.data_ptr()
+        nf = hawq.hawq_conv_fragment_weights_bytes(d)    # ... and in matrix-instruction fragment order (resident-pixel kernel)
+        if nf and R == 3 and stride == 1:
+            wf = torch.empty(nf, dtype=torch.uint8, device="cuda")
+            hawq.hawq_conv_fragment_weights(d, w, wf)
+            d.w_fragments = wf.data_ptr()
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
         for _ in range(5):
             hawq.hawq_conv2d_int(d, x, w, bias, b, c, None, None, None, y)
@@ -163,6 +199,10 @@ def main():
     ap.add_argument("--single-stream", action="store_true",
                     help="run the batch as one part on one stream (the library otherwise runs a batch of 96 or more as two "
                          "halves on two streams); for per-kernel profiles, where overlapping kernels blur the durations")
+    ap.add_argument("--fuse-tails", type=int, default=0,
+                    help="1: run the 3x3 -> 1x1 + shortcut tails of identity bottleneck blocks as one launch wherever the fused "
+                         "kernel applies; 2: only the 256-channel blocks (measurement of hawq_bottleneck_tail_int inside the network; "
+                         "0: the plan's rule)")
     ap.add_argument("--conv-sweep", action="store_true",
                     help="time the single-layer configurations (one 3x3 layer; the ResNet18-shaped INT4 / INT8 sweep) and exit")
     ap.add_argument("--module-ops", action="store_true",
@@ -209,7 +249,9 @@ def main():
             bits = {k: int(v) for k, v in json.load(f).items()}
     net = wl.make_resnet(arch, seed=wk["seed"], bits=bits, int32_shortcut=wk.get("int32_shortcut", False) and not args.bits_json)
     x = torch.from_numpy(wl.make_image_batch(wk["seed"] + 1, N)).cuda()
+    hawq.hawq_tune_set_fusion(args.fuse_tails)
     hn = hawq.HawqNet(arch, net["layers"], net["pool_b"], net["pool_c"])
+    hawq.hawq_tune_set_fusion(0)
     if args.single_stream:
         hawq.hawq_tune_set_split(-1)
     first = hn.split_first(N)
@@ -266,8 +308,9 @@ def main():
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
     roof.update(traffic=profiled_traffic(args.workload),
-                kernel="one forward = %s%d launches (conv_stem_pool, conv3x3_c64, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)"
+                kernel="one forward = %s%d launches (conv_stem_pool, conv3x3_c64, conv_rp, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)"
                        % ("2 x " if first else "", sum(r["mbytes"] > 0 for r in rows)),
+                dominant_kernel=profiled_dominant_kernel(args.workload),
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
                 # the same against what a register-only INT8 MFMA loop sustains on this device, measured now

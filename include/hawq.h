@@ -383,8 +383,9 @@ void hawq_tune_set_tile(int32_t tile);
 void hawq_tune_set_split(int32_t n_first);
 
 /* Measurement hook for the network plan: networks created by later hawq_net_create calls run the 3x3 and the closing 1x1 of
- * an identity-shortcut bottleneck block as one launch (the kernel of hawq_bottleneck_tail_int) wherever it applies (1), or
- * by the plan's own rule (0, default: the rule keeps two launches on the ResNet50 shapes, where one launch measured slower).
+ * an identity-shortcut bottleneck block as one launch (the kernel of hawq_bottleneck_tail_int) wherever it applies (1),
+ * only where the 3x3 has 256 input channels (2), or by the plan's own rule (0, default: the rule keeps two launches on the
+ * ResNet50 shapes, where one launch measured slower).
  * Process-wide state, as hawq_tune_set_tile.  Results are identical for every setting. */
 void hawq_tune_set_fusion(int32_t mode);
 

@@ -240,7 +240,8 @@ def hawq_noalloc_workspace_limit():
 
 
 def hawq_tune_set_fusion(mode):
-    """Measurement hook: 1 = later networks fuse bottleneck tails wherever the kernel applies, 0 = the plan's rule."""
+    """Measurement hook: 1 = later networks fuse bottleneck tails wherever the kernel applies, 2 = only at 256 input
+    channels, 0 = the plan's rule."""
     load_library().hawq_tune_set_fusion(int(mode))
 
 

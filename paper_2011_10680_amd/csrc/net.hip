@@ -622,7 +622,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
             // (resident-pixel 3x3, then the streaming 1x1) 55 / 38 us -- the second convolution's integer epilogue binds, and
             // in the fused kernel it runs at two waves per SIMD on the tiles' compute units only.  The plan therefore keeps
             // two launches unless told otherwise (hawq_tune_set_fusion).
-            const bool want = g_fuse_tails > 0;
+            const bool want = g_fuse_tails == 1 || (g_fuse_tails == 2 && c2.desc.C == 256);
             if (want && c2.w_f && c3.w_f && types && c2.desc.R == 3 && c3.desc.R == 1 && conv_rp_shape_ok(probe, true)) {
                 c2.tail_next = s3;
                 c3.tail_prev = s2;
@@ -919,7 +919,7 @@ static hawq_status run_forward(const hawq_net *net, const void *x, int32_t N, in
 // Set it before sizing the workspace.
 void hawq_tune_set_split(int32_t n_first) { g_split_override = n_first; }
 
-void hawq_tune_set_fusion(int32_t mode) { g_fuse_tails = mode > 0 ? 1 : (mode < 0 ? -1 : 0); }
+void hawq_tune_set_fusion(int32_t mode) { g_fuse_tails = mode; }
 
 hawq_status hawq_forward_resnet(const hawq_net *net, const void *x, int32_t N, int32_t *logits, void *workspace,
                                 size_t workspace_bytes, void *stream) {
