@@ -79,8 +79,12 @@ typedef struct {
                                       (whole cache lines per fetch).  w is still required: other kernels read it. */
     const void *w_fragments;       /* optional (NULL: none): device copy of the same weights made by
                                       hawq_conv_fragment_weights; a 3x3 / stride 1 / pad 1 layer with 128, 256 or 512
-                                      input channels (8-bit or packed 4-bit operands) then runs on the kernel that keeps
-                                      its pixels in LDS and streams these. */
+                                      input channels (8-bit or packed 4-bit operands), or a 1x1 / stride 1 layer with
+                                      512, 1024 or 2048 input channels and K % 256 == 0 (8-bit operands), then runs on
+                                      a kernel that keeps its pixels in LDS and streams these.
+                                      (hawq_conv2d_dual_int ignores the field: that kernel's two-convolution form needs
+                                      a bound on the main branch's values that only hawq_net_create, which sees the
+                                      weights on the host, can establish.) */
 } hawq_conv_desc;
 
 /*

@@ -86,7 +86,7 @@ hawq_status make_conv_args(const hawq_conv_desc *d, const void *x, const void *w
     a.res = (const uint8_t *)residual; a.res_b = residual ? res_b : nullptr; a.res_c = residual ? res_c : nullptr;
     a.y = (uint8_t *)y;
     a.xs = nullptr; a.ws = nullptr; a.bias_s = nullptr; a.b_s = nullptr; a.c_s = nullptr;
-    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.ws_t = nullptr; a.dual16 = 0;
+    a.Hs = a.Ws = a.Cs = 0; a.stride_sh = a.stride_sw = 1; a.xs_dt = HAWQ_U8; a.ws_dt = HAWQ_S8; a.mid_s8 = 0; a.corun = 0; a.ws_t = nullptr; a.ws_f = nullptr; a.dual16 = 0;
     a.w_t = (d->w_blocked != nullptr && ((uintptr_t)d->w_blocked & 15) == 0) ? d->w_blocked : nullptr;
     a.w_f = (d->w_fragments != nullptr && ((uintptr_t)d->w_fragments & 15) == 0) ? d->w_fragments : nullptr;
     a.N = d->N; a.H = d->H; a.W = d->W; a.C = d->C; a.K = d->K; a.R = d->R; a.S = d->S;
@@ -140,6 +140,41 @@ bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *
     return conv_rp_shape_ok(r, true);
 }
 
+// The resident-pixel 1x1 kernel's view of a validated request: one convolution (weights a.w_f) with an optional 8-bit
+// shortcut tensor, or -- a.xs set -- the two-convolution block output (weights a.w_f and a.ws_f) when the caller vouches
+// for the 16-bit form (a.dual16).
+bool make_rp1_args(const ConvArgs &a, int x_hi, int xs_hi, Rp1Args &r) {
+    if (a.R != 1 || a.S != 1 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
+    if (a.w_f == nullptr || a.b == nullptr || a.w_dt != HAWQ_S8) return false;
+    if (a.x_dt == HAWQ_U8 ? x_hi > 127 : a.x_dt != HAWQ_S8) return false;
+    if (a.y_dt != HAWQ_U8 && a.y_dt != HAWQ_S8) return false;
+    if (((uintptr_t)a.x | (uintptr_t)a.y | (uintptr_t)a.w_f) & 15) return false;
+    if ((int64_t)a.M * a.C >= kMaxBytes || (int64_t)a.M * a.K >= kMaxBytes) return false;
+    r = Rp1Args{};
+    r.corun = a.corun;
+    r.x = a.x; r.M = a.M; r.C = a.C;
+    r.wf = (const uint8_t *)a.w_f; r.bias = a.bias; r.b = a.b; r.c = a.c; r.K = a.K; r.lo = a.lo; r.hi = a.hi;
+    r.y = a.y; r.res_dt = HAWQ_U8;
+    if (a.xs == nullptr) {
+        if (a.res != nullptr) {
+            if (a.res_dt != HAWQ_U8 && a.res_dt != HAWQ_S8) return false;
+            if ((uintptr_t)a.res & 15) return false;
+            r.res = a.res; r.res_b = a.res_b; r.res_c = a.res_c; r.res_dt = a.res_dt;
+        }
+        return conv_rp1_shape_ok(r);
+    }
+    if (!a.dual16 || a.ws_f == nullptr || a.res != nullptr || a.b_s == nullptr || a.ws_dt != HAWQ_S8) return false;
+    if (a.xs_dt == HAWQ_U8 ? xs_hi > 127 : a.xs_dt != HAWQ_S8) return false;
+    if (((uintptr_t)a.xs | (uintptr_t)a.ws_f) & 15) return false;
+    if (a.mid_s8 && (a.res_b == nullptr || a.res_c == nullptr)) return false;
+    r.xs = a.xs; r.wsf = (const uint8_t *)a.ws_f; r.bias_s = a.bias_s; r.b_s = a.b_s; r.c_s = a.c_s;
+    r.Cs = a.Cs; r.PQ = a.P * a.Q; r.Q = a.Q; r.Hs = a.Hs; r.Ws = a.Ws; r.sh = a.stride_sh; r.sw = a.stride_sw;
+    r.mid_s8 = a.mid_s8; r.res_b = a.res_b; r.res_c = a.res_c;
+    r.xs_bytes = (int64_t)a.N * a.Hs * a.Ws * a.Cs;
+    if (r.xs_bytes >= kMaxBytes) return false;
+    return conv_rp1_shape_ok(r);
+}
+
 hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     if (a.x_dt == HAWQ_U8 && x_hi > 127 && gemm_splitk_eligible(a)) return launch_gemm_splitk(a, x_hi, s);
@@ -149,6 +184,8 @@ hawq_status dispatch_conv(const ConvArgs &a, int x_hi, hipStream_t s) {
     if (tile_override() == 0 && a.w_f != nullptr) {
         RpArgs r;
         if (make_rp_args(a, x_hi, nullptr, nullptr, r)) return launch_conv_rp(r, false, s);
+        Rp1Args r1;
+        if (make_rp1_args(a, x_hi, 0, r1)) return launch_conv_rp1(r1, s);
     }
     if (conv_mfma_eligible(a, x_hi)) return launch_conv_mfma(a, s);
     return launch_conv_direct(a, s);
@@ -174,7 +211,8 @@ hawq_status make_dual_args(const hawq_conv_desc *d, const void *x, const void *w
     if (t.R != 1 || t.S != 1 || t.pad_h != 0 || t.pad_w != 0) return HAWQ_ERR_SHAPE;
     if (t.N != a.N || t.P != a.P || t.Q != a.Q || t.K != a.K) return HAWQ_ERR_SHAPE;
     a.xs = t.x; a.ws = t.w; a.bias_s = t.bias; a.b_s = t.b; a.c_s = t.c;
-    a.ws_t = t.w_t;      // (the shortcut's blocked weights, if its descriptor names them)
+    a.ws_t = t.w_t;      // (the shortcut's blocked / fragment-ordered weights, if its descriptor names them)
+    a.ws_f = t.w_f;
     a.Hs = t.H; a.Ws = t.W; a.Cs = t.C; a.stride_sh = t.stride_h; a.stride_sw = t.stride_w; a.xs_dt = t.x_dt; a.ws_dt = t.w_dt;
     return HAWQ_OK;
 }
@@ -182,6 +220,10 @@ hawq_status make_dual_args(const hawq_conv_desc *d, const void *x, const void *w
 hawq_status dispatch_conv_dual(const ConvArgs &a, int x_hi, int xs_hi, hipStream_t s) {
     if (a.M == 0) return HAWQ_OK;
     if (conv_pws_dual_eligible(a, x_hi, xs_hi)) return launch_conv_pws_dual(a, s);
+    if (tile_override() == 0 && a.w_f != nullptr && a.ws_f != nullptr) {
+        Rp1Args r1;
+        if (make_rp1_args(a, x_hi, xs_hi, r1)) return launch_conv_rp1(r1, s);
+    }
     if (conv_mfma_dual_eligible(a, x_hi, xs_hi)) return launch_conv_mfma_dual(a, s);
     return launch_conv_direct(a, s);
 }

@@ -45,6 +45,8 @@ struct ConvArgs {
     const void *w_t, *ws_t;
     // w_f (optional): the weights in MFMA fragment order for the resident-pixel 3x3 kernel (launch_fragment_weights)
     const void *w_f;
+    // ws_f (optional): the shortcut convolution's weights in the same fragment order (two-convolution form of conv_rp1.hip)
+    const void *ws_f;
     // corun: kernels of another stream share the chip with this launch (the forward's two half-batches): configurations
     // meant for a launch that is alone (small tiles with a deep LDS ring when there are few tiles) are not chosen
     int32_t corun;
@@ -80,6 +82,32 @@ struct RpArgs {
 #ifdef HAWQ_RP_TIMING
     long long *timing;       // measurement build only: [workgroup][wave][6] cycle stamps
 #endif
+};
+
+// Arguments of the resident-pixel 1x1 kernel (conv_rp1.hip): one convolution with an optional shortcut tensor, or a block
+// output with a convolution on both branches (xs != nullptr).
+struct Rp1Args {
+    const uint8_t *x;        // main operand [M][C], 8-bit (signed operand range)
+    int32_t M, C;
+    const uint8_t *wf;       // [K][C] weights in MFMA fragment order (launch_fragment_weights)
+    const int32_t *bias, *b;
+    const uint8_t *c;
+    int32_t K, lo, hi;       // clamp with ReLU folded in
+    const uint8_t *res;      // shortcut tensor [M][K] 8-bit or nullptr (one-convolution form only)
+    const int32_t *res_b;    // its rescale -- or, two-convolution form with mid_s8, the stored shortcut's
+    const uint8_t *res_c;
+    int32_t res_dt;          // HAWQ_U8 | HAWQ_S8
+    uint8_t *y;              // [M][K] 8-bit
+    // shortcut convolution: 1x1, unpadded, strides (sh, sw) over [N][Hs][Ws][Cs]; output pixel m = (n P + p) Q + q
+    const uint8_t *xs;
+    const uint8_t *wsf;      // [K][Cs] weights in fragment order
+    const int32_t *bias_s, *b_s;
+    const uint8_t *c_s;
+    int32_t Cs, PQ, Q, Hs, Ws, sh, sw;
+    int32_t mid_s8;          // see ConvArgs::mid_s8
+    int64_t xs_bytes;        // bytes of the xs tensor
+    int32_t corun;           // see ConvArgs::corun
+    int32_t npass;           // set by the launcher: groups of 256 output channels a workgroup walks
 };
 
 __host__ __device__ inline bool is4(int dt) { return dt == HAWQ_U4 || dt == HAWQ_S4; }
@@ -204,6 +232,11 @@ bool conv_rp_shape_ok(const RpArgs &a, bool fused);
 // RpArgs from a validated 3x3 layer (and, fused, the 1x1 layer that follows it); false if types, alignment or shape do not fit
 bool make_rp_args(const ConvArgs &a1, int x_hi, const ConvArgs *a2, const void *w2f, RpArgs &r);
 hawq_status launch_conv_rp(const RpArgs &a, bool fused, hipStream_t s);
+// resident-pixel 1x1 kernel (one convolution + optional shortcut tensor, or two convolutions when a.xs is set and the
+// caller vouches for a.dual16): Rp1Args from validated requests; false if types, alignment or shape do not fit
+bool conv_rp1_shape_ok(const Rp1Args &a);
+bool make_rp1_args(const ConvArgs &a, int x_hi, int xs_hi, Rp1Args &r);
+hawq_status launch_conv_rp1(const Rp1Args &a, hipStream_t s);
 // [K][row bytes] weights -> MFMA fragment order for that kernel (four: packed 4-bit rows, expanded to bytes on the way);
 // out: ceil(K/32) * 32 * (bytes of an expanded row)
 hawq_status launch_fragment_weights(const void *w, void *w_frag, int K, int64_t row, bool four, hipStream_t s);

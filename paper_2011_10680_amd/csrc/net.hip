@@ -100,6 +100,7 @@ struct Step {
     hawq_conv_desc desc_s{};      // STEP_CONV_DUAL: the transition convolution (reads tensor `res`)
     const uint8_t *w_s = nullptr;             // ... its parameters
     const uint8_t *w_t = nullptr, *w_s_t = nullptr;   // the weights (and the shortcut's) in the implicit-GEMM kernel's blocked order
+    const uint8_t *w_s_f = nullptr;                   // the shortcut's in fragment order
     bool dual16 = false;   // two-convolution launches (STEP_CONV_DUAL, fused pairs): the main branch's rescaled term provably fits 16 bits
     const int32_t *bias_s = nullptr, *b_s = nullptr;
     const uint8_t *c_s = nullptr;
@@ -348,9 +349,11 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
     auto rp3x3 = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && is8(i) && (L[i].C == 128 || L[i].C == 256 || (L[i].C == 512 && L[i].W <= 14)) && L[i].K % L[i].C == 0; };
     // ... and the same layers with packed 4-bit operands (the kernel's packed form)
     auto rp3x3pk = [&](int i) { return L[i].R == 3 && L[i].S == 3 && L[i].stride == 1 && L[i].pad == 1 && !is8(i) && L[i].W <= 28 && (L[i].C == 128 || L[i].C == 256 || (L[i].C == 512 && L[i].W <= 14)) && L[i].K % L[i].C == 0; };
+    // ... and the 1x1 layers of the resident-pixel 1x1 kernel (main branches and transition convolutions alike)
+    auto rp1x1 = [&](int i) { return L[i].R == 1 && L[i].S == 1 && L[i].pad == 0 && is8(i) && L[i].K % 256 == 0 && (L[i].C == 256 || L[i].C == 512 || L[i].C == 1024 || L[i].C == 2048); };
     auto fragmented = [&](int i) {
         if (L[i].is_stem || L[i].is_fc) return false;
-        if (rp3x3(i) || rp3x3pk(i)) return true;
+        if (rp3x3(i) || rp3x3pk(i) || rp1x1(i)) return true;
         return i > 0 && L[i].R == 1 && L[i].has_residual && is8(i) && rp3x3(i - 1) && L[i - 1].block == L[i].block && L[i].C == L[i - 1].K;
     };
     std::vector<Off> off(nl);
@@ -576,6 +579,7 @@ hawq_status hawq_net_create(int32_t arch, int32_t image_hw, int32_t num_classes,
                 d.x_dtype = block_in_dt; d.w_dtype = HAWQ_S8; d.x_hi = act_hi(in_bits);   // (8-bit form: block_in_dt is HAWQ_U8)
                 st.w_s = A + off[ds].w; st.bias_s = (const int32_t *)(A + off[ds].bias);
                 st.w_s_t = blocked(ds) ? A + off[ds].wt : nullptr;
+                st.w_s_f = fragmented(ds) ? A + off[ds].wf : nullptr;
                 st.dual16 = fits16(last, ds, u_bits, false);
                 st.b_s = (const int32_t *)(A + off[ds].b); st.c_s = A + off[ds].c;
                 st.macs_per_image += (double)L[ds].P * L[ds].Q * L[ds].K * L[ds].C;
@@ -782,6 +786,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
             a.mid_s8 = 1; a.res_b = l.res_b; a.res_c = l.res_c;
             a.corun = n_parts > 1;
             a.w_t = l.w_t; a.ws_t = d.w_t;
+            a.w_f = l.w_f; a.ws_f = d.w_f;
             a.dual16 = l.dual16;
             if (st.pair_last >= 0) {
                 if (pair_runs_fused(net, N, (int)s) && (conv_pws_dual_eligible(a, x_hi, xs_hi) || conv_mfma_dual_eligible(a, x_hi, xs_hi))) {
@@ -863,6 +868,7 @@ static hawq_status run_parts(const hawq_net *net, Part *parts, int n_parts, hipE
                                 true, a, x_hi, xs_hi);
             a.corun = n_parts > 1;
             a.w_t = st.w_t; a.ws_t = st.w_s_t;
+            a.w_f = st.w_f; a.ws_f = st.w_s_f;
             a.dual16 = st.dual16;
             if (rc == HAWQ_OK) rc = dispatch_conv_dual(a, x_hi, xs_hi, stream);
             break;
