@@ -74,7 +74,9 @@ def test_fragment_weights_copy_is_the_documented_order(hawq, K, R, C):
 PLAIN = [(3, 14, 14, 256, 256, None, False), (2, 28, 28, 128, 128, None, False), (1, 13, 11, 256, 512, "u8", False),
          (2, 9, 28, 128, 256, "s8", False), (1, 5, 3, 128, 128, "u8", True), (5, 7, 7, 256, 256, None, True),
          (1, 1, 1, 128, 128, None, False), (1, 2, 300, 128, 128, None, False),   # last: wider than the kernel's patch -> other kernel
-         (9, 7, 7, 512, 512, None, False), (3, 7, 7, 512, 512, "u8", False), (2, 5, 14, 512, 256, "s8", True)]
+         (9, 7, 7, 512, 512, None, False), (3, 7, 7, 512, 512, "u8", False), (2, 5, 14, 512, 256, "s8", True),
+         # 128 channels reach this kernel from forty 256-pixel tiles on (fewer: the tiled kernel, as the small cases above)
+         (14, 28, 28, 128, 128, None, False), (14, 28, 28, 128, 256, "s8", False), (15, 27, 26, 128, 128, "u8", True)]
 
 
 @pytest.mark.parametrize("N,H,W,C,K,res,wide", PLAIN)
