@@ -199,6 +199,8 @@ def main():
     ap.add_argument("--single-stream", action="store_true",
                     help="run the batch as one part on one stream (the library otherwise runs a batch of 96 or more as two "
                          "halves on two streams); for per-kernel profiles, where overlapping kernels blur the durations")
+    ap.add_argument("--split", type=int, default=0,
+                    help="run the batch as two parts on two streams with this many images in the first part (0: the library's rule)")
     ap.add_argument("--fuse-tails", type=int, default=0,
                     help="1: run the 3x3 -> 1x1 + shortcut tails of identity bottleneck blocks as one launch wherever the fused "
                          "kernel applies; 2: only the 256-channel blocks (measurement of hawq_bottleneck_tail_int inside the network; "
@@ -254,6 +256,8 @@ def main():
     hawq.hawq_tune_set_fusion(0)
     if args.single_stream:
         hawq.hawq_tune_set_split(-1)
+    elif args.split > 0:
+        hawq.hawq_tune_set_split(args.split)
     first = hn.split_first(N)
     ws = torch.empty(hn.workspace_bytes(N), dtype=torch.uint8, device="cuda")
     logits = torch.empty((N, 1000), dtype=torch.int32, device="cuda")
