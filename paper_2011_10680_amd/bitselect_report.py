@@ -60,7 +60,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--arch", type=int, default=50)
     ap.add_argument("--batch", type=int, default=128)
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "bitselect"))
+    ap.add_argument("--out", default=os.path.join(ROOT, "bitselect_out"))
     args = ap.parse_args()
     import torch
     import paper_2011_10680_amd as hawq

@@ -365,11 +365,7 @@ conv_rp_kernel(const RpArgs a) {
 #pragma unroll
                     for (int tp = 0; tp < TP; ++tp) bf[hn % 2][tp] = *(const v4i *)(tile + base[tp] + tn * 64 + kn * 32);
                 }
-#ifndef HAWQ_RP_ABL_NO_P2_MFMA
                 mfma_row(std::integral_constant<int, h % 2>{}, ag[t][kk]);
-#else
-                asm volatile("" :: "v"(ag[t][kk]), "v"(bf[h % 2][0]), "v"(bf[h % 2][TP - 1]));
-#endif
                 if constexpr (kk == 1) {   // the same K-step of the next pass
                     if (pass + 1 < npass2) {
                         ag[t][0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, lane16, woff, 0);
