@@ -105,6 +105,44 @@ def test_blocked_weight_copy_size_and_validation_on_host(lib):
     assert lib.hawq_conv_block_weights(ctypes.byref(d), ctypes.c_void_p(4100), P, None) == 6
 
 
+def test_fragment_weight_copy_and_fused_tail_validate_on_host(lib):
+    """Size of the fragment-ordered copy (whole groups of 32 channels, bytes also for 4-bit weights) and the cases with
+    none; the copy call and the fused bottleneck tail fail before any launch on null pointers, misaligned pointers and
+    layer pairs the kernel does not take."""
+    import paper_2011_10680_amd as hawq
+    size = lambda **kw: lib.hawq_conv_fragment_weights_bytes(ctypes.byref(_desc(**kw)))
+    assert size(C=128, K=128) == 128 * 9 * 128
+    assert size(C=256, K=100, R=1, S=1, pad_h=0, pad_w=0) == 128 * 256
+    assert size(C=128, K=33, x_dtype=hawq.U4, w_dtype=hawq.S4) == 64 * 9 * 128     # expanded to one byte per weight
+    assert size(C=96) == 0 and size(C=128, w_dtype=hawq.U8) == 0
+    assert lib.hawq_conv_fragment_weights_bytes(None) == 0
+    P = ctypes.c_void_p(4096)
+    d = _desc(C=128, K=128)
+    assert lib.hawq_conv_fragment_weights(ctypes.byref(d), None, P, None) == 1
+    assert lib.hawq_conv_fragment_weights(ctypes.byref(d), P, None, None) == 1
+    assert lib.hawq_conv_fragment_weights(None, P, P, None) == 1
+    assert lib.hawq_conv_fragment_weights(ctypes.byref(_desc(C=96)), P, P, None) == 6
+    assert lib.hawq_conv_fragment_weights(ctypes.byref(d), P, ctypes.c_void_p(4104), None) == 6
+    d2 = _desc(N=2, H=14, W=14, C=256, K=256)
+    d3 = _desc(N=2, H=14, W=14, C=256, K=1024, R=1, S=1, pad_h=0, pad_w=0)
+    tail = lambda a, b, x=P, w2=P, b2=P, w3=P, b3=P, res=P, y=P: lib.hawq_bottleneck_tail_int(
+        ctypes.byref(a), x, w2, P, b2, P, ctypes.byref(b), w3, P, b3, P, res, P, P, y, None)
+    assert tail(d2, d3, w2=None) == 1 and tail(d2, d3, w3=None) == 1 and tail(d2, d3, res=None) == 1 and tail(d2, d3, b3=None) == 1
+    assert tail(d2, d3, x=None) == 1 and tail(d2, d3, y=None) == 1
+    assert tail(_desc(N=2, H=14, W=14, C=256, K=256, y_lo=5, y_hi=3), d3) == 4
+    assert tail(d2, _desc(N=2, H=14, W=14, C=256, K=1024, R=1, S=1, pad_h=0, pad_w=0, y_dtype=9)) == 3
+    for bad2, bad3 in ((_desc(N=2, H=14, W=14, C=256, K=256, stride_h=2, stride_w=2), d3),          # strided 3x3
+                       (_desc(N=2, H=14, W=14, C=192, K=192), _desc(N=2, H=14, W=14, C=192, K=768, R=1, S=1, pad_h=0, pad_w=0)),
+                       (d2, _desc(N=2, H=14, W=14, C=128, K=1024, R=1, S=1, pad_h=0, pad_w=0)),         # channel counts do not chain
+                       (d2, _desc(N=2, H=7, W=7, C=256, K=1024, R=1, S=1, pad_h=0, pad_w=0)),           # other image
+                       (d2, _desc(N=2, H=14, W=14, C=256, K=1024, R=1, S=1, pad_h=0, pad_w=0, y_dtype=hawq.U4, y_hi=15)),
+                       (_desc(N=2, H=14, W=14, C=256, K=256, x_dtype=hawq.U4, w_dtype=hawq.S4, x_hi=0), d3)):
+        assert tail(bad2, bad3) == 6
+    assert tail(d2, d3, w2=ctypes.c_void_p(4100)) == 6
+    assert lib.hawq_noalloc_workspace_limit() == 64 << 20
+    assert lib.hawq_forward_resnet_noalloc(None, P, 1, P, None) == 1
+
+
 def test_dual_conv_argument_validation_on_host(lib):
     import paper_2011_10680_amd as hawq
     P = ctypes.c_void_p(4096)
