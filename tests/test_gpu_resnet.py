@@ -82,6 +82,30 @@ def test_fused_stem_with_wide_parameters_and_odd_sizes(hawq, image_hw, N):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("image_hw,N,ties", [(64, 2, True), (36, 3, True), (64, 2, False)])
+def test_fused_stem_pools_before_it_requantises(hawq, image_hw, N, ties):
+    """The fused conv1 + max pool kernel takes the window maximum of the INT32 accumulators and requantises once (the
+    requantisation never decreases in the accumulator).  Cases where that order could show: channels with multiplier 0
+    (every output is rq(., 0, c) = 0), channels whose accumulators are all far below zero (ReLU clamps the maximum), channels
+    with the largest admissible multiplier and shift 1, and a bias that puts the maxima right at rounding boundaries."""
+    net = wl.make_resnet(18, seed=78, image_hw=image_hw)
+    x = wl.make_image_batch(10, N, image_hw=image_hw)
+    conv1 = net["layers"][0]
+    conv1["b"] = conv1["b"].copy(); conv1["c"] = conv1["c"].copy(); conv1["bias"] = conv1["bias"].copy()
+    conv1["b"][0:8] = 0
+    conv1["bias"][8:16] = -(1 << 28)
+    conv1["bias"][16:24] = (1 << 28)
+    conv1["b"][24:28] = (1 << 30) - 1; conv1["c"][24:28] = 31         # just below one half per accumulator step
+    if ties:   # one half per accumulator step: every odd value is a tie (outside the narrow evaluation: the exact 64-bit form)
+        conv1["b"][28:32] = 1; conv1["c"][28:32] = 1
+    want = onet.forward(net, x)
+    got, _ = _forward_gpu(hawq, net, x, False)
+    assert np.array_equal(got, want)
+    # the same through the unfused kernels (kept activations): conv1's tensor, the pooled tensor, logits
+    got_keep, _ = _forward_gpu(hawq, net, x, True)
+    assert np.array_equal(got_keep, want)
+
+
 @pytest.mark.parametrize("arch,batch,mixed,seed,int32_sc", [(18, 64, False, 1002, True), (50, 128, False, 1003, True), (50, 256, True, 1004, False),
                                                             (18, 64, False, 1002, False), (50, 128, False, 1003, False)])
 def test_full_size_configs_whole_batch_against_oracle(hawq, arch, batch, mixed, seed, int32_sc):
