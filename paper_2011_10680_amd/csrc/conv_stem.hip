@@ -151,7 +151,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) c
 constexpr int FUSE_PT = 8;                         // pooled tile edge
 constexpr int FUSE_CT = 2 * FUSE_PT + 1;           // 17 conv rows / columns under it
 constexpr int FUSE_ROWS = 2 * FUSE_CT + 5;         // 39 input rows
-constexpr int FUSE_COLS = 44;                      // patch width in pixels (40 used; origin = image column 4*pq0 - 5)
+// patch width in pixels (41 used; origin = image column 4*pq0 - 5).  42: the 32 lanes of one pass of a fragment read touch
+// three conv1 rows (two patch rows apart) x 18 consecutive dwords each; 2 x 42 = 20 (mod 64 banks) lays the three spans side
+// by side, where 44 wrapped the third onto the first (every pass a two-way conflict: half of all LDS cycles)
+constexpr int FUSE_COLS = 42;
 constexpr int FUSE_GROUPS = 11;                    // 4-pixel groups fetched per patch row (patch columns -3 .. 40)
 
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
