@@ -98,6 +98,19 @@ def profiled_dominant_kernel(workload):
     return best
 
 
+def dominant_kernel_layers(workload, kernel):
+    """Names of the layers that the committed launch-by-launch summary (profiles/per_layer_<workload>.md) shows on `kernel`."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "per_layer_%s.md" % workload)
+    if not os.path.exists(path):
+        return []
+    names = []
+    for line in open(path):
+        c = [x.strip() for x in line.strip().strip("|").split("|")]
+        if len(c) >= 5 and c[0].isdigit() and c[3].strip("`") == kernel:
+            names.append(c[1])
+    return names
+
+
 def conv_sweep(hawq, torch, wl, np):
     """Single-layer configurations: the 56x56x64 3x3 layer (batch 1 as specified, batch 128 as a throughput companion) and
     the ResNet18-shaped 3x3 / strided / 1x1 sweep in INT4 and in INT8 (batch 8 as specified, and batch 128), seeded inputs
@@ -311,10 +324,21 @@ def main():
         roof = dict(bound="hbm", achieved=achieved_gbs, peak=PEAK_HBM_GBS, unit="GB/s", frac=achieved_gbs / PEAK_HBM_GBS)
     else:
         roof = dict(bound="mfma", achieved=achieved_tops, peak=PEAK_INT8_TOPS, unit="TOP/s", frac=achieved_tops / PEAK_INT8_TOPS)
+    # the profile's dominant kernel, cross-checked live: this run's per-launch event times (one stream; each interval holds
+    # a few microseconds of launch and event overhead) of the layers the committed launch-by-launch summary shows on it
+    dom = profiled_dominant_kernel(args.workload)
+    if dom is not None and not args.bits_json:
+        layers = set(dominant_kernel_layers(args.workload, dom["name"]))
+        live = [r for r in rows if r["name"] in layers]
+        if live and len(live) == dom["launches_per_forward"]:
+            live_us = sum(r["ms"] for r in live) * 1e3
+            dom["live_event_us_per_forward"] = live_us
+            dom["live_tops"] = 2 * sum(r["gmac"] for r in live) * 1e9 / (live_us * 1e-6) / 1e12
+            dom["live_frac_int8_mfma_peak"] = dom["live_tops"] / PEAK_INT8_TOPS
     roof.update(traffic=profiled_traffic(args.workload),
                 kernel="one forward = %s%d launches (conv_stem_pool, conv3x3_c64, conv_rp, conv_mfma, conv_pw, conv_pws, conv_pws_dual, avgpool)"
                        % ("2 x " if first else "", sum(r["mbytes"] > 0 for r in rows)),
-                dominant_kernel=profiled_dominant_kernel(args.workload),
+                dominant_kernel=dom,
                 launch_ms=ev_ms_per_step, algorithmic_bytes=total_bytes, t_hbm_ms=t_mem * 1e3, t_mfma_ms=t_mfma * 1e3,
                 mfma_tops=achieved_tops, mfma_frac=achieved_tops / PEAK_INT8_TOPS,
                 # the same against what a register-only INT8 MFMA loop sustains on this device, measured now
